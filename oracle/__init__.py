@@ -1,0 +1,181 @@
+"""CPU oracle for the multi-replica compression step Y_p = Comp(X, U_p, V_p, W_p).
+
+TEST INFRASTRUCTURE ONLY.  The test-suite, the smoke check and the benchmark's
+cpu_baseline leg may import this package; the product (the HIP library and its
+Python binding) never does, and this package never imports the product.
+
+Every function is a numpy-facing wrapper over oracle/exat_oracle.c (plain C,
+fp64 accumulation), plus two pure-numpy cross-checks used only by the pins.
+
+Conventions (paper Sec. 3, Eq. 3 and Sec. 4.1):
+  X   float32 array of shape (I, J, K), Fortran (column-major) order
+  U   float32 (L, I), V (M, J), W (N, K), C order (reduction index contiguous)
+  Y   float64 (L, M, N), Fortran order
+Stacked operands hold replica p in rows p*L .. p*L+L-1.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+from .build import build as _build
+
+_lib = None
+_i64 = ctypes.c_int64
+_fp = ctypes.POINTER(ctypes.c_float)
+_dp = ctypes.POINTER(ctypes.c_double)
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        _lib = ctypes.CDLL(_build())
+        _lib.orc_noise.restype = ctypes.c_double
+        _lib.orc_noise.argtypes = [ctypes.c_uint64, _i64, _i64, _i64]
+        _lib.orc_noise_word.restype = ctypes.c_uint32
+        _lib.orc_noise_word.argtypes = [ctypes.c_uint64, _i64, _i64, _i64]
+        _lib.orc_round_bf16.restype = ctypes.c_float
+        _lib.orc_round_bf16.argtypes = [ctypes.c_float]
+        _lib.orc_comp.restype = ctypes.c_int
+        _lib.orc_closed_form.restype = ctypes.c_int
+    return _lib
+
+
+def _f32c(a):
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    return a, a.ctypes.data_as(_fp)
+
+
+def _x_f(X):
+    X = np.asarray(X)
+    if X.dtype != np.float32 or X.ndim != 3:
+        raise ValueError("X must be a float32 array of shape (I, J, K)")
+    return np.asfortranarray(X)
+
+
+def comp_brute(X, U, V, W):
+    """Eq. 3 as six nested loops (tiny sizes only)."""
+    X = _x_f(X)
+    I, J, K = X.shape
+    U, pU = _f32c(U); V, pV = _f32c(V); W, pW = _f32c(W)
+    L, M, N = U.shape[0], V.shape[0], W.shape[0]
+    assert U.shape[1] == I and V.shape[1] == J and W.shape[1] == K
+    Y = np.zeros((L, M, N), dtype=np.float64, order="F")
+    lib().orc_comp_brute(X.ctypes.data_as(_fp), _i64(I), _i64(J), _i64(K),
+                         pU, _i64(I), _i64(L), pV, _i64(J), _i64(M), pW, _i64(K), _i64(N),
+                         Y.ctypes.data_as(_dp))
+    return Y
+
+
+def comp(X, U, V, W, order=(0, 1, 2)):
+    """Comp(X,U,V,W) mode by mode (Sec. 4.3), in the given mode order (0-based)."""
+    X = _x_f(X)
+    I, J, K = X.shape
+    U, pU = _f32c(U); V, pV = _f32c(V); W, pW = _f32c(W)
+    L, M, N = U.shape[0], V.shape[0], W.shape[0]
+    assert U.shape[1] == I and V.shape[1] == J and W.shape[1] == K
+    assert sorted(order) == [0, 1, 2]
+    Y = np.zeros((L, M, N), dtype=np.float64, order="F")
+    o = (ctypes.c_int * 3)(*order)
+    rc = lib().orc_comp(X.ctypes.data_as(_fp), _i64(I), _i64(J), _i64(K),
+                        pU, _i64(I), _i64(L), pV, _i64(J), _i64(M), pW, _i64(K), _i64(N),
+                        o, Y.ctypes.data_as(_dp))
+    if rc != 0:
+        raise MemoryError("oracle: out of memory")
+    return Y
+
+
+def comp_multi(X, Us, Vs, Ws, P, replicas=None):
+    """All (or the listed) replicas, one at a time.  Us is (P*L, I) etc.
+    Returns float64 (L, M, N, len(replicas)) in Fortran order: the layout
+    Y[l + L*(m + M*(n + N*p))] of the library's output."""
+    L, M, N = Us.shape[0] // P, Vs.shape[0] // P, Ws.shape[0] // P
+    reps = list(range(P)) if replicas is None else list(replicas)
+    Y = np.zeros((L, M, N, len(reps)), dtype=np.float64, order="F")
+    for t, p in enumerate(reps):
+        Y[:, :, :, t] = comp(X, Us[p * L:(p + 1) * L], Vs[p * M:(p + 1) * M], Ws[p * N:(p + 1) * N])
+    return Y
+
+
+def comp_box(Xbox, Us, Vs, Ws, P, box, replicas=None):
+    """Contribution of the sub-box box=(i0,i1,j0,j1,k0,k1) of X (Sec. 4.3: a block is
+    compressed with the matching column slices of U, V, W)."""
+    i0, i1, j0, j1, k0, k1 = box
+    return comp_multi(Xbox, Us[:, i0:i1], Vs[:, j0:j1], Ws[:, k0:k1], P, replicas)
+
+
+def closed_form(A, B, C, U, V, W):
+    """Comp of the exactly rank-R tensor [[A,B,C]]: sum_r (U a_r) o (V b_r) o (W c_r)."""
+    A = np.asfortranarray(A, dtype=np.float32); B = np.asfortranarray(B, dtype=np.float32)
+    C = np.asfortranarray(C, dtype=np.float32)
+    I, R = A.shape; J = B.shape[0]; K = C.shape[0]
+    U, pU = _f32c(U); V, pV = _f32c(V); W, pW = _f32c(W)
+    L, M, N = U.shape[0], V.shape[0], W.shape[0]
+    Y = np.zeros((L, M, N), dtype=np.float64, order="F")
+    rc = lib().orc_closed_form(A.ctypes.data_as(_fp), B.ctypes.data_as(_fp), C.ctypes.data_as(_fp),
+                               _i64(I), _i64(J), _i64(K), _i64(R),
+                               pU, _i64(I), _i64(L), pV, _i64(J), _i64(M), pW, _i64(K), _i64(N),
+                               Y.ctypes.data_as(_dp))
+    if rc != 0:
+        raise MemoryError("oracle: out of memory")
+    return Y
+
+
+def closed_form_multi(A, B, C, Us, Vs, Ws, P, replicas=None):
+    L, M, N = Us.shape[0] // P, Vs.shape[0] // P, Ws.shape[0] // P
+    reps = list(range(P)) if replicas is None else list(replicas)
+    Y = np.zeros((L, M, N, len(reps)), dtype=np.float64, order="F")
+    for t, p in enumerate(reps):
+        Y[:, :, :, t] = closed_form(A, B, C, Us[p * L:(p + 1) * L], Vs[p * M:(p + 1) * M],
+                                    Ws[p * N:(p + 1) * N])
+    return Y
+
+
+def noise(seed, i, j, k):
+    """g(seed; i,j,k): one standard-normal draw (see exat_oracle.c for the definition)."""
+    return float(lib().orc_noise(ctypes.c_uint64(seed), _i64(i), _i64(j), _i64(k)))
+
+
+def noise_word(seed, i, j, k):
+    return int(lib().orc_noise_word(ctypes.c_uint64(seed), _i64(i), _i64(j), _i64(k)))
+
+
+def noise_box(seed, box):
+    i0, i1, j0, j1, k0, k1 = box
+    out = np.zeros((i1 - i0, j1 - j0, k1 - k0), dtype=np.float64, order="F")
+    lib().orc_noise_box(ctypes.c_uint64(seed), _i64(i0), _i64(i1), _i64(j0), _i64(j1), _i64(k0), _i64(k1),
+                        out.ctypes.data_as(_dp))
+    return out
+
+
+def round_bf16(a):
+    """Round-to-nearest-even to bf16, returned as float32."""
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    out = np.empty_like(a)
+    lib().orc_round_bf16_array(a.ctypes.data_as(_fp), out.ctypes.data_as(_fp), _i64(a.size))
+    return out
+
+
+def gen_box(A, B, C, seed, sigma, box=None, to_bf16=False):
+    """X = fl32([[A,B,C]] + sigma*g) on a box (default: everything), float32 Fortran order."""
+    A = np.asfortranarray(A, dtype=np.float32); B = np.asfortranarray(B, dtype=np.float32)
+    C = np.asfortranarray(C, dtype=np.float32)
+    I, R = A.shape; J = B.shape[0]; K = C.shape[0]
+    if box is None:
+        box = (0, I, 0, J, 0, K)
+    i0, i1, j0, j1, k0, k1 = box
+    out = np.zeros((i1 - i0, j1 - j0, k1 - k0), dtype=np.float32, order="F")
+    lib().orc_gen_box(A.ctypes.data_as(_fp), B.ctypes.data_as(_fp), C.ctypes.data_as(_fp),
+                      _i64(I), _i64(J), _i64(K), _i64(R), ctypes.c_uint64(seed), ctypes.c_double(sigma),
+                      _i64(i0), _i64(i1), _i64(j0), _i64(j1), _i64(k0), _i64(k1),
+                      ctypes.c_int(1 if to_bf16 else 0), out.ctypes.data_as(_fp))
+    return out
+
+
+def rel_fro(Y, Yref):
+    """Per-replica relative Frobenius error max_p ||Y_p - Yref_p||_F / ||Yref_p||_F
+    for arrays of shape (L, M, N, P)."""
+    Y = np.asarray(Y, dtype=np.float64); Yref = np.asarray(Yref, dtype=np.float64)
+    num = np.sqrt(((Y - Yref) ** 2).sum(axis=(0, 1, 2)))
+    den = np.sqrt((Yref ** 2).sum(axis=(0, 1, 2)))
+    return float((num / den).max())

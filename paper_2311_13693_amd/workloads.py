@@ -1,0 +1,99 @@
+"""Seeded synthetic inputs shaped like the paper's dense experiments (Sec. 5.1).
+
+This module only draws random input matrices and names problem sizes.  It
+contains none of the method's arithmetic (no compression, no tensor
+generation, no noise function): both the HIP library's tests/benchmark and the
+CPU oracle's tests take their inputs from here.
+
+The paper's dense workload: I=J=K, Gaussian CP factor matrices A,B,C (I x R),
+Gaussian compression matrices U_p (L x I), V_p (M x J), W_p (N x K), cubic
+blocks of edge d.  The five benchmark configurations add sigma=0.01 noise and
+fix R, P, L and d as listed in CONFIGS.
+"""
+from dataclasses import dataclass, replace
+
+import numpy as np
+
+BASE_SEED = 0x231113693000
+
+
+@dataclass(frozen=True)
+class Config:
+    name: str
+    I: int
+    J: int
+    K: int
+    R: int
+    P: int
+    L: int
+    M: int
+    N: int
+    dI: int
+    dJ: int
+    dK: int
+    dtype: str           # "f32" or "bf16": type of the X tile and of U,V,W as the kernels consume them
+    materialised: bool   # X resident in HBM (True) or generated tile by tile inside the kernel (False)
+    sigma: float = 0.01
+    index: int = 0
+
+    @property
+    def seed(self) -> int:
+        return BASE_SEED + self.index
+
+    @property
+    def elements(self) -> int:
+        return self.I * self.J * self.K
+
+    @property
+    def flops(self) -> int:
+        """Algorithmic flops of the three-mode chain, each mode once at full extent."""
+        PL = self.P * self.L
+        return 2 * PL * (self.I * self.J * self.K + self.M * self.J * self.K + self.M * self.N * self.K)
+
+
+def _cube(name, index, n, R, P, L, d, dtype, materialised):
+    return Config(name, n, n, n, R, P, L, L, L, d, d, d, dtype, materialised, 0.01, index)
+
+
+CONFIGS = {
+    "cfg1": _cube("cfg1", 0, 128, 8, 4, 16, 128, "f32", True),
+    "cfg2": _cube("cfg2", 1, 512, 16, 16, 32, 128, "f32", True),
+    "cfg3": _cube("cfg3", 2, 1024, 32, 32, 64, 256, "f32", True),
+    "cfg4": _cube("cfg4", 3, 4096, 64, 64, 64, 256, "f32", False),
+    "cfg5": _cube("cfg5", 4, 10000, 32, 48, 50, 250, "bf16", False),
+    # scaled-down twins of the two generated configurations (same awkward sizes, oracle-sized)
+    "cfg4_twin": _cube("cfg4_twin", 5, 512, 64, 64, 64, 256, "f32", False),
+    "cfg5_twin": _cube("cfg5_twin", 6, 500, 32, 48, 50, 250, "bf16", False),
+}
+
+
+def with_sigma(cfg: Config, sigma: float) -> Config:
+    return replace(cfg, sigma=sigma)
+
+
+def _normal(seed, stream, shape, std):
+    g = np.random.Generator(np.random.Philox(key=[seed & 0xFFFFFFFFFFFFFFFF, stream]))
+    return (g.standard_normal(shape, dtype=np.float64) * std).astype(np.float32)
+
+
+def cp_factors(cfg: Config):
+    """A (I x R), B (J x R), C (K x R): iid N(0,1), float32, column-major."""
+    A = np.asfortranarray(_normal(cfg.seed, 1, (cfg.R, cfg.I), 1.0).T)
+    B = np.asfortranarray(_normal(cfg.seed, 2, (cfg.R, cfg.J), 1.0).T)
+    C = np.asfortranarray(_normal(cfg.seed, 3, (cfg.R, cfg.K), 1.0).T)
+    return A, B, C
+
+
+def compression_matrices(cfg: Config):
+    """Stacked U (P*L x I), V (P*M x J), W (P*N x K): iid N(0, 1/L) etc., float32, row-major,
+    replica p in rows p*L .. p*L+L-1."""
+    U = _normal(cfg.seed, 4, (cfg.P * cfg.L, cfg.I), cfg.L ** -0.5)
+    V = _normal(cfg.seed, 5, (cfg.P * cfg.M, cfg.J), cfg.M ** -0.5)
+    W = _normal(cfg.seed, 6, (cfg.P * cfg.N, cfg.K), cfg.N ** -0.5)
+    return U, V, W
+
+
+def small(name="tiny", index=100, I=24, J=20, K=28, R=3, P=3, L=5, M=4, N=6, dI=12, dJ=10, dK=7,
+          dtype="f32", materialised=True, sigma=0.01) -> Config:
+    """An arbitrary small non-cubic configuration for tests."""
+    return Config(name, I, J, K, R, P, L, M, N, dI, dJ, dK, dtype, materialised, sigma, index)

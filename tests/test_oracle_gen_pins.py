@@ -1,0 +1,154 @@
+"""Pins for the oracle's synthetic-input generator: the counter-based noise function, the
+bf16 rounding and the low-rank-plus-noise tensor (paper Sec. 5.1 describes the low-rank part;
+the noise term is this project's own definition, so it is pinned by its stated mathematics:
+Box-Muller inversion, normal moments and distribution, independence, tiling invariance)."""
+import numpy as np
+import pytest
+import torch
+from scipy import stats
+
+import oracle
+from paper_2311_13693_amd import workloads as wl
+
+SEED = 0x231113693000
+
+
+def test_noise_is_deterministic_and_depends_on_global_coordinates_only():
+    whole = oracle.noise_box(SEED, (0, 37, 0, 11, 0, 9))
+    again = oracle.noise_box(SEED, (0, 37, 0, 11, 0, 9))
+    assert np.array_equal(whole, again)
+    # any tiling reproduces the same elements, including tiles that start off the 4-aligned quad grid
+    for box in [(5, 23, 3, 8, 2, 9), (1, 2, 0, 11, 8, 9), (30, 37, 10, 11, 0, 1)]:
+        part = oracle.noise_box(SEED, box)
+        i0, i1, j0, j1, k0, k1 = box
+        assert np.array_equal(part, whole[i0:i1, j0:j1, k0:k1])
+    assert oracle.noise(SEED, 17, 4, 6) == whole[17, 4, 6]
+
+
+def test_noise_differs_between_seeds_and_coordinates():
+    a = oracle.noise_box(SEED, (0, 64, 0, 16, 0, 16))
+    b = oracle.noise_box(SEED + 1, (0, 64, 0, 16, 0, 16))
+    c = oracle.noise_box(SEED ^ (1 << 40), (0, 64, 0, 16, 0, 16))   # high seed word matters too
+    for other in (b, c):
+        assert abs(np.corrcoef(a.ravel(), other.ravel())[0, 1]) < 0.04
+    # swapping j and k must not give the same field
+    off = ~np.eye(16, dtype=bool)
+    assert abs(np.corrcoef(a[:, off].ravel(), a.transpose(0, 2, 1)[:, off].ravel())[0, 1]) < 0.04
+    # large coordinates (1e12-element configuration) are in range
+    assert np.isfinite(oracle.noise(SEED, 9999, 9999, 9999))
+    assert oracle.noise(SEED, 9999, 9999, 9999) != oracle.noise(SEED, 9999, 9998, 9999)
+
+
+def test_box_muller_inverts_to_the_16_bit_uniform_grid():
+    # g = sqrt(-2 ln u1) (cos|sin)(2 pi u2) with u = (f + 1/2)/65536: invert the pair and land on the grid
+    z = oracle.noise_box(SEED, (0, 4096, 0, 8, 0, 8))
+    z0, z1 = z[0::2], z[1::2]
+    u1 = np.exp(-(z0 ** 2 + z1 ** 2) / 2.0) * 65536.0 - 0.5
+    u2 = (np.arctan2(z1, z0) / (2 * np.pi)) % 1.0 * 65536.0 - 0.5
+    assert np.abs(u1 - np.round(u1)).max() < 1e-6
+    assert np.abs(u2 - np.round(u2)).max() < 1e-6
+    f1, f2 = np.round(u1).astype(np.int64), np.round(u2).astype(np.int64)
+    assert f1.min() >= 0 and f1.max() <= 65535 and f2.min() >= 0 and f2.max() <= 65535
+    # and they are the two halves of the hash word of the pair
+    for (ip, j, k) in [(0, 0, 0), (5, 3, 2), (2047, 7, 7)]:
+        w = oracle.noise_word(SEED, 2 * ip, j, k)
+        assert w == oracle.noise_word(SEED, 2 * ip + 1, j, k)
+        assert (w >> 16, w & 0xFFFF) == (f1[ip, j, k], f2[ip, j, k])
+    # the two pairs of a quad use different words
+    assert oracle.noise_word(SEED, 0, 0, 0) != oracle.noise_word(SEED, 2, 0, 0)
+
+
+def test_noise_moments_and_distribution():
+    z = oracle.noise_box(SEED, (0, 400, 0, 160, 0, 160)).ravel()      # 1.024e7 draws
+    n = z.size
+    assert abs(z.mean()) < 5 / np.sqrt(n)
+    assert abs(z.var() - 1.0) < 5 * np.sqrt(2.0 / n)
+    assert abs(stats.skew(z)) < 5 * np.sqrt(6.0 / n)
+    assert abs(stats.kurtosis(z)) < 5 * np.sqrt(24.0 / n)              # excess kurtosis of a normal is 0
+    assert abs((z ** 6).mean() - 15.0) < 5 * np.sqrt((10395 - 225) / n)
+    # Kolmogorov-Smirnov against the standard normal on a 1e6 subsample (critical value 1.63/sqrt(n) at 1%)
+    d = stats.kstest(z[::10], "norm").statistic
+    assert d < 1.95 / np.sqrt(z[::10].size)
+    assert np.abs(z).max() < 4.9          # sqrt(-2 ln(2^-17)) = 4.854 is the largest attainable radius
+
+
+def test_noise_is_uncorrelated_along_every_axis_and_within_pairs():
+    z = oracle.noise_box(SEED + 3, (0, 256, 0, 128, 0, 128))
+    n = z.size
+    lim = 5 / np.sqrt(n)
+    for axis in range(3):
+        for lag in (1, 2, 3, 4, 8):
+            a = np.take(z, range(0, z.shape[axis] - lag), axis=axis).ravel()
+            b = np.take(z, range(lag, z.shape[axis]), axis=axis).ravel()
+            assert abs(np.corrcoef(a, b)[0, 1]) < lim, (axis, lag)
+            assert abs(np.corrcoef(a * a, b * b)[0, 1]) < lim, (axis, lag, "squares")
+
+
+def test_hash_words_are_uniform():
+    ii, jj, kk = np.meshgrid(np.arange(0, 256, 2), np.arange(64), np.arange(64), indexing="ij")
+    words = np.array([oracle.noise_word(SEED, int(i), int(j), int(k))
+                      for i, j, k in zip(ii.ravel()[:200000], jj.ravel()[:200000], kk.ravel()[:200000])],
+                     dtype=np.uint64)
+    n = words.size
+    for shift in (0, 8, 16, 24):
+        counts = np.bincount(((words >> shift) & 0xFF).astype(np.int64), minlength=256)
+        chi2 = ((counts - n / 256) ** 2 / (n / 256)).sum()
+        assert chi2 < stats.chi2.ppf(0.9999, 255), shift
+    for bit in range(32):
+        ones = int(((words >> bit) & 1).sum())
+        assert abs(ones - n / 2) < 5 * np.sqrt(n) / 2, bit
+
+
+def test_bf16_rounding_matches_library_round_to_nearest_even():
+    rng = np.random.default_rng(5)
+    x = np.concatenate([rng.standard_normal(100000).astype(np.float32) * 37.0,
+                        np.array([1.0, 1.00390625, 1.01171875, -1.00390625, 3.0e38, 1e-30, 0.0], np.float32)])
+    ours = oracle.round_bf16(x)
+    ref = torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy()
+    assert np.array_equal(ours, ref)
+    # ties go to even: 1 + 2^-8 -> 1, 1 + 3*2^-8 -> 1 + 2^-6
+    assert oracle.round_bf16(np.float32([1.00390625]))[0] == 1.0
+    assert oracle.round_bf16(np.float32([1.01171875]))[0] == 1.015625
+
+
+def test_generated_tensor_is_low_rank_plus_sigma_times_noise():
+    cfg = wl.small(I=20, J=9, K=11, R=4)
+    A, B, C = wl.cp_factors(cfg)
+    X0 = oracle.gen_box(A, B, C, cfg.seed, 0.0)
+    Xe = np.einsum("ir,jr,kr->ijk", A.astype(np.float64), B.astype(np.float64), C.astype(np.float64))
+    assert np.array_equal(X0, Xe.astype(np.float32))
+    X = oracle.gen_box(A, B, C, cfg.seed, 0.01)
+    g = oracle.noise_box(cfg.seed, (0, cfg.I, 0, cfg.J, 0, cfg.K))
+    assert np.array_equal(X, (Xe + 0.01 * g).astype(np.float32))
+    # boxes are views of the same tensor; bf16 output is the RNE rounding of the fp32 tensor
+    box = (3, 17, 2, 9, 5, 6)
+    Xb = oracle.gen_box(A, B, C, cfg.seed, 0.01, box)
+    assert np.array_equal(Xb, X[3:17, 2:9, 5:6])
+    Xh = oracle.gen_box(A, B, C, cfg.seed, 0.01, box, to_bf16=True)
+    assert np.array_equal(Xh, torch.from_numpy(np.ascontiguousarray(Xb)).to(torch.bfloat16).to(torch.float32).numpy())
+
+
+def test_noise_energy_through_the_chain_matches_its_expectation():
+    # E || Comp(sigma*g, U, V, W) ||_F^2 = sigma^2 ||U||_F^2 ||V||_F^2 ||W||_F^2 for iid unit-variance g
+    cfg = wl.small(I=48, J=40, K=44, L=6, M=5, N=7, P=8, R=2)
+    U, V, W = wl.compression_matrices(cfg)
+    g = oracle.noise_box(cfg.seed, (0, cfg.I, 0, cfg.J, 0, cfg.K)).astype(np.float32)
+    Y = oracle.comp_multi(np.asfortranarray(g), U, V, W, cfg.P)
+    got, want = 0.0, 0.0
+    for p in range(cfg.P):
+        got += (Y[..., p] ** 2).sum()
+        want += ((U[p * cfg.L:(p + 1) * cfg.L].astype(np.float64) ** 2).sum() *
+                 (V[p * cfg.M:(p + 1) * cfg.M].astype(np.float64) ** 2).sum() *
+                 (W[p * cfg.N:(p + 1) * cfg.N].astype(np.float64) ** 2).sum())
+    # relative spread of the sum of P*L*M*N ~ chi-square terms
+    assert abs(got / want - 1.0) < 5 * np.sqrt(2.0 / (cfg.P * cfg.L * cfg.M * cfg.N))
+
+
+def test_noise_definition_is_frozen():
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "noise_words.txt")
+    rows = [ln.split() for ln in open(path) if not ln.startswith("#")]
+    assert len(rows) >= 10
+    for seed, i, j, k, word, g in rows:
+        assert oracle.noise_word(int(seed, 16), int(i), int(j), int(k)) == int(word, 16)
+        assert oracle.noise(int(seed, 16), int(i), int(j), int(k)) == float(g)
