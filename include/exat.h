@@ -1,0 +1,150 @@
+/*
+ * exat.h -- C ABI of the MI355X (gfx950) multi-replica tensor compression library.
+ *
+ * The operation is the compression stage of the Exascale-Tensor scheme
+ * (paper Sec. 3 "Compression", Eq. 3; Alg. 2 lines 1-2): for p = 0..P-1
+ *
+ *     Y_p[l,m,n] = sum_{i,j,k} U_p[l,i] * V_p[m,j] * W_p[n,k] * X[i,j,k]
+ *
+ * i.e. Y_p = X x1 U_p x2 V_p x3 W_p, computed block by block (Sec. 4.3, Fig. 2)
+ * with all P replicas' U_p stacked into one (P*L) x I operand (the stacked
+ * matrix of Eq. 4), so that X is traversed once for all replicas.
+ *
+ * Conventions
+ *   - Every pointer named "device" is a HIP device pointer on the current device;
+ *     descriptors (exat_desc_t, exat_gen_t, exat_box_t) are host structs.
+ *   - X is column-major (Sec. 4.1): element (i,j,k) at X[i + I*(j + J*k)].
+ *   - U, V, W are stacked and row-major with the reduction index contiguous:
+ *     U[(p*L + l)*ldU + i], V[(p*M + m)*ldV + j], W[(p*N + n)*ldW + k]; fp32.
+ *   - Y is fp32, column-major per replica, replicas outermost:
+ *     Y[l + L*(m + M*(n + N*p))].
+ *   - `stream` is a borrowed hipStream_t (NULL = default stream).  All work is
+ *     enqueued asynchronously on it; no call synchronises the device.
+ *   - The caller owns every buffer it passes.  A plan owns only its workspace
+ *     (packed operand copies, the mode-2 intermediate, block partials).
+ *   - Every function returns EXAT_OK (0) or a negative exat_status_t; nothing is
+ *     printed, thrown or aborted across this boundary.
+ *   - Calls on one plan must not overlap in time (they share the plan's workspace).
+ */
+#ifndef EXAT_H
+#define EXAT_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct exat_plan_s *exat_plan_t; /* opaque */
+
+typedef enum {
+    EXAT_OK = 0,
+    EXAT_ERR_NULL = -1,   /* a required pointer is NULL                                    */
+    EXAT_ERR_SHAPE = -2,  /* non-positive or too large extent, block does not divide the   */
+                          /* tensor, box not inside the tensor, ld too small               */
+    EXAT_ERR_DTYPE = -3,  /* unknown in_dtype                                              */
+    EXAT_ERR_STATE = -4,  /* factors not set, block submitted twice, finalize with nothing */
+    EXAT_ERR_ALLOC = -5,  /* device or host allocation failed                              */
+    EXAT_ERR_HIP = -6     /* a HIP runtime call or kernel launch failed                    */
+} exat_status_t;
+
+/* Type in which the kernels consume the X tile and U, V, W.  Products are always
+ * accumulated in fp32 and Y is always fp32.  With EXAT_BF16 the elements of X, U, V, W
+ * are rounded to bf16 (round-to-nearest-even) before use; the intermediates of the
+ * mode-1 and mode-2 contractions stay fp32. */
+typedef enum { EXAT_F32 = 0, EXAT_BF16 = 1 } exat_dtype_t;
+
+/* Problem statement: the inputs of Alg. 2 plus the block edge of Sec. 4.3. */
+typedef struct {
+    int64_t I, J, K;     /* X is I x J x K; each extent in [1, 2^31 - 64]                  */
+    int32_t L, M, N, P;  /* each Y_p is L x M x N; P replicas; M <= 64; P*L < 2^24          */
+    int32_t dI, dJ, dK;  /* block edges; must divide I, J, K (Sec. 4.3)                     */
+    int32_t in_dtype;    /* exat_dtype_t                                                    */
+} exat_desc_t;
+
+/* Synthetic input of the dense experiments (Sec. 5.1, Eq. 1) plus additive noise:
+ *   X[i,j,k] = sum_{r<R} A[i,r] B[j,r] C[k,r] + sigma * g(seed; i,j,k)
+ * A, B, C: device, fp32, column-major I x R, J x R, K x R (A[i + I*r]).
+ * g is the library's counter-based standard-normal function of the GLOBAL coordinates
+ * (so X does not depend on how it is tiled): with 32-bit mixers
+ *   mixA(x): x^=x>>16; x*=0x7feb352d; x^=x>>15; x*=0x846ca68b; x^=x>>16
+ *   mixB(x): x^=x>>16; x*=0x21f0aaad; x^=x>>15; x*=0x735a2d97; x^=x>>15
+ *   s  = mixA(mixA(lo32(seed) ^ 0x243f6a88) ^ hi32(seed));  ck = mixA(mixA(s ^ k) ^ j)
+ *   w  = (i & 2) ? mixB(ck ^ (i>>2)) : mixA(ck ^ (i>>2))
+ *   u1 = ((w>>16) + 0.5)/65536, u2 = ((w & 0xffff) + 0.5)/65536
+ *   g  = sqrt(-2 ln u1) * ((i & 1) ? sin(2 pi u2) : cos(2 pi u2))
+ * evaluated in fp32 with the hardware log2/sqrt/sin/cos. */
+typedef struct {
+    const float *A, *B, *C; /* device */
+    int32_t R;              /* 1 <= R <= 256 */
+    uint64_t seed;
+    float sigma;
+} exat_gen_t;
+
+/* Half-open sub-box [i0,i1) x [j0,j1) x [k0,k1) of X; any non-empty box inside X. */
+typedef struct { int64_t i0, i1, j0, j1, k0, k1; } exat_box_t;
+
+/* Creates a plan for `desc` on the current device and allocates its workspace
+ * (packed U/V/W copies and the mode-2 intermediate of P*L x M x K floats).
+ * Errors: NULL, SHAPE, DTYPE, ALLOC. */
+int exat_plan_create(exat_plan_t *plan, const exat_desc_t *desc);
+
+/* Frees the plan's workspace.  The caller must have synchronised the streams the plan
+ * was used on.  NULL is accepted. */
+int exat_plan_destroy(exat_plan_t plan);
+
+/* Operand preparation: copies the stacked fp32 U (P*L x I), V (P*M x J), W (P*N x K)
+ * (device, leading dimensions ldU >= I, ldV >= J, ldW >= K in elements) into the plan's
+ * padded tile layout, rounding to bf16 when in_dtype is EXAT_BF16.  The shared first S
+ * rows of Alg. 2 line 1 are a property of the caller's matrices; the library is agnostic.
+ * Must be called before any compress call; may be called again to replace the matrices.
+ * Errors: NULL, SHAPE, HIP. */
+int exat_set_factors(exat_plan_t plan, const float *U, int64_t ldU, const float *V, int64_t ldV,
+                     const float *W, int64_t ldW, void *stream);
+
+/* Y_p = Comp(X, U_p, V_p, W_p) for all p over a fully materialised X (Eq. 3).
+ * X: device, column-major I x J x K, fp32 (EXAT_F32) or bf16 (EXAT_BF16).
+ * Y: device, P*L*M*N floats, overwritten.  Bit-identical from run to run.
+ * Errors: NULL, STATE (factors not set), HIP. */
+int exat_compress(exat_plan_t plan, const void *X, float *Y, void *stream);
+
+/* Block-streamed compression (Sec. 4.3, Fig. 2a): compresses the block
+ * T^{bi,bj,bk} = X(bi*dI:(bi+1)*dI, bj*dJ:.., bk*dK:..) given as its own column-major
+ * dI x dJ x dK device array (in_dtype) with the matching column slices of U, V, W and
+ * adds the result to the plan's partial sums.  Xblk may be reused as soon as the work
+ * enqueued on `stream` has completed.  Each block is accepted once (a second
+ * submission returns STATE); exat_finalize merges the partials in a fixed order, so Y
+ * does not depend on the submission order whenever the plan could give every block its
+ * own partial (it can for up to 4 GiB of partials; beyond that, blocks that share a
+ * partial are summed in submission order).
+ * Errors: NULL, SHAPE (block index out of range), STATE, HIP. */
+int exat_compress_block(exat_plan_t plan, const void *Xblk, int32_t bi, int32_t bj, int32_t bk,
+                        void *stream);
+
+/* Merges the block partials into Y (overwritten) and resets the plan's block state so
+ * that a new sequence of exat_compress_block calls can start.
+ * Errors: NULL, STATE (no block submitted), HIP. */
+int exat_finalize(exat_plan_t plan, float *Y, void *stream);
+
+/* Compression of the synthetic tensor of exat_gen_t without ever materialising it: the
+ * kernels generate each X tile on chip.  box == NULL means the whole tensor; otherwise
+ * only the elements of X inside the box contribute (the merge of Fig. 2a over a sub-box).
+ * Y: device, P*L*M*N floats, overwritten.
+ * Errors: NULL, SHAPE (bad R or box), STATE, HIP. */
+int exat_compress_gen(exat_plan_t plan, const exat_gen_t *gen, const exat_box_t *box, float *Y,
+                      void *stream);
+
+/* Writes block (bi,bj,bk) of the synthetic tensor into `out` (device, column-major
+ * dI x dJ x dK, fp32 or bf16 according to desc->in_dtype): the same element function the
+ * fused kernels evaluate on chip.
+ * Errors: NULL, SHAPE, DTYPE, HIP. */
+int exat_gen_block(const exat_desc_t *desc, const exat_gen_t *gen, int32_t bi, int32_t bj, int32_t bk,
+                   void *out, void *stream);
+
+/* Static description of a status code (never NULL). */
+const char *exat_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EXAT_H */

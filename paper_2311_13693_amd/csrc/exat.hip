@@ -1,0 +1,369 @@
+// C ABI of the exat library (declarations and contracts in include/exat.h): argument
+// validation, plan/workspace management and kernel launches.  No compute happens on the host.
+#include "../../include/exat.h"
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "exat_aux.h"
+#include "exat_mode12.h"
+
+using namespace exat;
+
+namespace {
+
+constexpr int64_t kMaxExtent = 2147483647LL - 64;
+constexpr int64_t kSlotBudgetBytes = 4LL << 30;
+
+struct KernelChoice { int rt, ct; };
+
+}  // namespace
+
+struct exat_plan_s {
+    exat_desc_t d;
+    int PL, PLpad, Mpad, MT;
+    int64_t Ipad, Jpad;
+    void *Upack = nullptr;
+    float *Vpack = nullptr, *Wpack = nullptr, *Q = nullptr;
+    bool factors_set = false;
+    // block-streamed state
+    float *slots = nullptr;
+    unsigned char *used_dev = nullptr;
+    int nslots = 0;
+    int64_t nblocks = 0, ysize = 0;
+    std::vector<unsigned char> submitted, slot_used;
+    int64_t nsubmitted = 0;
+};
+
+namespace {
+
+inline int64_t ceil_to(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
+inline size_t esize(int dt) { return dt == EXAT_BF16 ? 2 : 4; }
+
+int env_int(const char *name, int dflt)
+{
+    const char *s = getenv(name);
+    return s ? atoi(s) : dflt;
+}
+
+// row-tile count per wave of the mode-1/2 kernel (workgroup rows = 128*rt)
+int choose_rt(const exat_plan_s *pl, bool generated)
+{
+    const int forced = env_int("EXAT_RT", 0);
+    if (pl->d.in_dtype == EXAT_BF16) {
+        if (forced == 2 || forced == 5) return forced;
+        return pl->PL > 512 ? 5 : 2;
+    }
+    if (forced == 1 || forced == 2 || forced == 4) return forced;
+    if (pl->PL <= 128) return 1;
+    if (generated && pl->PL >= 512) return 4;
+    return 2;
+}
+
+int validate_desc(const exat_desc_t *d)
+{
+    if (!d) return EXAT_ERR_NULL;
+    if (d->in_dtype != EXAT_F32 && d->in_dtype != EXAT_BF16) return EXAT_ERR_DTYPE;
+    if (d->I < 1 || d->J < 1 || d->K < 1 || d->I > kMaxExtent || d->J > kMaxExtent || d->K > kMaxExtent) return EXAT_ERR_SHAPE;
+    if (d->L < 1 || d->M < 1 || d->N < 1 || d->P < 1 || d->M > 64) return EXAT_ERR_SHAPE;
+    if ((int64_t)d->P * d->L >= (1 << 24) || (int64_t)d->P * d->N >= (1 << 24)) return EXAT_ERR_SHAPE;
+    if (d->dI < 1 || d->dJ < 1 || d->dK < 1) return EXAT_ERR_SHAPE;
+    if (d->I % d->dI || d->J % d->dJ || d->K % d->dK) return EXAT_ERR_SHAPE;
+    return EXAT_OK;
+}
+
+int validate_gen(const exat_gen_t *g)
+{
+    if (!g || !g->A || !g->B || !g->C) return EXAT_ERR_NULL;
+    if (g->R < 1 || g->R > 256) return EXAT_ERR_SHAPE;
+    if (!(g->sigma >= 0.0f) || !(g->sigma < 1e18f)) return EXAT_ERR_SHAPE;
+    return EXAT_OK;
+}
+
+float amp2_ln2_of(float sigma) { return sigma == 0.0f ? 0.0f : (float)(-2.0 * 0.69314718055994530942 * (double)sigma * (double)sigma); }
+
+template <typename T, int RT, int CT, int SRC>
+int launch_mode12_inst(const Mode12Params &mp, int nk, hipStream_t st)
+{
+    typedef Mode12Cfg<T, RT, CT> cfg;
+    auto kern = k_mode12<T, RT, CT, SRC>;
+    static bool attr_done = false;  // per instantiation; setting it twice is harmless
+    if (!attr_done) {
+        if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, cfg::LDS_BYTES) != hipSuccess) return EXAT_ERR_HIP;
+        attr_done = true;
+    }
+    const int64_t grid = 8LL * ((nk + 7) / 8) * mp.G;
+    if (grid > 2147483647LL) return EXAT_ERR_SHAPE;
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), cfg::LDS_BYTES, st, mp);
+    return hipGetLastError() == hipSuccess ? EXAT_OK : EXAT_ERR_HIP;
+}
+
+template <typename T, int SRC>
+int launch_mode12_rt(int rt, const Mode12Params &mp, int nk, hipStream_t st);
+
+template <int SRC>
+int launch_mode12_f32(int rt, const Mode12Params &mp, int nk, hipStream_t st)
+{
+    switch (rt) {
+    case 1: return launch_mode12_inst<float, 1, 4, SRC>(mp, nk, st);
+    case 2: return launch_mode12_inst<float, 2, 4, SRC>(mp, nk, st);
+    default: return launch_mode12_inst<float, 4, 4, SRC>(mp, nk, st);
+    }
+}
+template <int SRC>
+int launch_mode12_bf16(int rt, const Mode12Params &mp, int nk, hipStream_t st)
+{
+    switch (rt) {
+    case 2: return launch_mode12_inst<__bf16, 2, 4, SRC>(mp, nk, st);
+    default: return launch_mode12_inst<__bf16, 5, 4, SRC>(mp, nk, st);
+    }
+}
+
+// fills the plan-dependent part of the parameters and launches mode 1+2 followed by mode 3
+int run_chain(exat_plan_s *pl, Mode12Params mp, bool generated, float *Yout, int accumulate, hipStream_t st)
+{
+    const int rt = choose_rt(pl, generated);
+    const int rows = 128 * rt;
+    mp.U = pl->Upack; mp.V = pl->Vpack; mp.Q = pl->Q;
+    mp.I = pl->d.I; mp.Ipad = pl->Ipad; mp.Jpad = pl->Jpad;
+    mp.L = pl->d.L; mp.PL = pl->PL; mp.PLpad = pl->PLpad; mp.Mpad = pl->Mpad; mp.MT = pl->MT;
+    mp.G = (pl->PL + rows - 1) / rows;
+    const int nk = (int)(mp.k1 - mp.k0);
+    int rc;
+    if (pl->d.in_dtype == EXAT_BF16)
+        rc = generated ? launch_mode12_bf16<SRC_GENERATED>(rt, mp, nk, st) : launch_mode12_bf16<SRC_MATERIALISED>(rt, mp, nk, st);
+    else
+        rc = generated ? launch_mode12_f32<SRC_GENERATED>(rt, mp, nk, st) : launch_mode12_f32<SRC_MATERIALISED>(rt, mp, nk, st);
+    if (rc != EXAT_OK) return rc;
+    Mode3Params m3;
+    m3.Q = pl->Q; m3.W = pl->Wpack; m3.Y = Yout;
+    m3.L = pl->d.L; m3.M = pl->d.M; m3.N = pl->d.N; m3.PL = pl->PL; m3.PLpad = pl->PLpad; m3.Mpad = pl->Mpad;
+    m3.K = pl->d.K; m3.k0 = mp.k0; m3.k1 = mp.k1; m3.accumulate = accumulate;
+    constexpr int NT = 16;
+    const int64_t npos = (int64_t)pl->PL * pl->Mpad;
+    dim3 grid((unsigned)((npos + 255) / 256), (unsigned)((pl->d.N + NT - 1) / NT));
+    hipLaunchKernelGGL(k_mode3<NT>, grid, dim3(256), 0, st, m3);
+    return hipGetLastError() == hipSuccess ? EXAT_OK : EXAT_ERR_HIP;
+}
+
+__global__ void k_set_flag(unsigned char *flags, int idx, unsigned char v) { flags[idx] = v; }
+__global__ void k_clear_flags(unsigned char *flags, int n)
+{
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) flags[i] = 0;
+}
+
+unsigned grid_for(int64_t n) { int64_t g = (n + 255) / 256; return (unsigned)(g > 65536 ? 65536 : (g < 1 ? 1 : g)); }
+
+}  // namespace
+
+extern "C" {
+
+int exat_plan_create(exat_plan_t *plan, const exat_desc_t *desc)
+{
+    if (!plan) return EXAT_ERR_NULL;
+    *plan = nullptr;
+    int rc = validate_desc(desc);
+    if (rc != EXAT_OK) return rc;
+    exat_plan_s *pl = new (std::nothrow) exat_plan_s();
+    if (!pl) return EXAT_ERR_ALLOC;
+    pl->d = *desc;
+    pl->PL = desc->P * desc->L;
+    pl->MT = (desc->M + 31) / 32;
+    pl->Mpad = 32 * pl->MT;
+    pl->Ipad = ceil_to(desc->I, 32);
+    pl->Jpad = ceil_to(desc->J, 256);
+    // every kernel variant the plan may pick must find its row groups inside the padding
+    int64_t plpad = 0;
+    const int rts_f32[] = {1, 2, 4}, rts_bf16[] = {2, 5};
+    if (desc->in_dtype == EXAT_BF16) { for (int rt : rts_bf16) { int64_t v = ceil_to(pl->PL, 128 * rt); if (v > plpad) plpad = v; } }
+    else { for (int rt : rts_f32) { int64_t v = ceil_to(pl->PL, 128 * rt); if (v > plpad) plpad = v; } }
+    pl->PLpad = (int)plpad;
+    const size_t es = esize(desc->in_dtype);
+    const size_t ub = (size_t)pl->PLpad * pl->Ipad * es;
+    const size_t vb = (size_t)desc->P * pl->Mpad * pl->Jpad * 4;
+    const size_t wb = (size_t)desc->P * desc->N * desc->K * 4;
+    const size_t qb = (size_t)desc->K * pl->PLpad * pl->Mpad * 4;
+    if (hipMalloc(&pl->Upack, ub) != hipSuccess || hipMalloc((void **)&pl->Vpack, vb) != hipSuccess ||
+        hipMalloc((void **)&pl->Wpack, wb) != hipSuccess || hipMalloc((void **)&pl->Q, qb) != hipSuccess) {
+        (void)hipGetLastError();
+        exat_plan_destroy(pl);
+        return EXAT_ERR_ALLOC;
+    }
+    pl->nblocks = (desc->I / desc->dI) * (desc->J / desc->dJ) * (desc->K / desc->dK);
+    pl->ysize = (int64_t)desc->P * desc->L * desc->M * desc->N;
+    *plan = pl;
+    return EXAT_OK;
+}
+
+int exat_plan_destroy(exat_plan_t pl)
+{
+    if (!pl) return EXAT_OK;
+    (void)hipFree(pl->Upack); (void)hipFree(pl->Vpack); (void)hipFree(pl->Wpack); (void)hipFree(pl->Q);
+    (void)hipFree(pl->slots); (void)hipFree(pl->used_dev);
+    delete pl;
+    return EXAT_OK;
+}
+
+int exat_set_factors(exat_plan_t pl, const float *U, int64_t ldU, const float *V, int64_t ldV,
+                     const float *W, int64_t ldW, void *stream)
+{
+    if (!pl || !U || !V || !W) return EXAT_ERR_NULL;
+    const exat_desc_t &d = pl->d;
+    if (ldU < d.I || ldV < d.J || ldW < d.K) return EXAT_ERR_SHAPE;
+    hipStream_t st = (hipStream_t)stream;
+    const int64_t nu = (int64_t)pl->PLpad * pl->Ipad, nv = (int64_t)d.P * pl->Mpad * pl->Jpad, nw = (int64_t)d.P * d.N * d.K;
+    if (d.in_dtype == EXAT_BF16) {
+        hipLaunchKernelGGL(k_pack_u<__bf16>, dim3(grid_for(nu)), dim3(256), 0, st, U, ldU, pl->PL, d.I, (__bf16 *)pl->Upack, pl->PLpad, pl->Ipad);
+        hipLaunchKernelGGL(k_pack_v<__bf16>, dim3(grid_for(nv)), dim3(256), 0, st, V, ldV, d.P, d.M, d.J, pl->Vpack, pl->Mpad, pl->Jpad);
+        hipLaunchKernelGGL(k_pack_w<__bf16>, dim3(grid_for(nw)), dim3(256), 0, st, W, ldW, d.P * d.N, d.K, pl->Wpack);
+    } else {
+        hipLaunchKernelGGL(k_pack_u<float>, dim3(grid_for(nu)), dim3(256), 0, st, U, ldU, pl->PL, d.I, (float *)pl->Upack, pl->PLpad, pl->Ipad);
+        hipLaunchKernelGGL(k_pack_v<float>, dim3(grid_for(nv)), dim3(256), 0, st, V, ldV, d.P, d.M, d.J, pl->Vpack, pl->Mpad, pl->Jpad);
+        hipLaunchKernelGGL(k_pack_w<float>, dim3(grid_for(nw)), dim3(256), 0, st, W, ldW, d.P * d.N, d.K, pl->Wpack);
+    }
+    if (hipGetLastError() != hipSuccess) return EXAT_ERR_HIP;
+    pl->factors_set = true;
+    return EXAT_OK;
+}
+
+int exat_compress(exat_plan_t pl, const void *X, float *Y, void *stream)
+{
+    if (!pl || !X || !Y) return EXAT_ERR_NULL;
+    if (!pl->factors_set) return EXAT_ERR_STATE;
+    const exat_desc_t &d = pl->d;
+    Mode12Params mp;
+    memset(&mp, 0, sizeof(mp));
+    mp.X = X; mp.x_sj = d.I; mp.x_sk = d.I * d.J;
+    const int e16 = 16 / (int)esize(d.in_dtype);
+    mp.x_vec = (d.I % e16 == 0) && (((uintptr_t)X & 15) == 0);
+    mp.i0 = 0; mp.i1 = d.I; mp.j0 = 0; mp.j1 = d.J; mp.k0 = 0; mp.k1 = d.K;
+    return run_chain(pl, mp, false, Y, 0, (hipStream_t)stream);
+}
+
+int exat_compress_gen(exat_plan_t pl, const exat_gen_t *gen, const exat_box_t *box, float *Y, void *stream)
+{
+    if (!pl || !Y) return EXAT_ERR_NULL;
+    int rc = validate_gen(gen);
+    if (rc != EXAT_OK) return rc;
+    if (!pl->factors_set) return EXAT_ERR_STATE;
+    const exat_desc_t &d = pl->d;
+    exat_box_t b = {0, d.I, 0, d.J, 0, d.K};
+    if (box) b = *box;
+    if (b.i0 < 0 || b.j0 < 0 || b.k0 < 0 || b.i1 > d.I || b.j1 > d.J || b.k1 > d.K || b.i0 >= b.i1 || b.j0 >= b.j1 || b.k0 >= b.k1)
+        return EXAT_ERR_SHAPE;
+    Mode12Params mp;
+    memset(&mp, 0, sizeof(mp));
+    mp.A = gen->A; mp.B = gen->B; mp.C = gen->C; mp.ldA = d.I; mp.ldB = d.J; mp.ldC = d.K; mp.R = gen->R;
+    mp.skey = seed_key(gen->seed);
+    mp.amp2_ln2 = amp2_ln2_of(gen->sigma);
+    mp.i0 = b.i0; mp.i1 = b.i1; mp.j0 = b.j0; mp.j1 = b.j1; mp.k0 = b.k0; mp.k1 = b.k1;
+    return run_chain(pl, mp, true, Y, 0, (hipStream_t)stream);
+}
+
+int exat_compress_block(exat_plan_t pl, const void *Xblk, int32_t bi, int32_t bj, int32_t bk, void *stream)
+{
+    if (!pl || !Xblk) return EXAT_ERR_NULL;
+    if (!pl->factors_set) return EXAT_ERR_STATE;
+    const exat_desc_t &d = pl->d;
+    const int64_t nbi = d.I / d.dI, nbj = d.J / d.dJ, nbk = d.K / d.dK;
+    if (bi < 0 || bj < 0 || bk < 0 || bi >= nbi || bj >= nbj || bk >= nbk) return EXAT_ERR_SHAPE;
+    hipStream_t st = (hipStream_t)stream;
+    if (!pl->slots) {
+        int64_t ns = kSlotBudgetBytes / (pl->ysize * 4);
+        if (ns < 1) ns = 1;
+        if (ns > pl->nblocks) ns = pl->nblocks;
+        if (ns > (1 << 20)) ns = 1 << 20;
+        if (hipMalloc((void **)&pl->slots, (size_t)ns * pl->ysize * 4) != hipSuccess || hipMalloc((void **)&pl->used_dev, (size_t)ns) != hipSuccess) {
+            (void)hipGetLastError();
+            (void)hipFree(pl->slots); (void)hipFree(pl->used_dev);
+            pl->slots = nullptr; pl->used_dev = nullptr;
+            return EXAT_ERR_ALLOC;
+        }
+        pl->nslots = (int)ns;
+        pl->submitted.assign((size_t)pl->nblocks, 0);
+        pl->slot_used.assign((size_t)ns, 0);
+        pl->nsubmitted = 0;
+        hipLaunchKernelGGL(k_clear_flags, dim3(grid_for(ns)), dim3(256), 0, st, pl->used_dev, (int)ns);
+    }
+    const int64_t blk = bi + nbi * (bj + nbj * (int64_t)bk);
+    if (pl->submitted[(size_t)blk]) return EXAT_ERR_STATE;
+    const int slot = (int)(blk % pl->nslots);
+    Mode12Params mp;
+    memset(&mp, 0, sizeof(mp));
+    mp.X = Xblk; mp.x_sj = d.dI; mp.x_sk = (int64_t)d.dI * d.dJ;
+    mp.xo_i = (int64_t)bi * d.dI; mp.xo_j = (int64_t)bj * d.dJ; mp.xo_k = (int64_t)bk * d.dK;
+    const int e16 = 16 / (int)esize(d.in_dtype);
+    mp.x_vec = (d.dI % e16 == 0) && (mp.xo_i % e16 == 0) && (((uintptr_t)Xblk & 15) == 0);
+    mp.i0 = mp.xo_i; mp.i1 = mp.xo_i + d.dI; mp.j0 = mp.xo_j; mp.j1 = mp.xo_j + d.dJ; mp.k0 = mp.xo_k; mp.k1 = mp.xo_k + d.dK;
+    int rc = run_chain(pl, mp, false, pl->slots + (int64_t)slot * pl->ysize, pl->slot_used[(size_t)slot] ? 1 : 0, st);
+    if (rc != EXAT_OK) return rc;
+    if (!pl->slot_used[(size_t)slot]) {
+        hipLaunchKernelGGL(k_set_flag, dim3(1), dim3(1), 0, st, pl->used_dev, slot, (unsigned char)1);
+        if (hipGetLastError() != hipSuccess) return EXAT_ERR_HIP;
+        pl->slot_used[(size_t)slot] = 1;
+    }
+    pl->submitted[(size_t)blk] = 1;
+    pl->nsubmitted++;
+    return EXAT_OK;
+}
+
+int exat_finalize(exat_plan_t pl, float *Y, void *stream)
+{
+    if (!pl || !Y) return EXAT_ERR_NULL;
+    if (!pl->slots || pl->nsubmitted == 0) return EXAT_ERR_STATE;
+    hipStream_t st = (hipStream_t)stream;
+    hipLaunchKernelGGL(k_merge, dim3(grid_for(pl->ysize)), dim3(256), 0, st, pl->slots, pl->used_dev, pl->nslots, pl->ysize, Y);
+    hipLaunchKernelGGL(k_clear_flags, dim3(grid_for(pl->nslots)), dim3(256), 0, st, pl->used_dev, pl->nslots);
+    if (hipGetLastError() != hipSuccess) return EXAT_ERR_HIP;
+    std::fill(pl->submitted.begin(), pl->submitted.end(), 0);
+    std::fill(pl->slot_used.begin(), pl->slot_used.end(), 0);
+    pl->nsubmitted = 0;
+    return EXAT_OK;
+}
+
+int exat_gen_block(const exat_desc_t *desc, const exat_gen_t *gen, int32_t bi, int32_t bj, int32_t bk, void *out, void *stream)
+{
+    int rc = validate_desc(desc);
+    if (rc != EXAT_OK) return rc;
+    rc = validate_gen(gen);
+    if (rc != EXAT_OK) return rc;
+    if (!out) return EXAT_ERR_NULL;
+    const exat_desc_t &d = *desc;
+    if (bi < 0 || bj < 0 || bk < 0 || bi >= d.I / d.dI || bj >= d.J / d.dJ || bk >= d.K / d.dK) return EXAT_ERR_SHAPE;
+    GenParams gp;
+    gp.A = gen->A; gp.B = gen->B; gp.C = gen->C; gp.ldA = d.I; gp.ldB = d.J; gp.ldC = d.K; gp.R = gen->R;
+    gp.skey = seed_key(gen->seed);
+    gp.amp2_ln2 = amp2_ln2_of(gen->sigma);
+    gp.i0 = (int64_t)bi * d.dI; gp.i1 = gp.i0 + d.dI;
+    gp.j0 = (int64_t)bj * d.dJ; gp.j1 = gp.j0 + d.dJ;
+    gp.k0 = (int64_t)bk * d.dK; gp.k1 = gp.k0 + d.dK;
+    const int64_t nq = ((gp.i1 - 1) >> 2) - (gp.i0 >> 2) + 1;
+    const int64_t n = nq * d.dJ * d.dK;
+    hipStream_t st = (hipStream_t)stream;
+    if (d.in_dtype == EXAT_BF16)
+        hipLaunchKernelGGL(k_gen_box<__bf16>, dim3(grid_for(n)), dim3(256), 0, st, gp, (__bf16 *)out);
+    else
+        hipLaunchKernelGGL(k_gen_box<float>, dim3(grid_for(n)), dim3(256), 0, st, gp, (float *)out);
+    return hipGetLastError() == hipSuccess ? EXAT_OK : EXAT_ERR_HIP;
+}
+
+const char *exat_strerror(int status)
+{
+    switch (status) {
+    case EXAT_OK: return "success";
+    case EXAT_ERR_NULL: return "a required pointer is NULL";
+    case EXAT_ERR_SHAPE: return "invalid shape, block, box or leading dimension";
+    case EXAT_ERR_DTYPE: return "unknown element type";
+    case EXAT_ERR_STATE: return "call not valid in the plan's current state";
+    case EXAT_ERR_ALLOC: return "allocation failed";
+    case EXAT_ERR_HIP: return "HIP runtime error";
+    default: return "unknown status";
+    }
+}
+
+}  // extern "C"

@@ -1,0 +1,164 @@
+"""ctypes binding over libexat.so (C ABI in include/exat.h).
+
+Argument marshalling only: every step of the compression runs in the HIP kernels.  PyTorch is
+used for device memory (torch tensors own the buffers) and for the stream handle.  There is no
+CPU fallback: if the library is missing, loading fails loudly.
+"""
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libexat.so")
+
+EXAT_F32, EXAT_BF16 = 0, 1
+OK, ERR_NULL, ERR_SHAPE, ERR_DTYPE, ERR_STATE, ERR_ALLOC, ERR_HIP = 0, -1, -2, -3, -4, -5, -6
+
+EXPORTS = ["exat_plan_create", "exat_plan_destroy", "exat_set_factors", "exat_compress",
+           "exat_compress_block", "exat_finalize", "exat_compress_gen", "exat_gen_block", "exat_strerror"]
+
+
+class Desc(ctypes.Structure):
+    _fields_ = [("I", ctypes.c_int64), ("J", ctypes.c_int64), ("K", ctypes.c_int64),
+                ("L", ctypes.c_int32), ("M", ctypes.c_int32), ("N", ctypes.c_int32), ("P", ctypes.c_int32),
+                ("dI", ctypes.c_int32), ("dJ", ctypes.c_int32), ("dK", ctypes.c_int32),
+                ("in_dtype", ctypes.c_int32)]
+
+
+class Gen(ctypes.Structure):
+    _fields_ = [("A", ctypes.c_void_p), ("B", ctypes.c_void_p), ("C", ctypes.c_void_p),
+                ("R", ctypes.c_int32), ("seed", ctypes.c_uint64), ("sigma", ctypes.c_float)]
+
+
+class Box(ctypes.Structure):
+    _fields_ = [("i0", ctypes.c_int64), ("i1", ctypes.c_int64), ("j0", ctypes.c_int64),
+                ("j1", ctypes.c_int64), ("k0", ctypes.c_int64), ("k1", ctypes.c_int64)]
+
+
+class ExatError(RuntimeError):
+    def __init__(self, status, msg):
+        super().__init__("exat: %s (status %d)" % (msg, status))
+        self.status = status
+
+
+_lib = None
+
+
+def lib():
+    """Loads libexat.so; raises if it has not been built (python -m paper_2311_13693_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise ImportError("libexat.so is not built: run `python paper_2311_13693_amd/build.py` "
+                              "(there is no CPU fallback)")
+        L = ctypes.CDLL(_LIB_PATH)
+        vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+        L.exat_plan_create.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(Desc)]
+        L.exat_plan_destroy.argtypes = [vp]
+        L.exat_set_factors.argtypes = [vp, vp, i64, vp, i64, vp, i64, vp]
+        L.exat_compress.argtypes = [vp, vp, vp, vp]
+        L.exat_compress_block.argtypes = [vp, vp, i32, i32, i32, vp]
+        L.exat_finalize.argtypes = [vp, vp, vp]
+        L.exat_compress_gen.argtypes = [vp, ctypes.POINTER(Gen), ctypes.POINTER(Box), vp, vp]
+        L.exat_gen_block.argtypes = [ctypes.POINTER(Desc), ctypes.POINTER(Gen), i32, i32, i32, vp, vp]
+        L.exat_strerror.argtypes = [ctypes.c_int]
+        L.exat_strerror.restype = ctypes.c_char_p
+        for name in EXPORTS[:-1]:
+            getattr(L, name).restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def strerror(status):
+    return lib().exat_strerror(int(status)).decode()
+
+
+def _check(status):
+    if status != OK:
+        raise ExatError(status, strerror(status))
+
+
+def _stream_handle(stream):
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _ptr(t):
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def make_desc(I, J, K, L, M, N, P, dI, dJ, dK, in_dtype=EXAT_F32):
+    return Desc(I, J, K, L, M, N, P, dI, dJ, dK, in_dtype)
+
+
+def make_gen(A, B, C, seed, sigma):
+    """A, B, C: float32 CUDA tensors holding the column-major I x R, J x R, K x R factor matrices,
+    i.e. torch tensors of shape (R, I) etc. that are contiguous (element (i, r) at r*I + i)."""
+    import torch
+    for t in (A, B, C):
+        assert t.is_cuda and t.dtype == torch.float32 and t.is_contiguous() and t.dim() == 2
+    g = Gen(A.data_ptr(), B.data_ptr(), C.data_ptr(), A.shape[0], seed & 0xFFFFFFFFFFFFFFFF, float(sigma))
+    g._keep = (A, B, C)
+    return g
+
+
+def gen_block(desc, gen, bi, bj, bk, out, stream=None):
+    """Writes block (bi,bj,bk) of the synthetic tensor into `out` (CUDA tensor of dI*dJ*dK elements,
+    float32 or bfloat16 according to desc.in_dtype, column-major on the block)."""
+    _check(lib().exat_gen_block(ctypes.byref(desc), ctypes.byref(gen), bi, bj, bk, _ptr(out), _stream_handle(stream)))
+    return out
+
+
+class Plan:
+    """Owns an exat_plan_t.  Tensors passed in must be CUDA tensors on the current device."""
+
+    def __init__(self, desc):
+        self.desc = desc
+        self._h = ctypes.c_void_p()
+        _check(lib().exat_plan_create(ctypes.byref(self._h), ctypes.byref(desc)))
+        self.ysize = desc.P * desc.L * desc.M * desc.N
+
+    def close(self):
+        if self._h:
+            import torch
+            torch.cuda.synchronize()
+            lib().exat_plan_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def set_factors(self, U, V, W, stream=None):
+        """U (P*L, I), V (P*M, J), W (P*N, K): float32 CUDA tensors, last dimension contiguous."""
+        import torch
+        for t in (U, V, W):
+            assert t.is_cuda and t.dtype == torch.float32 and t.dim() == 2 and t.stride(1) == 1
+        _check(lib().exat_set_factors(self._h, _ptr(U), U.stride(0), _ptr(V), V.stride(0), _ptr(W), W.stride(0),
+                                      _stream_handle(stream)))
+
+    def new_y(self):
+        import torch
+        return torch.empty(self.ysize, dtype=torch.float32, device="cuda")
+
+    def compress(self, X, Y=None, stream=None):
+        """X: CUDA tensor holding the column-major I x J x K tensor (float32 or bfloat16)."""
+        Y = self.new_y() if Y is None else Y
+        _check(lib().exat_compress(self._h, _ptr(X), _ptr(Y), _stream_handle(stream)))
+        return Y
+
+    def compress_block(self, Xblk, bi, bj, bk, stream=None):
+        _check(lib().exat_compress_block(self._h, _ptr(Xblk), bi, bj, bk, _stream_handle(stream)))
+
+    def finalize(self, Y=None, stream=None):
+        Y = self.new_y() if Y is None else Y
+        _check(lib().exat_finalize(self._h, _ptr(Y), _stream_handle(stream)))
+        return Y
+
+    def compress_gen(self, gen, box=None, Y=None, stream=None):
+        Y = self.new_y() if Y is None else Y
+        b = None if box is None else ctypes.byref(Box(*box))
+        _check(lib().exat_compress_gen(self._h, ctypes.byref(gen), b, _ptr(Y), _stream_handle(stream)))
+        return Y

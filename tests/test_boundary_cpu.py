@@ -1,0 +1,72 @@
+"""Boundary checks that need no GPU: the C-ABI library loads, exports every function that
+include/exat.h declares, and rejects bad arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2311_13693_amd import exat
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "exat.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(exat_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_function():
+    names = _declared()
+    assert len(names) >= 9
+    L = exat.lib()
+    for n in names:
+        assert hasattr(L, n), n
+    assert sorted(exat.EXPORTS) == names
+
+
+def test_strerror_is_total():
+    for s in range(-8, 2):
+        assert isinstance(exat.strerror(s), str) and exat.strerror(s)
+    assert exat.strerror(0) == "success"
+
+
+def _desc(**kw):
+    base = dict(I=8, J=8, K=8, L=2, M=2, N=2, P=1, dI=4, dJ=4, dK=4, in_dtype=0)
+    base.update(kw)
+    return exat.make_desc(**base)
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(I=0), exat.ERR_SHAPE), (dict(J=-3), exat.ERR_SHAPE), (dict(K=2 ** 31), exat.ERR_SHAPE),
+    (dict(L=0), exat.ERR_SHAPE), (dict(M=65), exat.ERR_SHAPE), (dict(P=0), exat.ERR_SHAPE),
+    (dict(dI=3), exat.ERR_SHAPE), (dict(dJ=0), exat.ERR_SHAPE), (dict(dK=5), exat.ERR_SHAPE),
+    (dict(in_dtype=7), exat.ERR_DTYPE), (dict(P=2 ** 20, L=64), exat.ERR_SHAPE),
+])
+def test_plan_create_rejects_bad_descriptors(kw, code):
+    h = ctypes.c_void_p()
+    d = _desc(**kw)
+    assert exat.lib().exat_plan_create(ctypes.byref(h), ctypes.byref(d)) == code
+    assert not h
+
+
+def test_null_arguments_are_errors_not_crashes():
+    L = exat.lib()
+    d = _desc()
+    h = ctypes.c_void_p()
+    assert L.exat_plan_create(None, ctypes.byref(d)) == exat.ERR_NULL
+    assert L.exat_plan_create(ctypes.byref(h), None) == exat.ERR_NULL
+    assert L.exat_plan_destroy(None) == exat.OK
+    assert L.exat_set_factors(None, None, 0, None, 0, None, 0, None) == exat.ERR_NULL
+    assert L.exat_compress(None, None, None, None) == exat.ERR_NULL
+    assert L.exat_compress_block(None, None, 0, 0, 0, None) == exat.ERR_NULL
+    assert L.exat_finalize(None, None, None) == exat.ERR_NULL
+    assert L.exat_compress_gen(None, None, None, None, None) == exat.ERR_NULL
+    g = exat.Gen(None, None, None, 3, 1, 0.0)
+    assert L.exat_gen_block(ctypes.byref(d), ctypes.byref(g), 0, 0, 0, None, None) == exat.ERR_NULL
+    assert L.exat_gen_block(None, ctypes.byref(g), 0, 0, 0, None, None) == exat.ERR_NULL
+    g2 = exat.Gen(1, 1, 1, 0, 1, 0.0)   # R = 0 (pointers are never dereferenced on this path)
+    assert L.exat_gen_block(ctypes.byref(d), ctypes.byref(g2), 0, 0, 0, ctypes.c_void_p(1), None) == exat.ERR_SHAPE
+    g3 = exat.Gen(1, 1, 1, 2, 1, 0.0)
+    assert L.exat_gen_block(ctypes.byref(d), ctypes.byref(g3), 2, 0, 0, ctypes.c_void_p(1), None) == exat.ERR_SHAPE

@@ -1,0 +1,236 @@
+"""GPU parity: the HIP path through the C ABI against the CPU oracle, element by element / per
+replica on the same seeded inputs.  Tolerances (relative Frobenius error per replica, the
+benchmark contract): 1e-5 on fp32 paths, 2e-2 on bf16-input/fp32-accumulate paths."""
+import os
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2311_13693_amd import exat, workloads as wl
+
+sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
+import gpu_util as gu  # noqa: E402
+
+pytestmark = pytest.mark.gpu
+
+TOL_F32 = 1e-5
+TOL_BF16 = 2e-2
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+@pytest.fixture(autouse=True)
+def _announce(request):
+    _say("[case] " + request.node.nodeid)
+    os.environ.pop("EXAT_RT", None)
+    yield
+    torch.cuda.synchronize()
+
+
+SMALL = {
+    "tiny": dict(I=24, J=20, K=28, R=3, P=3, L=5, M=4, N=6, dI=12, dJ=10, dK=7),
+    "odd_scalar_path": dict(I=37, J=29, K=11, R=4, P=21, L=7, M=33, N=5, dI=37, dJ=29, dK=11),
+    "two_row_groups": dict(I=64, J=140, K=9, R=5, P=9, L=32, M=16, N=3, dI=32, dJ=70, dK=3),
+    "l_below_tile": dict(I=40, J=36, K=10, R=2, P=40, L=4, M=3, N=2, dI=20, dJ=12, dK=5),
+    "ragged_j_chunks": dict(I=100, J=300, K=6, R=6, P=2, L=50, M=50, N=50, dI=50, dJ=150, dK=3),
+}
+
+
+def _inputs(cfg):
+    A, B, C = wl.cp_factors(cfg)
+    U, V, W = wl.compression_matrices(cfg)
+    return A, B, C, U, V, W
+
+
+@pytest.mark.parametrize("name", list(SMALL))
+@pytest.mark.parametrize("rt", [0, 1, 4])
+def test_compress_materialised_fp32_small(name, rt):
+    cfg = wl.small(name=name, index=200 + list(SMALL).index(name), **SMALL[name])
+    if rt:
+        os.environ["EXAT_RT"] = str(rt)
+    A, B, C, U, V, W = _inputs(cfg)
+    X = oracle.gen_box(A, B, C, cfg.seed, cfg.sigma)
+    plan = gu.plan_with_factors(cfg, U, V, W)
+    Y = gu.y_to_numpy(plan.compress(gu.to_dev_x(X)), cfg)
+    Yo = oracle.comp_multi(X, U, V, W, cfg.P)
+    err = oracle.rel_fro(Y, Yo)
+    _say("  rel_fro=%.3e" % err)
+    assert err <= TOL_F32
+    plan.close()
+
+
+def test_compress_is_bit_identical_run_to_run():
+    cfg = wl.small(name="det", index=210, **SMALL["two_row_groups"])
+    A, B, C, U, V, W = _inputs(cfg)
+    X = gu.to_dev_x(oracle.gen_box(A, B, C, cfg.seed, cfg.sigma))
+    plan = gu.plan_with_factors(cfg, U, V, W)
+    y1 = plan.compress(X).clone()
+    y2 = plan.compress(X).clone()
+    assert torch.equal(y1, y2)
+    plan.close()
+
+
+def test_cfg1_full_parity():
+    cfg = wl.CONFIGS["cfg1"]
+    A, B, C, U, V, W = _inputs(cfg)
+    X = oracle.gen_box(A, B, C, cfg.seed, cfg.sigma)
+    plan = gu.plan_with_factors(cfg, U, V, W)
+    Y = gu.y_to_numpy(plan.compress(gu.to_dev_x(X)), cfg)
+    Yo = oracle.comp_multi(X, U, V, W, cfg.P)
+    err = oracle.rel_fro(Y, Yo)
+    _say("  cfg1 rel_fro=%.3e" % err)
+    assert err <= TOL_F32
+    # the same tensor produced on the GPU by the block generator, then compressed
+    Xg = torch.empty(cfg.elements, dtype=torch.float32, device="cuda")
+    exat.gen_block(gu.desc_of(cfg), gu.gen_of(cfg, A, B, C), 0, 0, 0, Xg)
+    Y2 = gu.y_to_numpy(plan.compress(Xg), cfg)
+    err2 = oracle.rel_fro(Y2, Yo)
+    _say("  cfg1 (GPU-generated X) rel_fro=%.3e" % err2)
+    assert err2 <= TOL_F32
+    # and never materialised
+    Y3 = gu.y_to_numpy(plan.compress_gen(gu.gen_of(cfg, A, B, C)), cfg)
+    err3 = oracle.rel_fro(Y3, Yo)
+    _say("  cfg1 (generated in kernel) rel_fro=%.3e" % err3)
+    assert err3 <= TOL_F32
+    plan.close()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_gen_block_matches_oracle_elementwise(dtype):
+    cfg = wl.small(name="gen", index=220, I=52, J=18, K=10, R=7, dI=26, dJ=9, dK=5, dtype=dtype)
+    A, B, C = wl.cp_factors(cfg)
+    desc = gu.desc_of(cfg)
+    gen = gu.gen_of(cfg, A, B, C)
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    for (bi, bj, bk) in [(0, 0, 0), (1, 1, 1), (1, 0, 1)]:
+        out = torch.empty(cfg.dI * cfg.dJ * cfg.dK, dtype=tdt, device="cuda")
+        exat.gen_block(desc, gen, bi, bj, bk, out)
+        got = out.float().cpu().numpy().reshape((cfg.dI, cfg.dJ, cfg.dK), order="F")
+        box = (bi * cfg.dI, (bi + 1) * cfg.dI, bj * cfg.dJ, (bj + 1) * cfg.dJ, bk * cfg.dK, (bk + 1) * cfg.dK)
+        want = oracle.gen_box(A, B, C, cfg.seed, cfg.sigma, box, to_bf16=(dtype == "bf16"))
+        diff = np.abs(got.astype(np.float64) - want.astype(np.float64))
+        scale = 1.0 + np.abs(want).max()
+        if dtype == "f32":
+            _say("  block %s max|diff|=%.3e (scale %.1f)" % ((bi, bj, bk), diff.max(), scale))
+            assert diff.max() <= 2e-6 * scale        # fp32 evaluation of an R-term sum vs fp64-then-round
+        else:
+            flips = (diff > 0).mean()
+            _say("  block %s bf16 flips=%.2e max|diff|=%.3e" % ((bi, bj, bk), flips, diff.max()))
+            assert flips <= 5e-3 and np.all(diff <= np.abs(want) * 2.0 ** -7 + 1e-30)
+
+
+def test_noise_alone_matches_oracle():
+    # zero factors: the block is sigma * g exactly
+    cfg = wl.small(name="noise", index=221, I=64, J=33, K=9, R=1, dI=64, dJ=33, dK=9, sigma=1.0)
+    Z = np.zeros((cfg.I, 1), np.float32, order="F")
+    gen = exat.make_gen(gu.to_dev_factor(Z), gu.to_dev_factor(np.zeros((cfg.J, 1), np.float32)),
+                        gu.to_dev_factor(np.zeros((cfg.K, 1), np.float32)), cfg.seed, 1.0)
+    out = torch.empty(cfg.elements, dtype=torch.float32, device="cuda")
+    exat.gen_block(gu.desc_of(cfg), gen, 0, 0, 0, out)
+    got = out.cpu().numpy().astype(np.float64).reshape((cfg.I, cfg.J, cfg.K), order="F")
+    want = oracle.noise_box(cfg.seed, (0, cfg.I, 0, cfg.J, 0, cfg.K))
+    d = np.abs(got - want).max()
+    _say("  max|g_gpu - g_oracle| = %.3e" % d)
+    assert d <= 5e-6   # hardware log2/sqrt/sin/cos in fp32 against libm in fp64, |g| < 4.9
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_compress_gen_small_and_subboxes(dtype):
+    cfg = wl.small(name="cgen", index=230, I=100, J=60, K=12, R=5, P=6, L=10, M=9, N=8, dI=50, dJ=30, dK=4, dtype=dtype)
+    A, B, C, U, V, W = _inputs(cfg)
+    plan = gu.plan_with_factors(cfg, U, V, W)
+    gen = gu.gen_of(cfg, A, B, C)
+    X = oracle.gen_box(A, B, C, cfg.seed, cfg.sigma)
+    Yo = oracle.comp_multi(X, U, V, W, cfg.P)
+    Y = gu.y_to_numpy(plan.compress_gen(gen), cfg)
+    err = oracle.rel_fro(Y, Yo)
+    _say("  full: rel_fro=%.3e" % err)
+    assert err <= (TOL_BF16 if dtype == "bf16" else TOL_F32)
+    if dtype == "bf16":
+        # against the oracle on bf16-rounded inputs: isolates kernel errors from quantisation
+        rb = oracle.round_bf16
+        Yr = oracle.comp_multi(np.asfortranarray(rb(X.reshape(-1, order="F")).reshape(X.shape, order="F")),
+                               rb(U), rb(V), rb(W), cfg.P)
+        err_r = oracle.rel_fro(Y, Yr)
+        _say("  full vs oracle on bf16-rounded inputs: rel_fro=%.3e" % err_r)
+        assert err_r <= 5e-4
+    # sub-boxes, including ones that are not aligned to anything
+    acc = np.zeros_like(Yo)
+    boxes = [(0, 50, 0, 30, 0, 4), (50, 100, 30, 60, 8, 12), (13, 71, 7, 41, 3, 10)]
+    for box in boxes:
+        Yb = gu.y_to_numpy(plan.compress_gen(gen, box), cfg)
+        i0, i1, j0, j1, k0, k1 = box
+        Xb = np.asfortranarray(X[i0:i1, j0:j1, k0:k1])
+        Yob = oracle.comp_box(Xb, U, V, W, cfg.P, box)
+        e = oracle.rel_fro(Yb, Yob)
+        _say("  box %s rel_fro=%.3e" % (box, e))
+        assert e <= (TOL_BF16 if dtype == "bf16" else TOL_F32)
+    plan.close()
+
+
+def test_block_streamed_equals_one_shot_and_is_order_independent():
+    cfg = wl.small(name="blk", index=240, I=48, J=40, K=12, R=4, P=5, L=6, M=7, N=4, dI=16, dJ=20, dK=4)
+    A, B, C, U, V, W = _inputs(cfg)
+    X = oracle.gen_box(A, B, C, cfg.seed, cfg.sigma)
+    Yo = oracle.comp_multi(X, U, V, W, cfg.P)
+    plan = gu.plan_with_factors(cfg, U, V, W)
+    blocks = [(bi, bj, bk) for bi in range(3) for bj in range(2) for bk in range(3)]
+
+    def run(order):
+        for (bi, bj, bk) in order:
+            Xb = np.asfortranarray(X[bi * 16:(bi + 1) * 16, bj * 20:(bj + 1) * 20, bk * 4:(bk + 1) * 4])
+            plan.compress_block(gu.to_dev_x(Xb), bi, bj, bk)
+        return plan.finalize().clone()
+
+    y1 = run(blocks)
+    y2 = run(list(reversed(blocks)))
+    assert torch.equal(y1, y2)
+    err = oracle.rel_fro(gu.y_to_numpy(y1, cfg), Yo)
+    _say("  block-streamed rel_fro=%.3e" % err)
+    assert err <= TOL_F32
+    # state errors: finalize with nothing, a block twice, an index out of range
+    with pytest.raises(exat.ExatError) as e:
+        plan.finalize()
+    assert e.value.status == exat.ERR_STATE
+    Xb = gu.to_dev_x(np.asfortranarray(X[:16, :20, :4]))
+    plan.compress_block(Xb, 0, 0, 0)
+    with pytest.raises(exat.ExatError) as e:
+        plan.compress_block(Xb, 0, 0, 0)
+    assert e.value.status == exat.ERR_STATE
+    with pytest.raises(exat.ExatError) as e:
+        plan.compress_block(Xb, 3, 0, 0)
+    assert e.value.status == exat.ERR_SHAPE
+    plan.finalize()
+    plan.close()
+
+
+def test_compress_before_set_factors_is_a_state_error():
+    cfg = wl.small()
+    plan = exat.Plan(gu.desc_of(cfg))
+    X = torch.zeros(cfg.elements, dtype=torch.float32, device="cuda")
+    with pytest.raises(exat.ExatError) as e:
+        plan.compress(X)
+    assert e.value.status == exat.ERR_STATE
+    plan.close()
+
+
+def test_compress_materialised_bf16_small():
+    cfg = wl.small(name="bf16mat", index=250, I=96, J=72, K=10, R=4, P=7, L=50, M=50, N=50, dI=48, dJ=36, dK=5, dtype="bf16")
+    A, B, C, U, V, W = _inputs(cfg)
+    X = oracle.gen_box(A, B, C, cfg.seed, cfg.sigma, to_bf16=True)      # exactly representable in bf16
+    plan = gu.plan_with_factors(cfg, U, V, W)
+    Y = gu.y_to_numpy(plan.compress(gu.to_dev_x(X, bf16=True)), cfg)
+    rb = oracle.round_bf16
+    Yr = oracle.comp_multi(X, rb(U), rb(V), rb(W), cfg.P)
+    err_r = oracle.rel_fro(Y, Yr)
+    Yo = oracle.comp_multi(oracle.gen_box(A, B, C, cfg.seed, cfg.sigma), U, V, W, cfg.P)
+    err = oracle.rel_fro(Y, Yo)
+    _say("  bf16 materialised: vs rounded-input oracle %.3e, vs fp32-input oracle %.3e" % (err_r, err))
+    assert err_r <= 1e-5
+    assert err <= TOL_BF16
+    plan.close()
