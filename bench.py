@@ -1,0 +1,150 @@
+#!/usr/bin/env python3
+"""Benchmark of the compression hot path (all three mode contractions for all replicas) on one MI355X.
+
+One "step" = one full pass Y_p = X x1 U_p x2 V_p x3 W_p, p = 0..P-1, over one synthetic tensor of the
+chosen configuration, inputs resident in HBM (or generated on chip) when the timed region starts.
+Prints ONE JSON line: whole-job throughput in input elements/s, the roofline of the dominant kernel
+(fused mode-1/2, MFMA-bound) measured live with HIP events, and the CPU oracle timed on a bounded sample.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}   # MI355X dense MFMA peaks
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--config", default=os.environ.get("EXAT_BENCH_CONFIG", "cfg2"))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--check", action="store_true", help="also compare sampled replicas with the oracle")
+    return ap.parse_args()
+
+
+def cpu_baseline(cfg, A, B, C, U, V, W, budget_s=20.0):
+    """Times the oracle as it stands on a bounded sample of the workload: the triple-loop chain for a few
+    replicas on one block of X (the same block-wise operation the full run repeats), scaled to the
+    whole tensor and all P replicas."""
+    import oracle
+    # sample block: the configuration's own block, shrunk until one replica costs about a second
+    di, dj, dk = min(cfg.dI, cfg.I), min(cfg.dJ, cfg.J), min(cfg.dK, cfg.K)
+    box = (0, di, 0, dj, 0, dk)
+    Xb = oracle.gen_box(A, B, C, cfg.seed, cfg.sigma, box)
+    reps, t_total = 0, 0.0
+    while reps < cfg.P and (t_total < budget_s / 2 or reps < 1):
+        t0 = time.perf_counter()
+        oracle.comp_box(Xb, U, V, W, cfg.P, box, replicas=[reps])
+        t_total += time.perf_counter() - t0
+        reps += 1
+    per_rep_block = t_total / reps
+    nblocks = (cfg.I // di) * (cfg.J // dj) * (cfg.K // dk)
+    t_full = per_rep_block * cfg.P * nblocks
+    return {"value": cfg.elements / t_full, "unit": "elements/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": "%d replica(s) of %d on one %dx%dx%d block, extrapolated x%d replicas x %d blocks"
+                      % (reps, cfg.P, di, dj, dk, cfg.P, nblocks),
+            "seconds_measured": round(t_total, 3), "seconds_full_extrapolated": t_full}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives are part of it); "
+              "run with --gpus 1. Throughput at N GPUs is not measured.", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2311_13693_amd import exat, workloads as wl
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    cfg = wl.CONFIGS[args.config]
+    big = cfg.elements > 5e10
+    steps = args.steps if args.steps is not None else (2 if big else (5 if cfg.elements > 5e8 else 20))
+    warmup = args.warmup if args.warmup is not None else (1 if big else 3)
+
+    torch.cuda.set_device(0)
+    A, B, C = wl.cp_factors(cfg)
+    U, V, W = wl.compression_matrices(cfg)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+    gen = exat.make_gen(dev(A.T), dev(B.T), dev(C.T), cfg.seed, cfg.sigma)
+    dt = exat.EXAT_BF16 if cfg.dtype == "bf16" else exat.EXAT_F32
+    plan = exat.Plan(exat.make_desc(cfg.I, cfg.J, cfg.K, cfg.L, cfg.M, cfg.N, cfg.P, cfg.dI, cfg.dJ, cfg.dK, dt))
+    t0 = time.perf_counter()
+    plan.set_factors(dev(U), dev(V), dev(W))
+    torch.cuda.synchronize()
+    t_prep = time.perf_counter() - t0
+    X = None
+    if cfg.materialised:
+        # X resident in HBM before the timed region, produced by the library's own block generator
+        whole = exat.make_desc(cfg.I, cfg.J, cfg.K, cfg.L, cfg.M, cfg.N, cfg.P, cfg.I, cfg.J, cfg.K, dt)
+        X = torch.empty(cfg.elements, dtype=torch.bfloat16 if cfg.dtype == "bf16" else torch.float32, device="cuda")
+        exat.gen_block(whole, gen, 0, 0, 0, X)
+    Y = plan.new_y()
+    step = (lambda: plan.compress(X, Y)) if cfg.materialised else (lambda: plan.compress_gen(gen, None, Y))
+
+    plan.set_timing(True)
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    k12, k3 = [], []
+    e0.record()
+    for _ in range(steps):
+        step()
+        a, b = plan.last_timing()      # waits for this step's kernels (they are serialised on one stream anyway)
+        k12.append(a); k3.append(b)
+    e1.record()
+    torch.cuda.synchronize()
+    ms_step = e0.elapsed_time(e1) / steps
+    ms12, ms3 = float(np.mean(k12)), float(np.mean(k3))
+
+    PL = cfg.P * cfg.L
+    f12 = 2.0 * PL * (cfg.elements + cfg.M * cfg.J * cfg.K)      # algorithmic flops of the fused mode-1/2 launch
+    achieved = f12 / (ms12 * 1e-3) / 1e12
+    peak = PEAK_TFLOPS[cfg.dtype]
+    out = {
+        "metric": "input tensor elements compressed/sec + TTM TFLOP/s (% MFMA peak), 1 MI355X",
+        "value": cfg.elements / (ms_step * 1e-3), "unit": "elements/s",
+        "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if cfg.dtype == "f32" else "bf16 (fp32 accumulate)", "data": "synthetic",
+        "config": {"workload": "%s: %dx%dx%d %s, R=%d, P=%d, L=M=N=%d, %s" % (
+            cfg.name, cfg.I, cfg.J, cfg.K, cfg.dtype, cfg.R, cfg.P, cfg.L,
+            "materialised in HBM" if cfg.materialised else "generated on chip"),
+            "sigma": cfg.sigma, "block": [cfg.dI, cfg.dJ, cfg.dK]},
+        "ttm_tflops": cfg.flops / (ms_step * 1e-3) / 1e12,
+        "ttm_frac_of_mfma_peak": cfg.flops / (ms_step * 1e-3) / 1e12 / peak,
+        "kernel_ms": {"mode12": ms12, "mode3": ms3},
+        "operand_prep_ms": t_prep * 1e3,
+        "roofline": {"bound": "mfma", "kernel": "k_mode12", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
+                     "frac": achieved / peak, "traffic": None},
+    }
+    if cfg.materialised:
+        out["hbm_algorithmic_gbps"] = cfg.elements * (2 if cfg.dtype == "bf16" else 4) / (ms12 * 1e-3) / 1e9
+    if args.check:
+        import oracle
+        import gpu_util as gu
+        reps = [0, cfg.P - 1]
+        Yg = gu.y_to_numpy(Y, cfg)[..., reps]
+        if cfg.materialised and cfg.elements <= 2e9:
+            Xh = X.float().cpu().numpy().reshape((cfg.I, cfg.J, cfg.K), order="F")
+            Yo = oracle.comp_multi(Xh, U, V, W, cfg.P, replicas=reps)
+            out["check"] = {"replicas": reps, "rel_fro_vs_oracle": oracle.rel_fro(Yg, Yo)}
+        else:
+            Yc = oracle.closed_form_multi(A, B, C, U, V, W, cfg.P, replicas=reps)
+            out["check"] = {"replicas": reps, "rel_fro_vs_noiseless_closed_form": oracle.rel_fro(Yg, Yc)}
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, A, B, C, U, V, W)
+    plan.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

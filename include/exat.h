@@ -141,6 +141,14 @@ int exat_compress_gen(exat_plan_t plan, const exat_gen_t *gen, const exat_box_t 
 int exat_gen_block(const exat_desc_t *desc, const exat_gen_t *gen, int32_t bi, int32_t bj, int32_t bk,
                    void *out, void *stream);
 
+/* Measurement aid (not part of the paper's method): with timing enabled, every compress
+ * call records HIP events on its stream around the fused mode-1/2 kernel and around the
+ * mode-3 kernel.  exat_plan_last_timing waits for the most recent call's events and returns
+ * the two kernel durations in milliseconds (the one call in this API that blocks).
+ * Errors: NULL, STATE (timing off or no call since it was enabled), HIP. */
+int exat_plan_set_timing(exat_plan_t plan, int enable);
+int exat_plan_last_timing(exat_plan_t plan, float *ms_mode12, float *ms_mode3);
+
 /* Static description of a status code (never NULL). */
 const char *exat_strerror(int status);
 

@@ -41,6 +41,11 @@ def lib():
     return _lib
 
 
+def num_threads():
+    """Threads the oracle's OpenMP loops use."""
+    return int(lib().orc_num_threads())
+
+
 def _f32c(a):
     a = np.ascontiguousarray(a, dtype=np.float32)
     return a, a.ctypes.data_as(_fp)

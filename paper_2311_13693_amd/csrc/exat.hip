@@ -26,7 +26,7 @@ struct KernelChoice { int rt, ct; };
 
 struct exat_plan_s {
     exat_desc_t d;
-    int PL, PLpad, Mpad, MT;
+    int PL, PLpad, Mpad, MT, Npad;
     int64_t Ipad, Jpad;
     void *Upack = nullptr;
     float *Vpack = nullptr, *Wpack = nullptr, *Q = nullptr;
@@ -38,6 +38,9 @@ struct exat_plan_s {
     int64_t nblocks = 0, ysize = 0;
     std::vector<unsigned char> submitted, slot_used;
     int64_t nsubmitted = 0;
+    // optional per-kernel timing
+    bool timing = false, timing_valid = false;
+    hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
 };
 
 namespace {
@@ -135,20 +138,27 @@ int run_chain(exat_plan_s *pl, Mode12Params mp, bool generated, float *Yout, int
     mp.G = (pl->PL + rows - 1) / rows;
     const int nk = (int)(mp.k1 - mp.k0);
     int rc;
+    if (pl->timing && hipEventRecord(pl->ev[0], st) != hipSuccess) return EXAT_ERR_HIP;
     if (pl->d.in_dtype == EXAT_BF16)
         rc = generated ? launch_mode12_bf16<SRC_GENERATED>(rt, mp, nk, st) : launch_mode12_bf16<SRC_MATERIALISED>(rt, mp, nk, st);
     else
         rc = generated ? launch_mode12_f32<SRC_GENERATED>(rt, mp, nk, st) : launch_mode12_f32<SRC_MATERIALISED>(rt, mp, nk, st);
     if (rc != EXAT_OK) return rc;
+    if (pl->timing && hipEventRecord(pl->ev[1], st) != hipSuccess) return EXAT_ERR_HIP;
     Mode3Params m3;
     m3.Q = pl->Q; m3.W = pl->Wpack; m3.Y = Yout;
     m3.L = pl->d.L; m3.M = pl->d.M; m3.N = pl->d.N; m3.PL = pl->PL; m3.PLpad = pl->PLpad; m3.Mpad = pl->Mpad;
+    m3.Npad = pl->Npad;
     m3.K = pl->d.K; m3.k0 = mp.k0; m3.k1 = mp.k1; m3.accumulate = accumulate;
-    constexpr int NT = 16;
-    const int64_t npos = (int64_t)pl->PL * pl->Mpad;
-    dim3 grid((unsigned)((npos + 255) / 256), (unsigned)((pl->d.N + NT - 1) / NT));
-    hipLaunchKernelGGL(k_mode3<NT>, grid, dim3(256), 0, st, m3);
-    return hipGetLastError() == hipSuccess ? EXAT_OK : EXAT_ERR_HIP;
+    const int64_t ntile = ((int64_t)pl->PL * pl->Mpad + 31) / 32;
+    dim3 grid((unsigned)((ntile + 3) / 4), (unsigned)((pl->Npad + 63) / 64));
+    hipLaunchKernelGGL(k_mode3, grid, dim3(256), 0, st, m3);
+    if (hipGetLastError() != hipSuccess) return EXAT_ERR_HIP;
+    if (pl->timing) {
+        if (hipEventRecord(pl->ev[2], st) != hipSuccess) return EXAT_ERR_HIP;
+        pl->timing_valid = true;
+    }
+    return EXAT_OK;
 }
 
 __global__ void k_set_flag(unsigned char *flags, int idx, unsigned char v) { flags[idx] = v; }
@@ -175,6 +185,7 @@ int exat_plan_create(exat_plan_t *plan, const exat_desc_t *desc)
     pl->PL = desc->P * desc->L;
     pl->MT = (desc->M + 31) / 32;
     pl->Mpad = 32 * pl->MT;
+    pl->Npad = 32 * ((desc->N + 31) / 32);
     pl->Ipad = ceil_to(desc->I, 32);
     pl->Jpad = ceil_to(desc->J, 256);
     // every kernel variant the plan may pick must find its row groups inside the padding
@@ -186,7 +197,7 @@ int exat_plan_create(exat_plan_t *plan, const exat_desc_t *desc)
     const size_t es = esize(desc->in_dtype);
     const size_t ub = (size_t)pl->PLpad * pl->Ipad * es;
     const size_t vb = (size_t)desc->P * pl->Mpad * pl->Jpad * 4;
-    const size_t wb = (size_t)desc->P * desc->N * desc->K * 4;
+    const size_t wb = (size_t)desc->P * desc->K * pl->Npad * 4;
     const size_t qb = (size_t)desc->K * pl->PLpad * pl->Mpad * 4;
     if (hipMalloc(&pl->Upack, ub) != hipSuccess || hipMalloc((void **)&pl->Vpack, vb) != hipSuccess ||
         hipMalloc((void **)&pl->Wpack, wb) != hipSuccess || hipMalloc((void **)&pl->Q, qb) != hipSuccess) {
@@ -205,6 +216,7 @@ int exat_plan_destroy(exat_plan_t pl)
     if (!pl) return EXAT_OK;
     (void)hipFree(pl->Upack); (void)hipFree(pl->Vpack); (void)hipFree(pl->Wpack); (void)hipFree(pl->Q);
     (void)hipFree(pl->slots); (void)hipFree(pl->used_dev);
+    for (hipEvent_t e : pl->ev) if (e) (void)hipEventDestroy(e);
     delete pl;
     return EXAT_OK;
 }
@@ -216,15 +228,15 @@ int exat_set_factors(exat_plan_t pl, const float *U, int64_t ldU, const float *V
     const exat_desc_t &d = pl->d;
     if (ldU < d.I || ldV < d.J || ldW < d.K) return EXAT_ERR_SHAPE;
     hipStream_t st = (hipStream_t)stream;
-    const int64_t nu = (int64_t)pl->PLpad * pl->Ipad, nv = (int64_t)d.P * pl->Mpad * pl->Jpad, nw = (int64_t)d.P * d.N * d.K;
+    const int64_t nu = (int64_t)pl->PLpad * pl->Ipad, nv = (int64_t)d.P * pl->Mpad * pl->Jpad, nw = (int64_t)d.P * d.K * pl->Npad;
     if (d.in_dtype == EXAT_BF16) {
         hipLaunchKernelGGL(k_pack_u<__bf16>, dim3(grid_for(nu)), dim3(256), 0, st, U, ldU, pl->PL, d.I, (__bf16 *)pl->Upack, pl->PLpad, pl->Ipad);
         hipLaunchKernelGGL(k_pack_v<__bf16>, dim3(grid_for(nv)), dim3(256), 0, st, V, ldV, d.P, d.M, d.J, pl->Vpack, pl->Mpad, pl->Jpad);
-        hipLaunchKernelGGL(k_pack_w<__bf16>, dim3(grid_for(nw)), dim3(256), 0, st, W, ldW, d.P * d.N, d.K, pl->Wpack);
+        hipLaunchKernelGGL(k_pack_w<__bf16>, dim3(grid_for(nw)), dim3(256), 0, st, W, ldW, d.P, d.N, d.K, pl->Wpack, pl->Npad);
     } else {
         hipLaunchKernelGGL(k_pack_u<float>, dim3(grid_for(nu)), dim3(256), 0, st, U, ldU, pl->PL, d.I, (float *)pl->Upack, pl->PLpad, pl->Ipad);
         hipLaunchKernelGGL(k_pack_v<float>, dim3(grid_for(nv)), dim3(256), 0, st, V, ldV, d.P, d.M, d.J, pl->Vpack, pl->Mpad, pl->Jpad);
-        hipLaunchKernelGGL(k_pack_w<float>, dim3(grid_for(nw)), dim3(256), 0, st, W, ldW, d.P * d.N, d.K, pl->Wpack);
+        hipLaunchKernelGGL(k_pack_w<float>, dim3(grid_for(nw)), dim3(256), 0, st, W, ldW, d.P, d.N, d.K, pl->Wpack, pl->Npad);
     }
     if (hipGetLastError() != hipSuccess) return EXAT_ERR_HIP;
     pl->factors_set = true;
@@ -259,6 +271,7 @@ int exat_compress_gen(exat_plan_t pl, const exat_gen_t *gen, const exat_box_t *b
     Mode12Params mp;
     memset(&mp, 0, sizeof(mp));
     mp.A = gen->A; mp.B = gen->B; mp.C = gen->C; mp.ldA = d.I; mp.ldB = d.J; mp.ldC = d.K; mp.R = gen->R;
+    mp.a_vec = (d.I % 4 == 0) && (((uintptr_t)gen->A & 15) == 0);
     mp.skey = seed_key(gen->seed);
     mp.amp2_ln2 = amp2_ln2_of(gen->sigma);
     mp.i0 = b.i0; mp.i1 = b.i1; mp.j0 = b.j0; mp.j1 = b.j1; mp.k0 = b.k0; mp.k1 = b.k1;
@@ -350,6 +363,28 @@ int exat_gen_block(const exat_desc_t *desc, const exat_gen_t *gen, int32_t bi, i
     else
         hipLaunchKernelGGL(k_gen_box<float>, dim3(grid_for(n)), dim3(256), 0, st, gp, (float *)out);
     return hipGetLastError() == hipSuccess ? EXAT_OK : EXAT_ERR_HIP;
+}
+
+int exat_plan_set_timing(exat_plan_t pl, int enable)
+{
+    if (!pl) return EXAT_ERR_NULL;
+    if (enable && !pl->ev[0]) {
+        for (hipEvent_t &e : pl->ev)
+            if (hipEventCreate(&e) != hipSuccess) return EXAT_ERR_HIP;
+    }
+    pl->timing = enable != 0;
+    pl->timing_valid = false;
+    return EXAT_OK;
+}
+
+int exat_plan_last_timing(exat_plan_t pl, float *ms_mode12, float *ms_mode3)
+{
+    if (!pl || !ms_mode12 || !ms_mode3) return EXAT_ERR_NULL;
+    if (!pl->timing || !pl->timing_valid) return EXAT_ERR_STATE;
+    if (hipEventSynchronize(pl->ev[2]) != hipSuccess) return EXAT_ERR_HIP;
+    if (hipEventElapsedTime(ms_mode12, pl->ev[0], pl->ev[1]) != hipSuccess) return EXAT_ERR_HIP;
+    if (hipEventElapsedTime(ms_mode3, pl->ev[1], pl->ev[2]) != hipSuccess) return EXAT_ERR_HIP;
+    return EXAT_OK;
 }
 
 const char *exat_strerror(int status)

@@ -33,58 +33,97 @@ __global__ void k_pack_v(const float *src, int64_t ld, int P, int M, int64_t J, 
     }
 }
 
-// Stacked fp32 W (P*N x K) -> dense fp32 [P*N][K], values rounded through T.
+// Stacked fp32 W (P*N x K) -> transposed fp32 [P][K][Npad] (n contiguous, zero padded), values
+// rounded through T: the layout the mode-3 MFMA reads its B operand from with coalesced loads.
 template <typename T>
-__global__ void k_pack_w(const float *src, int64_t ld, int rows, int64_t K, float *dst)
+__global__ void k_pack_w(const float *src, int64_t ld, int P, int N, int64_t K, float *dst, int Npad)
 {
-    const int64_t n = (int64_t)rows * K;
-    for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < n; idx += (int64_t)gridDim.x * blockDim.x) {
-        const int64_t r = idx / K, c = idx % K;
-        dst[idx] = round_through<T>(src[r * ld + c]);
+    const int64_t n_all = (int64_t)P * K * Npad;
+    for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < n_all; idx += (int64_t)gridDim.x * blockDim.x) {
+        const int n = (int)(idx % Npad);
+        const int64_t pk = idx / Npad, k = pk % K, pr = pk / K;
+        const float v = (n < N) ? src[(pr * N + n) * ld + k] : 0.0f;
+        dst[idx] = round_through<T>(v);
     }
 }
 
-// Mode 3: Y[p,l,m,n] (=|+=) sum_{k in [k0,k1)} W_p[n,k] Q[k-k0][p*L+l][m], accumulated in fp64
-// in ascending k.  One thread per (q, m) position and NT consecutive n.
+// Mode 3: Y[p,l,m,n] (=|+=) sum_{k in [k0,k1)} W_p[n,k] Q[k-k0][p*L+l][m].
+// One wave owns 32 consecutive (q, m) positions of one stacked row q (so one replica) and up
+// to 64 values of n; it runs fp32 MFMAs over k in ascending order, flushing the fp32 partial
+// sums into fp64 totals every KFLUSH values of k so that the summation error does not grow
+// with the extent of K.
 struct Mode3Params {
     const float *Q;  // [nk][PLpad][Mpad]
-    const float *W;  // [P*N][K]
-    float *Y;        // [P][N][M][L] i.e. Y[l + L*(m + M*(n + N*p))]
-    int L, M, N, PL, PLpad, Mpad;
+    const float *W;  // [P][K][Npad]
+    float *Y;        // Y[l + L*(m + M*(n + N*p))]
+    int L, M, N, PL, PLpad, Mpad, Npad;
     int64_t K, k0, k1;
     int accumulate;
 };
 
-template <int NT>
 __global__ __launch_bounds__(256) void k_mode3(const Mode3Params p)
 {
-    const int64_t pos = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    const int q = (int)(pos / p.Mpad), m = (int)(pos % p.Mpad);
-    if (q >= p.PL || m >= p.M) return;
+    constexpr int KFLUSH = 512;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, l32 = lane & 31, hi = lane >> 5;
+    const int64_t pos0 = ((int64_t)blockIdx.x * 4 + wave) * 32;
+    if (pos0 >= (int64_t)p.PL * p.Mpad) return;  // whole wave; the kernel has no barriers
+    const int q = (int)(pos0 / p.Mpad), m0 = (int)(pos0 % p.Mpad);
+    if (m0 >= p.M) return;                       // a tile made of padding columns only
     const int pr = q / p.L, l = q % p.L;
-    const int n0 = blockIdx.y * NT;
-    const float *wrow[NT];
-#pragma unroll
-    for (int n = 0; n < NT; n++) {
-        const int nn = (n0 + n < p.N) ? n0 + n : p.N - 1;
-        wrow[n] = p.W + ((int64_t)pr * p.N + nn) * p.K + p.k0;
-    }
-    double acc[NT];
-#pragma unroll
-    for (int n = 0; n < NT; n++) acc[n] = 0.0;
+    const int n0 = blockIdx.y * 64;
+    const int ntiles = (p.Npad - n0 >= 64) ? 2 : 1;
     const int64_t nk = p.k1 - p.k0, qs = (int64_t)p.PLpad * p.Mpad;
-    const float *qp = p.Q + (int64_t)q * p.Mpad + m;
-    for (int64_t kk = 0; kk < nk; kk++) {
-        const double qv = (double)qp[kk * qs];
+    const float *qp = p.Q + pos0 + l32;                                       // + kk*qs
+    const float *wp = p.W + ((int64_t)pr * p.K + p.k0) * p.Npad + n0 + l32;   // + kk*Npad (+32 for tile 1)
+    double tot[2][16];
 #pragma unroll
-        for (int n = 0; n < NT; n++) acc[n] = __builtin_fma((double)wrow[n][kk], qv, acc[n]);
+    for (int t = 0; t < 2; t++)
+#pragma unroll
+        for (int e = 0; e < 16; e++) tot[t][e] = 0.0;
+    for (int64_t kc = 0; kc < nk; kc += KFLUSH) {
+        f32x16 acc[2];
+#pragma unroll
+        for (int t = 0; t < 2; t++)
+#pragma unroll
+            for (int e = 0; e < 16; e++) acc[t][e] = 0.0f;
+        const int64_t kend = (kc + KFLUSH < nk) ? kc + KFLUSH : nk;
+        for (int64_t kk = kc; kk < kend; kk += 8) {
+            float a[4], b0[4], b1[4];
+#pragma unroll
+            for (int t = 0; t < 4; t++) {
+                const int64_t kx = kk + 2 * t + hi;
+                const bool ok = kx < kend;
+                a[t] = ok ? qp[kx * qs] : 0.0f;
+                b0[t] = ok ? wp[kx * p.Npad] : 0.0f;
+                b1[t] = (ok && ntiles == 2) ? wp[kx * p.Npad + 32] : 0.0f;
+            }
+#pragma unroll
+            for (int t = 0; t < 4; t++) {
+                acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[t], b0[t], acc[0], 0, 0, 0);
+                if (ntiles == 2) acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[t], b1[t], acc[1], 0, 0, 0);
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < 2; t++)
+#pragma unroll
+            for (int e = 0; e < 16; e++) tot[t][e] += (double)acc[t][e];
     }
+    // C layout: element 4b+r of the accumulator is row (position) 8b + 4*hi + r, column n = l32
 #pragma unroll
-    for (int n = 0; n < NT; n++) {
-        if (n0 + n < p.N) {
-            float *dst = p.Y + l + (int64_t)p.L * (m + (int64_t)p.M * (n0 + n + (int64_t)p.N * pr));
-            const float v = (float)acc[n];
-            *dst = p.accumulate ? *dst + v : v;
+    for (int t = 0; t < 2; t++) {
+        const int n = n0 + 32 * t + l32;
+        if (t < ntiles && n < p.N) {
+#pragma unroll
+            for (int b4 = 0; b4 < 4; b4++)
+#pragma unroll
+                for (int r = 0; r < 4; r++) {
+                    const int m = m0 + 8 * b4 + 4 * hi + r;
+                    if (m < p.M) {
+                        float *dst = p.Y + l + (int64_t)p.L * (m + (int64_t)p.M * (n + (int64_t)p.N * pr));
+                        const float v = (float)tot[t][4 * b4 + r];
+                        *dst = p.accumulate ? *dst + v : v;
+                    }
+                }
         }
     }
 }

@@ -29,7 +29,7 @@ struct Mode12Params {
     // generated source
     const float *A, *B, *C;
     int64_t ldA, ldB, ldC;
-    int R;
+    int R, a_vec;  // a_vec: 16-byte loads of A rows are aligned
     uint32_t skey;
     float amp2_ln2;  // -2 ln2 sigma^2, 0 when sigma == 0
     int64_t I, Ipad, Jpad;
@@ -72,6 +72,74 @@ struct Mode12Cfg {
     static constexpr int LDS_BYTES = STAGE_BYTES > EPI_BYTES ? STAGE_BYTES : EPI_BYTES;
 };
 
+// Slow, fully guarded staging of the X tile straight into LDS (box edges, unaligned tensors).
+template <typename T, int COLS, int ROWB>
+__device__ __forceinline__ void stage_x_guarded(const Mode12Params &p, unsigned char *Xs, int64_t ib, int64_t jc, int64_t k, int tid)
+{
+    const T *Xp = (const T *)p.X;
+    for (int pc = tid; pc < COLS * 32; pc += 256) {
+        const int c = pc >> 5, e = pc & 31;
+        const int64_t j = jc + c, i = ib + e;
+        T v = elem<T>::from_f32(0.0f);
+        if (j >= p.j0 && j < p.j1 && i >= p.i0 && i < p.i1)
+            v = Xp[(i - p.xo_i) + (j - p.xo_j) * p.x_sj + (k - p.xo_k) * p.x_sk];
+        ((T *)(Xs + c * ROWB))[e] = v;
+    }
+}
+
+// On-chip generation of 16 consecutive i of one fibre (j,k):
+//   X = sum_r A[i,r] B[j,r] C[k,r] + sigma g(seed;i,j,k), zero outside the box.
+// Indices are clamped for the loads and the result is masked, so there are no branches.
+template <bool TAIL>
+__device__ __forceinline__ void gen_run16(const Mode12Params &p, int64_t i, int64_t j, int64_t k, float x[16])
+{
+    const bool colok = (j >= p.j0) && (j < p.j1);
+    const int64_t jj = colok ? j : p.j0;
+#pragma unroll
+    for (int e = 0; e < 16; e++) x[e] = 0.0f;
+    const float *bp = p.B + jj, *cp = p.C + k;
+    if (!TAIL) {
+        const float *ap = p.A + i;
+        for (int r = 0; r < p.R; r++) {
+            const float bc = bp[p.ldB * r] * cp[p.ldC * r];
+            const f32x4 *a4 = (const f32x4 *)(ap + p.ldA * r);
+            if (p.a_vec) {
+#pragma unroll
+                for (int q = 0; q < 4; q++) {
+                    const f32x4 av = a4[q];
+#pragma unroll
+                    for (int e = 0; e < 4; e++) x[4 * q + e] = __builtin_fmaf(av[e], bc, x[4 * q + e]);
+                }
+            } else {
+#pragma unroll
+                for (int e = 0; e < 16; e++) x[e] = __builtin_fmaf(ap[p.ldA * r + e], bc, x[e]);
+            }
+        }
+    } else {
+        for (int r = 0; r < p.R; r++) {
+            const float bc = bp[p.ldB * r] * cp[p.ldC * r];
+#pragma unroll
+            for (int e = 0; e < 16; e++) {
+                const int64_t ii = (i + e < p.I) ? i + e : p.I - 1;
+                x[e] = __builtin_fmaf(p.A[ii + p.ldA * r], bc, x[e]);
+            }
+        }
+    }
+    if (p.amp2_ln2 != 0.0f) {
+        const uint32_t ck = fibre_key(p.skey, (uint32_t)jj, (uint32_t)k);
+#pragma unroll
+        for (int q = 0; q < 4; q++) {
+            float z[4];
+            noise_quad(ck, (uint32_t)(i >> 2) + q, p.amp2_ln2, z);
+#pragma unroll
+            for (int e = 0; e < 4; e++) x[4 * q + e] += z[e];
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < 16; e++)
+        if (!colok || i + e < p.i0 || i + e >= p.i1) x[e] = 0.0f;
+}
+
 template <typename T, int RT, int CT, int SRC>
 __global__ __launch_bounds__(256) void k_mode12(const Mode12Params p)
 {
@@ -79,6 +147,10 @@ __global__ __launch_bounds__(256) void k_mode12(const Mode12Params p)
     typedef typename mma_frag<T>::type frag_t;
     constexpr int ROWS = cfg::ROWS, COLS = cfg::COLS, EI = cfg::EI, E16 = cfg::E16, FPR = cfg::FPR,
                   ROWB = cfg::ROWB, ZST = cfg::ZST;
+    constexpr int UPT = ROWS * FPR / 256;  // 16-byte pieces of the U tile per thread
+    constexpr int XPT = COLS * FPR / 256;  // 16-byte pieces of the X tile per thread (materialised)
+    constexpr int GPT = COLS * 2 / 256;    // 16-element runs of the X tile per thread (generated)
+    static_assert(ROWS * FPR % 256 == 0 && COLS * FPR % 256 == 0 && COLS * 2 % 256 == 0, "tile/thread mismatch");
     extern __shared__ __align__(16) unsigned char smem[];
     unsigned char *Us = smem;
     unsigned char *Xs = smem + ROWS * ROWB;
@@ -96,7 +168,20 @@ __global__ __launch_bounds__(256) void k_mode12(const Mode12Params p)
     const int64_t ia0 = p.i0 & ~(int64_t)(EI - 1);
     const int nstage = (int)((p.i1 - ia0 + EI - 1) / EI);
     const int64_t ja0 = (p.j0 / COLS) * COLS;
-    const T *Up = (const T *)p.U;
+
+    // per-thread piece coordinates (tile row/column r, 16-byte fragment f); piece u is r + u*(256/FPR)
+    const int pr0 = tid / FPR, pf = tid % FPR;
+    const unsigned u_voff = (unsigned)pr0 * (unsigned)p.Ipad + (unsigned)pf * E16;  // elements, < 2^31 by the plan's limits
+    const unsigned u_vstep = (unsigned)(256 / FPR) * (unsigned)p.Ipad;
+    const T *Ug = (const T *)p.U + (int64_t)row0 * p.Ipad;  // + ib: uniform
+    unsigned char *us_w = Us + pr0 * ROWB + pf * 16;         // + u*(256/FPR)*ROWB
+    unsigned char *xs_w = Xs + pr0 * ROWB + pf * 16;
+    const unsigned char *us_r = Us + (wave * (RT * 32) + l32) * ROWB + hi * 16;  // + rt*32*ROWB + g2*32
+    const unsigned char *xs_r = Xs + l32 * ROWB + hi * 16;                       // + ct*32*ROWB + g2*32
+
+    u32x4 upre[UPT];               // next stage of U, in flight from global memory
+    u32x4 xpre[SRC == SRC_MATERIALISED ? XPT : 1];
+    float xgen[SRC == SRC_GENERATED ? GPT : 1][16];
 
     for (int64_t jc = ja0; jc < p.j1; jc += COLS) {
         f32x16 acc[RT][CT];
@@ -107,97 +192,91 @@ __global__ __launch_bounds__(256) void k_mode12(const Mode12Params p)
 #pragma unroll
                 for (int e = 0; e < 16; e++) acc[rt][ct][e] = 0.0f;
 
-        for (int s = 0; s < nstage; s++) {
+        const bool jfull = (jc >= p.j0) && (jc + COLS <= p.j1);
+        // materialised source: per-thread element offset of piece 0 of this chunk inside X
+        const int64_t x_off = (pf * E16 - p.xo_i) + (jc + pr0 - p.xo_j) * p.x_sj + (k - p.xo_k) * p.x_sk;
+        const int64_t x_step = (int64_t)(256 / FPR) * p.x_sj;
+
+        // a stage takes the fast path when the whole 32 x COLS tile lies inside the box
+        auto is_fast = [&](int s) -> bool {
             const int64_t ib = ia0 + (int64_t)s * EI;
-            __syncthreads();
-            // ---- stage the U tile: ROWS x EI, rows contiguous in i ----
-            for (int pc = tid; pc < ROWS * FPR; pc += 256) {
-                const int r = pc / FPR, f = pc % FPR;
-                const uint4 v = *(const uint4 *)(Up + (int64_t)(row0 + r) * p.Ipad + ib + f * E16);
-                *(uint4 *)(Us + r * ROWB + f * 16) = v;
-            }
-            // ---- stage the X tile: COLS fibres x EI ----
-            if (SRC == SRC_MATERIALISED) {
-                const T *Xp = (const T *)p.X;
-                for (int pc = tid; pc < COLS * FPR; pc += 256) {
-                    const int c = pc / FPR, f = pc % FPR;
-                    const int64_t j = jc + c, i = ib + f * E16;
-                    union { uint4 v; T e[E16]; } u;
-                    u.v = make_uint4(0, 0, 0, 0);
-                    if (j >= p.j0 && j < p.j1) {
-                        const T *src = Xp + (i - p.xo_i) + (j - p.xo_j) * p.x_sj + (k - p.xo_k) * p.x_sk;
-                        if (p.x_vec && i >= p.i0 && i + E16 <= p.i1) {
-                            u.v = *(const uint4 *)src;
-                        } else {
+            if (SRC == SRC_MATERIALISED) return p.x_vec && jfull && ib >= p.i0 && ib + EI <= p.i1;
+            return ib + EI <= p.I;
+        };
+        // fetches (or generates) the operands of stage s into registers
+        auto fetch = [&](int s) {
+            const int64_t ib = ia0 + (int64_t)s * EI;
+            const T *ub = Ug + ib;
 #pragma unroll
-                            for (int e = 0; e < E16; e++)
-                                if (i + e >= p.i0 && i + e < p.i1) u.e[e] = src[e];
-                        }
-                    }
-                    *(uint4 *)(Xs + c * ROWB + f * 16) = u.v;
+            for (int u = 0; u < UPT; u++) upre[u] = *(const u32x4 *)(ub + (u_voff + u * u_vstep));
+            if constexpr (SRC == SRC_MATERIALISED) {
+                if (is_fast(s)) {
+                    const T *xb = (const T *)p.X + ib;
+#pragma unroll
+                    for (int u = 0; u < XPT; u++) xpre[u] = *(const u32x4 *)(xb + (x_off + u * x_step));
                 }
             } else {
-                // on-chip generation: X = sum_r A[i,r] B[j,r] C[k,r] + sigma g(seed;i,j,k)
-                for (int pc = tid; pc < COLS * 2; pc += 256) {
-                    const int c = pc >> 1, h = pc & 1;
-                    const int64_t j = jc + c, i = ib + 16 * h;
-                    float x[16];
 #pragma unroll
-                    for (int e = 0; e < 16; e++) x[e] = 0.0f;
-                    if (j >= p.j0 && j < p.j1 && i < p.i1 && i + 16 > p.i0) {
-                        if (i + 16 <= p.I) {
-                            for (int r = 0; r < p.R; r++) {
-                                const float bc = p.B[j + p.ldB * r] * p.C[k + p.ldC * r];
-                                const float *a = p.A + i + p.ldA * r;
-#pragma unroll
-                                for (int e = 0; e < 16; e++) x[e] = __builtin_fmaf(a[e], bc, x[e]);
-                            }
-                        } else {
-                            for (int r = 0; r < p.R; r++) {
-                                const float bc = p.B[j + p.ldB * r] * p.C[k + p.ldC * r];
-                                const float *a = p.A + i + p.ldA * r;
-#pragma unroll
-                                for (int e = 0; e < 16; e++)
-                                    if (i + e < p.I) x[e] = __builtin_fmaf(a[e], bc, x[e]);
-                            }
-                        }
-                        if (p.amp2_ln2 != 0.0f) {
-                            const uint32_t ck = fibre_key(p.skey, (uint32_t)j, (uint32_t)k);
-#pragma unroll
-                            for (int q = 0; q < 4; q++) {
-                                float z[4];
-                                noise_quad(ck, (uint32_t)(i >> 2) + q, p.amp2_ln2, z);
-#pragma unroll
-                                for (int e = 0; e < 4; e++) x[4 * q + e] += z[e];
-                            }
-                        }
-#pragma unroll
-                        for (int e = 0; e < 16; e++)
-                            if (i + e < p.i0 || i + e >= p.i1) x[e] = 0.0f;
-                    }
-                    T *dst = (T *)(Xs + c * ROWB) + 16 * h;
-#pragma unroll
-                    for (int e = 0; e < 16; e++) dst[e] = elem<T>::from_f32(x[e]);
+                for (int u = 0; u < GPT; u++) {
+                    const int pc = tid + u * 256, c = pc >> 1, h = pc & 1;
+                    if (is_fast(s)) gen_run16<false>(p, ib + 16 * h, jc + c, k, xgen[u]);
+                    else gen_run16<true>(p, ib + 16 * h, jc + c, k, xgen[u]);
                 }
             }
+        };
+        // writes the fetched stage into the LDS tiles
+        auto commit = [&](int s) {
+#pragma unroll
+            for (int u = 0; u < UPT; u++) *(u32x4 *)(us_w + u * (256 / FPR) * ROWB) = upre[u];
+            if constexpr (SRC == SRC_MATERIALISED) {
+                if (is_fast(s)) {
+#pragma unroll
+                    for (int u = 0; u < XPT; u++) *(u32x4 *)(xs_w + u * (256 / FPR) * ROWB) = xpre[u];
+                } else {
+                    stage_x_guarded<T, COLS, ROWB>(p, Xs, ia0 + (int64_t)s * EI, jc, k, tid);
+                }
+            } else {
+#pragma unroll
+                for (int u = 0; u < GPT; u++) {
+                    const int pc = tid + u * 256, c = pc >> 1, h = pc & 1;
+                    T *dst = (T *)(Xs + c * ROWB) + 16 * h;
+#pragma unroll
+                    for (int e = 0; e < 16; e++) dst[e] = elem<T>::from_f32(xgen[u][e]);
+                }
+            }
+        };
+
+        fetch(0);
+        for (int s = 0; s < nstage; s++) {
+            __syncthreads();  // the previous stage's MFMAs (or the epilogue) are done with the LDS
+            commit(s);
             __syncthreads();
+            if (s + 1 < nstage) fetch(s + 1);  // in flight while the MFMAs below run
             // ---- mode-1 MFMAs on the staged tiles ----
             // Both operands use the same lane -> i assignment (fragment 2*g2 + hi of the row),
             // so the order in which the 32 i of the stage are consumed is irrelevant.
+            // Fragments are double-buffered in registers: the LDS reads of step g2+1 are issued
+            // before the MFMAs of step g2, and the scheduling barriers keep them from moving further.
+            frag_t a[2][RT], bx[2][CT];
+#pragma unroll
+            for (int rt = 0; rt < RT; rt++) a[0][rt] = *(const frag_t *)(us_r + rt * 32 * ROWB);
+#pragma unroll
+            for (int ct = 0; ct < CT; ct++) bx[0][ct] = *(const frag_t *)(xs_r + ct * 32 * ROWB);
 #pragma unroll
             for (int g2 = 0; g2 < FPR / 2; g2++) {
-                frag_t a[RT], bx[CT];
+                __builtin_amdgcn_sched_barrier(0);
+                if (g2 + 1 < FPR / 2) {
+#pragma unroll
+                    for (int rt = 0; rt < RT; rt++) a[(g2 + 1) & 1][rt] = *(const frag_t *)(us_r + rt * 32 * ROWB + (g2 + 1) * 32);
+#pragma unroll
+                    for (int ct = 0; ct < CT; ct++) bx[(g2 + 1) & 1][ct] = *(const frag_t *)(xs_r + ct * 32 * ROWB + (g2 + 1) * 32);
+                }
 #pragma unroll
                 for (int rt = 0; rt < RT; rt++)
-                    a[rt] = *(const frag_t *)(Us + (wave * (RT * 32) + rt * 32 + l32) * ROWB + (2 * g2 + hi) * 16);
 #pragma unroll
-                for (int ct = 0; ct < CT; ct++)
-                    bx[ct] = *(const frag_t *)(Xs + (ct * 32 + l32) * ROWB + (2 * g2 + hi) * 16);
-#pragma unroll
-                for (int rt = 0; rt < RT; rt++)
-#pragma unroll
-                    for (int ct = 0; ct < CT; ct++) mma_frag<T>::mma(acc[rt][ct], a[rt], bx[ct]);
+                    for (int ct = 0; ct < CT; ct++) mma_frag<T>::mma(acc[rt][ct], a[g2 & 1][rt], bx[g2 & 1][ct]);
             }
+            __builtin_amdgcn_sched_barrier(0);
         }
 
         // ---- mode 2 on the finished Z chunk ----

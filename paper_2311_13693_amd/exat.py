@@ -14,7 +14,8 @@ EXAT_F32, EXAT_BF16 = 0, 1
 OK, ERR_NULL, ERR_SHAPE, ERR_DTYPE, ERR_STATE, ERR_ALLOC, ERR_HIP = 0, -1, -2, -3, -4, -5, -6
 
 EXPORTS = ["exat_plan_create", "exat_plan_destroy", "exat_set_factors", "exat_compress",
-           "exat_compress_block", "exat_finalize", "exat_compress_gen", "exat_gen_block", "exat_strerror"]
+           "exat_compress_block", "exat_finalize", "exat_compress_gen", "exat_gen_block",
+           "exat_plan_set_timing", "exat_plan_last_timing", "exat_strerror"]
 
 
 class Desc(ctypes.Structure):
@@ -60,6 +61,8 @@ def lib():
         L.exat_finalize.argtypes = [vp, vp, vp]
         L.exat_compress_gen.argtypes = [vp, ctypes.POINTER(Gen), ctypes.POINTER(Box), vp, vp]
         L.exat_gen_block.argtypes = [ctypes.POINTER(Desc), ctypes.POINTER(Gen), i32, i32, i32, vp, vp]
+        L.exat_plan_set_timing.argtypes = [vp, ctypes.c_int]
+        L.exat_plan_last_timing.argtypes = [vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_float)]
         L.exat_strerror.argtypes = [ctypes.c_int]
         L.exat_strerror.restype = ctypes.c_char_p
         for name in EXPORTS[:-1]:
@@ -138,6 +141,15 @@ class Plan:
             assert t.is_cuda and t.dtype == torch.float32 and t.dim() == 2 and t.stride(1) == 1
         _check(lib().exat_set_factors(self._h, _ptr(U), U.stride(0), _ptr(V), V.stride(0), _ptr(W), W.stride(0),
                                       _stream_handle(stream)))
+
+    def set_timing(self, enable=True):
+        _check(lib().exat_plan_set_timing(self._h, 1 if enable else 0))
+
+    def last_timing(self):
+        """(ms of the fused mode-1/2 kernel, ms of the mode-3 kernel) of the most recent compress call."""
+        a, b = ctypes.c_float(), ctypes.c_float()
+        _check(lib().exat_plan_last_timing(self._h, ctypes.byref(a), ctypes.byref(b)))
+        return a.value, b.value
 
     def new_y(self):
         import torch
