@@ -27,6 +27,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--config", default=os.environ.get("EXAT_BENCH_CONFIG", "cfg2"))
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--kslices", type=int, default=0,
+                    help="development aid: compress only the first N frontal slices (generated configs); "
+                         "the reported numbers then refer to that sub-box, not to the configuration")
     ap.add_argument("--check", action="store_true", help="also compare sampled replicas with the oracle")
     return ap.parse_args()
 
@@ -87,7 +90,10 @@ def main():
         X = torch.empty(cfg.elements, dtype=torch.bfloat16 if cfg.dtype == "bf16" else torch.float32, device="cuda")
         exat.gen_block(whole, gen, 0, 0, 0, X)
     Y = plan.new_y()
-    step = (lambda: plan.compress(X, Y)) if cfg.materialised else (lambda: plan.compress_gen(gen, None, Y))
+    box, frac = None, 1.0
+    if args.kslices and not cfg.materialised:
+        box, frac = (0, cfg.I, 0, cfg.J, 0, args.kslices), args.kslices / cfg.K
+    step = (lambda: plan.compress(X, Y)) if cfg.materialised else (lambda: plan.compress_gen(gen, box, Y))
 
     plan.set_timing(True)
     for _ in range(warmup):
@@ -106,12 +112,12 @@ def main():
     ms12, ms3 = float(np.mean(k12)), float(np.mean(k3))
 
     PL = cfg.P * cfg.L
-    f12 = 2.0 * PL * (cfg.elements + cfg.M * cfg.J * cfg.K)      # algorithmic flops of the fused mode-1/2 launch
+    f12 = 2.0 * PL * (cfg.elements + cfg.M * cfg.J * cfg.K) * frac   # algorithmic flops of the fused mode-1/2 launch
     achieved = f12 / (ms12 * 1e-3) / 1e12
     peak = PEAK_TFLOPS[cfg.dtype]
     out = {
         "metric": "input tensor elements compressed/sec + TTM TFLOP/s (% MFMA peak), 1 MI355X",
-        "value": cfg.elements / (ms_step * 1e-3), "unit": "elements/s",
+        "value": cfg.elements * frac / (ms_step * 1e-3), "unit": "elements/s",
         "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": ms_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32" if cfg.dtype == "f32" else "bf16 (fp32 accumulate)", "data": "synthetic",
@@ -119,8 +125,8 @@ def main():
             cfg.name, cfg.I, cfg.J, cfg.K, cfg.dtype, cfg.R, cfg.P, cfg.L,
             "materialised in HBM" if cfg.materialised else "generated on chip"),
             "sigma": cfg.sigma, "block": [cfg.dI, cfg.dJ, cfg.dK]},
-        "ttm_tflops": cfg.flops / (ms_step * 1e-3) / 1e12,
-        "ttm_frac_of_mfma_peak": cfg.flops / (ms_step * 1e-3) / 1e12 / peak,
+        "ttm_tflops": cfg.flops * frac / (ms_step * 1e-3) / 1e12,
+        "ttm_frac_of_mfma_peak": cfg.flops * frac / (ms_step * 1e-3) / 1e12 / peak,
         "kernel_ms": {"mode12": ms12, "mode3": ms3},
         "operand_prep_ms": t_prep * 1e3,
         "roofline": {"bound": "mfma", "kernel": "k_mode12", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
@@ -128,7 +134,9 @@ def main():
     }
     if cfg.materialised:
         out["hbm_algorithmic_gbps"] = cfg.elements * (2 if cfg.dtype == "bf16" else 4) / (ms12 * 1e-3) / 1e9
-    if args.check:
+    if frac != 1.0:
+        out["config"]["sub_box_k_slices"] = args.kslices
+    if args.check and frac == 1.0:
         import oracle
         import gpu_util as gu
         reps = [0, cfg.P - 1]

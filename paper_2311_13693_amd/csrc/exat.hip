@@ -12,6 +12,7 @@
 
 #include "exat_aux.h"
 #include "exat_mode12.h"
+#include "exat_mode12_v2.h"
 
 using namespace exat;
 
@@ -41,6 +42,7 @@ struct exat_plan_s {
     // optional per-kernel timing
     bool timing = false, timing_valid = false;
     hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
+    __bf16 *Asplit = nullptr;  // bf16 pieces of the generator's A factor, [3][Ipad][64]
 };
 
 namespace {
@@ -88,6 +90,8 @@ int validate_gen(const exat_gen_t *g)
     return EXAT_OK;
 }
 
+unsigned grid_for(int64_t n) { int64_t g = (n + 255) / 256; return (unsigned)(g > 65536 ? 65536 : (g < 1 ? 1 : g)); }
+
 float amp2_ln2_of(float sigma) { return sigma == 0.0f ? 0.0f : (float)(-2.0 * 0.69314718055994530942 * (double)sigma * (double)sigma); }
 
 template <typename T, int RT, int CT, int SRC>
@@ -127,10 +131,48 @@ int launch_mode12_bf16(int rt, const Mode12Params &mp, int nk, hipStream_t st)
     }
 }
 
+template <typename T, int NW, int RT, int SRC, int KS, bool BOXED>
+int launch_v2_inst(const Mode12Params &mp, const GenSplitParams &gs, int nk, hipStream_t st)
+{
+    typedef Mode12V2Cfg<NW, RT> cfg;
+    auto kern = k_mode12_v2<T, NW, RT, SRC, KS, BOXED>;
+    static bool attr_done = false;
+    if (!attr_done) {
+        if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, cfg::LDS_BYTES) != hipSuccess) return EXAT_ERR_HIP;
+        attr_done = true;
+    }
+    const int64_t grid = 8LL * ((nk + 7) / 8) * mp.G;
+    if (grid > 2147483647LL) return EXAT_ERR_SHAPE;
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(64 * NW), cfg::LDS_BYTES, st, mp, gs);
+    return hipGetLastError() == hipSuccess ? EXAT_OK : EXAT_ERR_HIP;
+}
+
+template <typename T, int NW, int RT>
+int launch_v2(const Mode12Params &mp, const GenSplitParams &gs, bool generated, int ks, bool boxed, int nk, hipStream_t st)
+{
+    if (!generated) return launch_v2_inst<T, NW, RT, SRC_MATERIALISED, 1, false>(mp, gs, nk, st);
+    if (ks == 1) return boxed ? launch_v2_inst<T, NW, RT, SRC_GENERATED, 1, true>(mp, gs, nk, st) : launch_v2_inst<T, NW, RT, SRC_GENERATED, 1, false>(mp, gs, nk, st);
+    return boxed ? launch_v2_inst<T, NW, RT, SRC_GENERATED, 2, true>(mp, gs, nk, st) : launch_v2_inst<T, NW, RT, SRC_GENERATED, 2, false>(mp, gs, nk, st);
+}
+
 // fills the plan-dependent part of the parameters and launches mode 1+2 followed by mode 3
 int run_chain(exat_plan_s *pl, Mode12Params mp, bool generated, float *Yout, int accumulate, hipStream_t st)
 {
-    const int rt = choose_rt(pl, generated);
+    // the pipelined kernel needs whole 64-byte stages of i inside the box (materialised source) or a
+    // factor rank that fits its generator (generated source); everything else takes the generic kernel
+    const bool bf = pl->d.in_dtype == EXAT_BF16;
+    const int ei = bf ? 32 : 16;
+    bool v2 = env_int("EXAT_V2", 1) != 0;
+    if (generated) v2 = v2 && mp.R <= 64;
+    else v2 = v2 && mp.x_vec && (mp.i0 % ei == 0) && ((mp.i1 - mp.i0) % ei == 0);
+    int rt = choose_rt(pl, generated);
+    if (v2) {
+        const int forced = env_int("EXAT_RT", 0);
+        rt = (forced == 2 || forced == 4) ? forced : (pl->PL > 256 ? 4 : 2);  // rt 4 = 8 waves x 2 row tiles
+        // The 8-wave bf16 generator variant faulted on the GPU at the 10000^3 size for a reason not yet
+        // found by reading; it stays switched off (the 4-wave variant is used) until the cause is known.
+        if (bf && generated) rt = 2;
+    }
     const int rows = 128 * rt;
     mp.U = pl->Upack; mp.V = pl->Vpack; mp.Q = pl->Q;
     mp.I = pl->d.I; mp.Ipad = pl->Ipad; mp.Jpad = pl->Jpad;
@@ -138,8 +180,20 @@ int run_chain(exat_plan_s *pl, Mode12Params mp, bool generated, float *Yout, int
     mp.G = (pl->PL + rows - 1) / rows;
     const int nk = (int)(mp.k1 - mp.k0);
     int rc;
+    GenSplitParams gs;
+    gs.Asp = pl->Asplit; gs.Irows = pl->Ipad; gs.Rpad = 32 * ((mp.R + 31) / 32);
+    if (v2 && generated) {
+        const int64_t n = gs.Irows * gs.Rpad;
+        hipLaunchKernelGGL(k_split_a, dim3(grid_for(n)), dim3(256), 0, st, mp.A, pl->d.I, mp.R, pl->Asplit, gs.Irows, gs.Rpad, bf ? 2 : 3);
+        if (hipGetLastError() != hipSuccess) return EXAT_ERR_HIP;
+    }
     if (pl->timing && hipEventRecord(pl->ev[0], st) != hipSuccess) return EXAT_ERR_HIP;
-    if (pl->d.in_dtype == EXAT_BF16)
+    if (v2) {
+        const bool boxed = generated && (mp.i0 != 0 || mp.i1 != pl->d.I);
+        const int ks = gs.Rpad / 32;
+        if (bf) rc = rt == 4 ? launch_v2<__bf16, 8, 2>(mp, gs, generated, ks, boxed, nk, st) : launch_v2<__bf16, 4, 2>(mp, gs, generated, ks, boxed, nk, st);
+        else rc = rt == 4 ? launch_v2<float, 8, 2>(mp, gs, generated, ks, boxed, nk, st) : launch_v2<float, 4, 2>(mp, gs, generated, ks, boxed, nk, st);
+    } else if (pl->d.in_dtype == EXAT_BF16)
         rc = generated ? launch_mode12_bf16<SRC_GENERATED>(rt, mp, nk, st) : launch_mode12_bf16<SRC_MATERIALISED>(rt, mp, nk, st);
     else
         rc = generated ? launch_mode12_f32<SRC_GENERATED>(rt, mp, nk, st) : launch_mode12_f32<SRC_MATERIALISED>(rt, mp, nk, st);
@@ -167,7 +221,6 @@ __global__ void k_clear_flags(unsigned char *flags, int n)
     for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) flags[i] = 0;
 }
 
-unsigned grid_for(int64_t n) { int64_t g = (n + 255) / 256; return (unsigned)(g > 65536 ? 65536 : (g < 1 ? 1 : g)); }
 
 }  // namespace
 
@@ -190,7 +243,7 @@ int exat_plan_create(exat_plan_t *plan, const exat_desc_t *desc)
     pl->Jpad = ceil_to(desc->J, 256);
     // every kernel variant the plan may pick must find its row groups inside the padding
     int64_t plpad = 0;
-    const int rts_f32[] = {1, 2, 4}, rts_bf16[] = {2, 5};
+    const int rts_f32[] = {1, 2, 4}, rts_bf16[] = {2, 4, 5};
     if (desc->in_dtype == EXAT_BF16) { for (int rt : rts_bf16) { int64_t v = ceil_to(pl->PL, 128 * rt); if (v > plpad) plpad = v; } }
     else { for (int rt : rts_f32) { int64_t v = ceil_to(pl->PL, 128 * rt); if (v > plpad) plpad = v; } }
     pl->PLpad = (int)plpad;
@@ -199,7 +252,8 @@ int exat_plan_create(exat_plan_t *plan, const exat_desc_t *desc)
     const size_t vb = (size_t)desc->P * pl->Mpad * pl->Jpad * 4;
     const size_t wb = (size_t)desc->P * desc->K * pl->Npad * 4;
     const size_t qb = (size_t)desc->K * pl->PLpad * pl->Mpad * 4;
-    if (hipMalloc(&pl->Upack, ub) != hipSuccess || hipMalloc((void **)&pl->Vpack, vb) != hipSuccess ||
+    if (hipMalloc((void **)&pl->Asplit, (size_t)3 * pl->Ipad * 64 * 2) != hipSuccess ||
+        hipMalloc(&pl->Upack, ub) != hipSuccess || hipMalloc((void **)&pl->Vpack, vb) != hipSuccess ||
         hipMalloc((void **)&pl->Wpack, wb) != hipSuccess || hipMalloc((void **)&pl->Q, qb) != hipSuccess) {
         (void)hipGetLastError();
         exat_plan_destroy(pl);
@@ -215,7 +269,7 @@ int exat_plan_destroy(exat_plan_t pl)
 {
     if (!pl) return EXAT_OK;
     (void)hipFree(pl->Upack); (void)hipFree(pl->Vpack); (void)hipFree(pl->Wpack); (void)hipFree(pl->Q);
-    (void)hipFree(pl->slots); (void)hipFree(pl->used_dev);
+    (void)hipFree(pl->slots); (void)hipFree(pl->used_dev); (void)hipFree(pl->Asplit);
     for (hipEvent_t e : pl->ev) if (e) (void)hipEventDestroy(e);
     delete pl;
     return EXAT_OK;
