@@ -1,0 +1,210 @@
+"""GPU parity at the five benchmark configurations, in the launch configuration bench.py times.
+
+cfg1-cfg3 (materialised): full or replica-sampled comparison with the CPU oracle on the same
+seeded tensor.  cfg4-cfg5 (never materialised; 5.7e14 / 4.8e15 flop would take the oracle
+hours): (i) sigma=0 full run against the closed form for exactly low-rank input, (ii) sampled
+tiles with noise against the oracle on exactly those tiles, (iii) the full noisy run against
+closed form + the exact expectation of the noise energy, (iv) scaled-down twins with the same
+awkward sizes against the full oracle.
+"""
+import os
+import sys
+import time
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2311_13693_amd import exat, workloads as wl
+
+sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
+import gpu_util as gu  # noqa: E402
+
+pytestmark = pytest.mark.gpu
+TOL = {"f32": 1e-5, "bf16": 2e-2}
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+@pytest.fixture(autouse=True)
+def _announce(request):
+    _say("[case] " + request.node.nodeid)
+    for v in ("EXAT_RT", "EXAT_V2"):
+        os.environ.pop(v, None)
+    yield
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+
+
+def _inputs(cfg):
+    A, B, C = wl.cp_factors(cfg)
+    U, V, W = wl.compression_matrices(cfg)
+    return A, B, C, U, V, W
+
+
+def _noise_energy(cfg, U, V, W, reps):
+    out = []
+    for p in reps:
+        out.append(cfg.sigma ** 2 *
+                   (U[p * cfg.L:(p + 1) * cfg.L].astype(np.float64) ** 2).sum() *
+                   (V[p * cfg.M:(p + 1) * cfg.M].astype(np.float64) ** 2).sum() *
+                   (W[p * cfg.N:(p + 1) * cfg.N].astype(np.float64) ** 2).sum())
+    return np.array(out)
+
+
+def test_cfg2_full_parity_materialised_generated_and_block_streamed():
+    cfg = wl.CONFIGS["cfg2"]
+    A, B, C, U, V, W = _inputs(cfg)
+    t0 = time.time()
+    X = oracle.gen_box(A, B, C, cfg.seed, cfg.sigma)
+    Yo = oracle.comp_multi(X, U, V, W, cfg.P)
+    _say("  oracle: %.1f s" % (time.time() - t0))
+    plan = gu.plan_with_factors(cfg, U, V, W)
+    Xd = gu.to_dev_x(X)
+    e1 = oracle.rel_fro(gu.y_to_numpy(plan.compress(Xd), cfg), Yo)
+    e2 = oracle.rel_fro(gu.y_to_numpy(plan.compress_gen(gu.gen_of(cfg, A, B, C)), cfg), Yo)
+    # streamed in 128^3 blocks, as the configuration states
+    Xv = Xd.view(cfg.K, cfg.J, cfg.I)
+    d = cfg.dI
+    for bk in range(cfg.K // d):
+        for bj in range(cfg.J // d):
+            for bi in range(cfg.I // d):
+                blk = Xv[bk * d:(bk + 1) * d, bj * d:(bj + 1) * d, bi * d:(bi + 1) * d].contiguous()
+                plan.compress_block(blk, bi, bj, bk)
+    e3 = oracle.rel_fro(gu.y_to_numpy(plan.finalize(), cfg), Yo)
+    _say("  cfg2 rel_fro: materialised %.3e, generated on chip %.3e, block-streamed %.3e" % (e1, e2, e3))
+    assert max(e1, e2, e3) <= TOL["f32"]
+    plan.close()
+
+
+def test_cfg3_replica_sampled_parity_and_noise_energy():
+    cfg = wl.CONFIGS["cfg3"]
+    A, B, C, U, V, W = _inputs(cfg)
+    t0 = time.time()
+    X = oracle.gen_box(A, B, C, cfg.seed, cfg.sigma)
+    _say("  oracle tensor: %.1f s" % (time.time() - t0))
+    plan = gu.plan_with_factors(cfg, U, V, W)
+    Xd = gu.to_dev_x(X)
+    Y = gu.y_to_numpy(plan.compress(Xd), cfg)
+    # the library's own generator produces the same tensor (sampled slab)
+    Xg = torch.empty(cfg.elements, dtype=torch.float32, device="cuda")
+    whole = exat.make_desc(cfg.I, cfg.J, cfg.K, cfg.L, cfg.M, cfg.N, cfg.P, cfg.I, cfg.J, cfg.K)
+    exat.gen_block(whole, gu.gen_of(cfg, A, B, C), 0, 0, 0, Xg)
+    dmax = float((Xg[: 1 << 26] - Xd[: 1 << 26]).abs().max())
+    _say("  max|X_gpu - X_oracle| on the first 2^26 elements: %.3e" % dmax)
+    assert dmax <= 2e-6 * (1.0 + float(Xd[: 1 << 26].abs().max()))
+    del Xg, Xd
+    reps = [0, 13, 31]
+    t0 = time.time()
+    Yo = oracle.comp_multi(X, U, V, W, cfg.P, replicas=reps)
+    _say("  oracle, %d replicas: %.1f s" % (len(reps), time.time() - t0))
+    err = oracle.rel_fro(Y[..., reps], Yo)
+    _say("  cfg3 rel_fro on replicas %s: %.3e" % (reps, err))
+    assert err <= TOL["f32"]
+    # all replicas: distance to the noiseless closed form is the compressed noise, whose energy is known
+    Yc = oracle.closed_form_multi(A, B, C, U, V, W, cfg.P)
+    got = ((Y - Yc) ** 2).sum(axis=(0, 1, 2))
+    want = _noise_energy(cfg, U, V, W, range(cfg.P))
+    ratio = got / want
+    _say("  noise energy ratio: min %.4f max %.4f" % (ratio.min(), ratio.max()))
+    assert np.all(np.abs(ratio - 1.0) <= 0.02)
+    plan.close()
+
+
+def _sample_boxes(cfg, n_random=4, seed=7):
+    nb = (cfg.I // cfg.dI, cfg.J // cfg.dJ, cfg.K // cfg.dK)
+    picks = [(0, 0, 0), (nb[0] - 1, nb[1] - 1, nb[2] - 1), (nb[0] // 2, nb[1] // 2, nb[2] // 2), (0, nb[1] - 1, nb[2] // 3)]
+    rng = np.random.default_rng(seed)
+    while len(picks) < 4 + n_random:
+        c = tuple(int(rng.integers(0, n)) for n in nb)
+        if c not in picks:
+            picks.append(c)
+    return [(bi * cfg.dI, (bi + 1) * cfg.dI, bj * cfg.dJ, (bj + 1) * cfg.dJ, bk * cfg.dK, (bk + 1) * cfg.dK)
+            for bi, bj, bk in picks]
+
+
+@pytest.mark.parametrize("name", ["cfg4", "cfg5"])
+def test_generated_config_sampled_tiles_against_oracle(name):
+    cfg = wl.CONFIGS[name]
+    A, B, C, U, V, W = _inputs(cfg)
+    plan = gu.plan_with_factors(cfg, U, V, W)
+    gen = gu.gen_of(cfg, A, B, C)
+    reps = [0, cfg.P // 2, cfg.P - 1]
+    rb = oracle.round_bf16
+    worst, worst_r = 0.0, 0.0
+    for box in _sample_boxes(cfg):
+        Yb = gu.y_to_numpy(plan.compress_gen(gen, box), cfg)[..., reps]
+        Xb = oracle.gen_box(A, B, C, cfg.seed, cfg.sigma, box)
+        Yo = oracle.comp_box(Xb, U, V, W, cfg.P, box, replicas=reps)
+        e = oracle.rel_fro(Yb, Yo)
+        worst = max(worst, e)
+        msg = "  %s tile %s: rel_fro %.3e" % (name, box, e)
+        if cfg.dtype == "bf16":
+            Xr = oracle.gen_box(A, B, C, cfg.seed, cfg.sigma, box, to_bf16=True)
+            Yr = oracle.comp_box(Xr, rb(U), rb(V), rb(W), cfg.P, box, replicas=reps)
+            er = oracle.rel_fro(Yb, Yr)
+            worst_r = max(worst_r, er)
+            msg += ", vs oracle on bf16-rounded inputs %.3e" % er
+        _say(msg)
+    assert worst <= TOL[cfg.dtype]
+    if cfg.dtype == "bf16":
+        assert worst_r <= 1e-3
+    plan.close()
+
+
+@pytest.mark.parametrize("name", ["cfg4", "cfg5"])
+def test_generated_config_full_runs_against_closed_form(name):
+    cfg = wl.CONFIGS[name]
+    A, B, C, U, V, W = _inputs(cfg)
+    plan = gu.plan_with_factors(cfg, U, V, W)
+    Yc = oracle.closed_form_multi(A, B, C, U, V, W, cfg.P)
+    t0 = time.time()
+    Y0 = gu.y_to_numpy(plan.compress_gen(gu.gen_of(cfg, A, B, C, sigma=0.0)), cfg)
+    _say("  %s full noiseless run: %.1f s" % (name, time.time() - t0))
+    e0 = oracle.rel_fro(Y0, Yc)
+    _say("  %s sigma=0: rel_fro vs closed form %.3e" % (name, e0))
+    assert e0 <= TOL[cfg.dtype]
+    t0 = time.time()
+    Y1 = gu.y_to_numpy(plan.compress_gen(gu.gen_of(cfg, A, B, C)), cfg)
+    _say("  %s full noisy run: %.1f s" % (name, time.time() - t0))
+    e1 = oracle.rel_fro(Y1, Yc)
+    _say("  %s sigma=%.2g: rel_fro vs closed form %.3e" % (name, cfg.sigma, e1))
+    assert e1 <= TOL[cfg.dtype] + 3e-3      # noise is ~1.2e-3 (cfg4) / ~1.8e-3 (cfg5) of ||Y||
+    if cfg.dtype == "f32":
+        ratio = ((Y1 - Yc) ** 2).sum(axis=(0, 1, 2)) / _noise_energy(cfg, U, V, W, range(cfg.P))
+        _say("  noise energy ratio: min %.4f max %.4f" % (ratio.min(), ratio.max()))
+        assert np.all(np.abs(ratio - 1.0) <= 0.02)
+    else:
+        # bf16: the noise must still be there on top of the quantisation error
+        assert ((Y1 - Y0) ** 2).sum() > 0.25 * _noise_energy(cfg, U, V, W, range(cfg.P)).sum()
+    plan.close()
+
+
+@pytest.mark.parametrize("name,nrep", [("cfg4_twin", 6), ("cfg5_twin", 48)])
+def test_scaled_down_twins_against_full_oracle(name, nrep):
+    cfg = wl.CONFIGS[name]
+    A, B, C, U, V, W = _inputs(cfg)
+    plan = gu.plan_with_factors(cfg, U, V, W)
+    Y = gu.y_to_numpy(plan.compress_gen(gu.gen_of(cfg, A, B, C)), cfg)
+    reps = list(range(cfg.P)) if nrep >= cfg.P else [int(r) for r in np.linspace(0, cfg.P - 1, nrep)]
+    X = oracle.gen_box(A, B, C, cfg.seed, cfg.sigma)
+    t0 = time.time()
+    Yo = oracle.comp_multi(X, U, V, W, cfg.P, replicas=reps)
+    _say("  oracle on %d replicas: %.1f s" % (len(reps), time.time() - t0))
+    e = oracle.rel_fro(Y[..., reps], Yo)
+    _say("  %s rel_fro %.3e" % (name, e))
+    assert e <= TOL[cfg.dtype]
+    # merge of per-tile results (Fig. 2a) equals the one-shot result
+    acc = np.zeros_like(Y)
+    gen = gu.gen_of(cfg, A, B, C)
+    for i0 in range(0, cfg.I, cfg.dI):
+        for j0 in range(0, cfg.J, cfg.dJ):
+            for k0 in range(0, cfg.K, cfg.dK):
+                acc += gu.y_to_numpy(plan.compress_gen(gen, (i0, i0 + cfg.dI, j0, j0 + cfg.dJ, k0, k0 + cfg.dK)), cfg)
+    em = oracle.rel_fro(acc, Y)
+    _say("  %s sum of tiles vs one shot: %.3e" % (name, em))
+    assert em <= (1e-3 if cfg.dtype == "bf16" else 2e-6)
+    plan.close()
