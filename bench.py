@@ -27,6 +27,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--config", default=os.environ.get("EXAT_BENCH_CONFIG", "cfg2"))
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="after the timed region, run one plain 256 MiB device copy (a kernel of known traffic "
+                         "that calibrates the FETCH_SIZE / WRITE_SIZE counters in a rocprofv3 --pmc run)")
     ap.add_argument("--kslices", type=int, default=0,
                     help="development aid: compress only the first N frontal slices (generated configs); "
                          "the reported numbers then refer to that sub-box, not to the configuration")
@@ -34,28 +37,39 @@ def parse():
     return ap.parse_args()
 
 
-def cpu_baseline(cfg, A, B, C, U, V, W, budget_s=20.0):
-    """Times the oracle as it stands on a bounded sample of the workload: the triple-loop chain for a few
-    replicas on one block of X (the same block-wise operation the full run repeats), scaled to the
-    whole tensor and all P replicas."""
+def cpu_baseline(cfg, A, B, C, U, V, W, budget_s=15.0):
+    """Times the oracle as it stands on a bounded sample of the workload: (block, replica) units of the
+    configuration's own block decomposition (Sec. 4.3), taken in order until the time budget is spent
+    (or everything is done), then scaled by units_total / units_done."""
     import oracle
-    # sample block: the configuration's own block, shrunk until one replica costs about a second
-    di, dj, dk = min(cfg.dI, cfg.I), min(cfg.dJ, cfg.J), min(cfg.dK, cfg.K)
-    box = (0, di, 0, dj, 0, dk)
-    Xb = oracle.gen_box(A, B, C, cfg.seed, cfg.sigma, box)
-    reps, t_total = 0, 0.0
-    while reps < cfg.P and (t_total < budget_s / 2 or reps < 1):
-        t0 = time.perf_counter()
-        oracle.comp_box(Xb, U, V, W, cfg.P, box, replicas=[reps])
-        t_total += time.perf_counter() - t0
-        reps += 1
-    per_rep_block = t_total / reps
-    nblocks = (cfg.I // di) * (cfg.J // dj) * (cfg.K // dk)
-    t_full = per_rep_block * cfg.P * nblocks
+    nb = (cfg.I // cfg.dI, cfg.J // cfg.dJ, cfg.K // cfg.dK)
+    units_total = nb[0] * nb[1] * nb[2] * cfg.P
+    done, t_gen, t_comp = 0, 0.0, 0.0
+    for bk in range(nb[2]):
+        for bj in range(nb[1]):
+            for bi in range(nb[0]):
+                box = (bi * cfg.dI, (bi + 1) * cfg.dI, bj * cfg.dJ, (bj + 1) * cfg.dJ, bk * cfg.dK, (bk + 1) * cfg.dK)
+                t0 = time.perf_counter()
+                Xb = oracle.gen_box(A, B, C, cfg.seed, cfg.sigma, box)     # input preparation, not counted
+                t_gen += time.perf_counter() - t0
+                for p in range(cfg.P):
+                    t0 = time.perf_counter()
+                    oracle.comp_box(Xb, U, V, W, cfg.P, box, replicas=[p])
+                    t_comp += time.perf_counter() - t0
+                    done += 1
+                    if t_comp >= budget_s:
+                        break
+                if t_comp >= budget_s or t_gen >= 2 * budget_s:
+                    break
+            if t_comp >= budget_s or t_gen >= 2 * budget_s:
+                break
+        if t_comp >= budget_s or t_gen >= 2 * budget_s:
+            break
+    t_full = t_comp * units_total / done
     return {"value": cfg.elements / t_full, "unit": "elements/s", "cores": oracle.num_threads(), "kind": "oracle",
-            "sample": "%d replica(s) of %d on one %dx%dx%d block, extrapolated x%d replicas x %d blocks"
-                      % (reps, cfg.P, di, dj, dk, cfg.P, nblocks),
-            "seconds_measured": round(t_total, 3), "seconds_full_extrapolated": t_full}
+            "sample": "%d of %d (block %dx%dx%d, replica) units of the same workload, %.1f s measured, scaled to all units"
+                      % (done, units_total, cfg.dI, cfg.dJ, cfg.dK, t_comp),
+            "seconds_full": t_full, "extrapolated": done < units_total}
 
 
 def main():
@@ -108,6 +122,11 @@ def main():
         k12.append(a); k3.append(b)
     e1.record()
     torch.cuda.synchronize()
+    if args.calib_copy:
+        src = torch.ones(64 << 20, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
     ms_step = e0.elapsed_time(e1) / steps
     ms12, ms3 = float(np.mean(k12)), float(np.mean(k3))
 
