@@ -16,6 +16,10 @@
 #pragma once
 #include "exat_mode12.h"
 
+#ifndef EXAT_SCHED_VALU_PER_MFMA
+#define EXAT_SCHED_VALU_PER_MFMA 0  // measured: forcing an MFMA/VALU interleave was slower than hipcc's own schedule
+#endif
+
 namespace exat {
 
 struct GenSplitParams {
@@ -66,6 +70,7 @@ __global__ __launch_bounds__(64 * NW) void k_mode12_v2(const Mode12Params p, con
     constexpr int XPT = COLS * 4 / NT;  // 16-byte pieces of the X tile per thread (materialised)
     constexpr int NSJ = 8 / NW;         // 16-column sub-tiles of the generated tile per wave
     constexpr int WCOLS = COLS / NW;    // columns of the generated tile owned by one wave
+    constexpr int SCHED = EXAT_SCHED_VALU_PER_MFMA;
     extern __shared__ __align__(16) unsigned char smem[];
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, hi = lane >> 5;
@@ -271,6 +276,16 @@ __global__ __launch_bounds__(64 * NW) void k_mode12_v2(const Mode12Params p, con
                 for (int rt = 0; rt < RT; rt++)
 #pragma unroll
                     for (int ct = 0; ct < CT; ct++) mma_frag<T>::mma(acc[rt][ct], a[g2][rt], bx[g2][ct]);
+            if constexpr (SRC == SRC_GENERATED && SCHED > 0) {
+                // Scheduling hint: one wave per SIMD issues in order, so the vector work of the generator
+                // (hash, Box-Muller, conversions) only overlaps the matrix pipe if it is interleaved with the
+                // MFMAs in program order: ask for SCHED vector instructions after every MFMA.
+#pragma unroll
+                for (int t = 0; t < 2 * RT * CT + 16; t++) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x002, SCHED, 0);
+                }
+            }
             __syncthreads();
         }
 

@@ -234,3 +234,60 @@ def test_compress_materialised_bf16_small():
     assert err_r <= 1e-5
     assert err <= TOL_BF16
     plan.close()
+
+
+# Every instantiation of the pipelined kernel at sizes the oracle finishes in seconds: 4- and 8-wave
+# workgroups (P*L above / below 256 stacked rows), both generator depths (R <= 32, R <= 64), sub-range
+# boxes, several row groups, ragged last column chunk.
+PIPELINED = {
+    "f32_8w_r32": dict(dtype="f32", I=96, J=150, K=5, R=20, P=9, L=40, M=33, N=7, dI=48, dJ=75, dK=5),
+    "f32_8w_r64": dict(dtype="f32", I=64, J=130, K=4, R=50, P=20, L=32, M=20, N=9, dI=32, dJ=65, dK=2),
+    "f32_4w_r64": dict(dtype="f32", I=80, J=40, K=6, R=40, P=4, L=50, M=50, N=50, dI=40, dJ=20, dK=3),
+    "bf16_4w_r32": dict(dtype="bf16", I=96, J=140, K=5, R=32, P=5, L=50, M=50, N=50, dI=48, dJ=70, dK=5),
+    "bf16_4w_r64": dict(dtype="bf16", I=64, J=40, K=6, R=64, P=3, L=64, M=64, N=64, dI=32, dJ=20, dK=3),
+}
+
+
+@pytest.mark.parametrize("name", list(PIPELINED))
+def test_pipelined_generator_variants(name):
+    kw = dict(PIPELINED[name])
+    cfg = wl.small(name=name, index=300 + list(PIPELINED).index(name), **kw)
+    A, B, C, U, V, W = _inputs(cfg)
+    plan = gu.plan_with_factors(cfg, U, V, W)
+    gen = gu.gen_of(cfg, A, B, C)
+    X = oracle.gen_box(A, B, C, cfg.seed, cfg.sigma)
+    tol = TOL_BF16 if cfg.dtype == "bf16" else TOL_F32
+    Yo = oracle.comp_multi(X, U, V, W, cfg.P)
+    e = oracle.rel_fro(gu.y_to_numpy(plan.compress_gen(gen), cfg), Yo)
+    _say("  %s full: rel_fro=%.3e" % (name, e))
+    assert e <= tol
+    box = (cfg.dI // 2, cfg.I - 3, 5, cfg.J - 1, 1, cfg.K)          # proper sub-range in every mode
+    Xb = np.asfortranarray(X[box[0]:box[1], box[2]:box[3], box[4]:box[5]])
+    eb = oracle.rel_fro(gu.y_to_numpy(plan.compress_gen(gen, box), cfg), oracle.comp_box(Xb, U, V, W, cfg.P, box))
+    _say("  %s box %s: rel_fro=%.3e" % (name, box, eb))
+    assert eb <= tol
+    plan.close()
+
+
+@pytest.mark.parametrize("dtype,P,L", [("f32", 20, 32), ("f32", 3, 50), ("bf16", 11, 50), ("bf16", 4, 40)])
+def test_pipelined_materialised_variants(dtype, P, L):
+    cfg = wl.small(name="pipe_mat", index=320 + P, dtype=dtype, I=96, J=200, K=4, R=6, P=P, L=L, M=L, N=9, dI=32, dJ=100, dK=2)
+    A, B, C, U, V, W = _inputs(cfg)
+    bf = dtype == "bf16"
+    X = oracle.gen_box(A, B, C, cfg.seed, cfg.sigma, to_bf16=bf)
+    plan = gu.plan_with_factors(cfg, U, V, W)
+    rb = oracle.round_bf16 if bf else (lambda a: a)
+    Yo = oracle.comp_multi(X, rb(U), rb(V), rb(W), cfg.P)
+    Xd = gu.to_dev_x(X, bf16=bf)
+    e = oracle.rel_fro(gu.y_to_numpy(plan.compress(Xd), cfg), Yo)
+    # the same through the block-streamed entry point (blocks are whole 64-byte stages of i)
+    Xv = Xd.view(cfg.K, cfg.J, cfg.I)
+    for bk in range(cfg.K // cfg.dK):
+        for bj in range(cfg.J // cfg.dJ):
+            for bi in range(cfg.I // cfg.dI):
+                blk = Xv[bk * cfg.dK:(bk + 1) * cfg.dK, bj * cfg.dJ:(bj + 1) * cfg.dJ, bi * cfg.dI:(bi + 1) * cfg.dI].contiguous()
+                plan.compress_block(blk, bi, bj, bk)
+    eb = oracle.rel_fro(gu.y_to_numpy(plan.finalize(), cfg), Yo)
+    _say("  %s P=%d L=%d: one shot %.3e, block-streamed %.3e" % (dtype, P, L, e, eb))
+    assert max(e, eb) <= 1e-5
+    plan.close()
