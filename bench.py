@@ -158,6 +158,7 @@ def main():
     }
     if cfg.materialised:
         out["hbm_algorithmic_gbps"] = cfg.elements * (2 if cfg.dtype == "bf16" else 4) / (ms12 * 1e-3) / 1e9
+    out["kernel_check_counters"] = plan.check_status()   # bounds-checked kernel variants: all zero when clean
     if frac != 1.0:
         out["config"]["sub_box_k_slices"] = args.kslices
     if args.check and frac == 1.0:

@@ -141,6 +141,12 @@ int exat_compress_gen(exat_plan_t plan, const exat_gen_t *gen, const exat_box_t 
 int exat_gen_block(const exat_desc_t *desc, const exat_gen_t *gen, int32_t bi, int32_t bj, int32_t bk,
                    void *out, void *stream);
 
+/* Diagnostic aid: kernel variants built with in-kernel bounds checking count every global access that
+ * would have left its buffer (the access is skipped).  Synchronises the device and copies the plan's 8
+ * counters to the host array: [0] = number of rejected accesses, [1..6] = flags per buffer
+ * (U, A pieces, B, C, V, Q).  All zero in a correct run.  Errors: NULL, HIP. */
+int exat_plan_check_status(exat_plan_t plan, uint32_t *counters8);
+
 /* Measurement aid (not part of the paper's method): with timing enabled, every compress
  * call records HIP events on its stream around the fused mode-1/2 kernel and around the
  * mode-3 kernel.  exat_plan_last_timing waits for the most recent call's events and returns

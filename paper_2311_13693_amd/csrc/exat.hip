@@ -43,6 +43,8 @@ struct exat_plan_s {
     bool timing = false, timing_valid = false;
     hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
     __bf16 *Asplit = nullptr;  // bf16 pieces of the generator's A factor, [3][Ipad][64]
+    unsigned *dbg = nullptr;   // 8 counters written by bounds-checked kernel variants
+    size_t ub = 0, vb = 0, qb = 0, ab = 0;  // byte sizes of Upack, Vpack, Q, Asplit
 };
 
 namespace {
@@ -131,11 +133,11 @@ int launch_mode12_bf16(int rt, const Mode12Params &mp, int nk, hipStream_t st)
     }
 }
 
-template <typename T, int NW, int RT, int SRC, int KS, bool BOXED>
-int launch_v2_inst(const Mode12Params &mp, const GenSplitParams &gs, int nk, hipStream_t st)
+template <typename T, int NW, int RT, int SRC, int KS, bool BOXED, bool CHECKED = false>
+int launch_v2_inst(const Mode12Params &mp, const GenSplitParams &gs, const CheckParams &ck, int nk, hipStream_t st)
 {
     typedef Mode12V2Cfg<NW, RT> cfg;
-    auto kern = k_mode12_v2<T, NW, RT, SRC, KS, BOXED>;
+    auto kern = k_mode12_v2<T, NW, RT, SRC, KS, BOXED, CHECKED>;
     static bool attr_done = false;
     if (!attr_done) {
         if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, cfg::LDS_BYTES) != hipSuccess) return EXAT_ERR_HIP;
@@ -143,16 +145,23 @@ int launch_v2_inst(const Mode12Params &mp, const GenSplitParams &gs, int nk, hip
     }
     const int64_t grid = 8LL * ((nk + 7) / 8) * mp.G;
     if (grid > 2147483647LL) return EXAT_ERR_SHAPE;
-    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(64 * NW), cfg::LDS_BYTES, st, mp, gs);
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(64 * NW), cfg::LDS_BYTES, st, mp, gs, ck);
     return hipGetLastError() == hipSuccess ? EXAT_OK : EXAT_ERR_HIP;
 }
 
 template <typename T, int NW, int RT>
-int launch_v2(const Mode12Params &mp, const GenSplitParams &gs, bool generated, int ks, bool boxed, int nk, hipStream_t st)
+int launch_v2(const Mode12Params &mp, const GenSplitParams &gs, const CheckParams &ck, bool generated, int ks, bool boxed, int nk, hipStream_t st)
 {
-    if (!generated) return launch_v2_inst<T, NW, RT, SRC_MATERIALISED, 1, false>(mp, gs, nk, st);
-    if (ks == 1) return boxed ? launch_v2_inst<T, NW, RT, SRC_GENERATED, 1, true>(mp, gs, nk, st) : launch_v2_inst<T, NW, RT, SRC_GENERATED, 1, false>(mp, gs, nk, st);
-    return boxed ? launch_v2_inst<T, NW, RT, SRC_GENERATED, 2, true>(mp, gs, nk, st) : launch_v2_inst<T, NW, RT, SRC_GENERATED, 2, false>(mp, gs, nk, st);
+    if (!generated) return launch_v2_inst<T, NW, RT, SRC_MATERIALISED, 1, false>(mp, gs, ck, nk, st);
+    if (ks == 1) return boxed ? launch_v2_inst<T, NW, RT, SRC_GENERATED, 1, true>(mp, gs, ck, nk, st) : launch_v2_inst<T, NW, RT, SRC_GENERATED, 1, false>(mp, gs, ck, nk, st);
+    return boxed ? launch_v2_inst<T, NW, RT, SRC_GENERATED, 2, true>(mp, gs, ck, nk, st) : launch_v2_inst<T, NW, RT, SRC_GENERATED, 2, false>(mp, gs, ck, nk, st);
+}
+
+// bf16, 8 waves, generated source: every global access of this variant is bounds-checked in the kernel
+int launch_v2_bf16_8w_gen_checked(const Mode12Params &mp, const GenSplitParams &gs, const CheckParams &ck, int ks, bool boxed, int nk, hipStream_t st)
+{
+    if (ks == 1) return boxed ? launch_v2_inst<__bf16, 8, 2, SRC_GENERATED, 1, true, true>(mp, gs, ck, nk, st) : launch_v2_inst<__bf16, 8, 2, SRC_GENERATED, 1, false, true>(mp, gs, ck, nk, st);
+    return boxed ? launch_v2_inst<__bf16, 8, 2, SRC_GENERATED, 2, true, true>(mp, gs, ck, nk, st) : launch_v2_inst<__bf16, 8, 2, SRC_GENERATED, 2, false, true>(mp, gs, ck, nk, st);
 }
 
 // fills the plan-dependent part of the parameters and launches mode 1+2 followed by mode 3
@@ -169,9 +178,12 @@ int run_chain(exat_plan_s *pl, Mode12Params mp, bool generated, float *Yout, int
     if (v2) {
         const int forced = env_int("EXAT_RT", 0);
         rt = (forced == 2 || forced == 4) ? forced : (pl->PL > 256 ? 4 : 2);  // rt 4 = 8 waves x 2 row tiles
+        // bf16 generated source: 4 waves x 3 row tiles (384 stacked rows) unless told otherwise
+        if (bf && generated && pl->PL > 256 && forced != 2 && forced != 4) rt = 3;
         // The 8-wave bf16 generator variant faulted on the GPU at the 10000^3 size for a reason not yet
-        // found by reading; it stays switched off (the 4-wave variant is used) until the cause is known.
-        if (bf && generated) rt = 2;
+        // found by reading.  It only runs in its bounds-checked form (every global access validated in the
+        // kernel, violations counted in the plan's check counters), and only on request.
+        if (bf && generated && rt == 4 && env_int("EXAT_BF16_8W_CHECKED", 0) == 0) rt = 3;
     }
     const int rows = 128 * rt;
     mp.U = pl->Upack; mp.V = pl->Vpack; mp.Q = pl->Q;
@@ -191,8 +203,18 @@ int run_chain(exat_plan_s *pl, Mode12Params mp, bool generated, float *Yout, int
     if (v2) {
         const bool boxed = generated && (mp.i0 != 0 || mp.i1 != pl->d.I);
         const int ks = gs.Rpad / 32;
-        if (bf) rc = rt == 4 ? launch_v2<__bf16, 8, 2>(mp, gs, generated, ks, boxed, nk, st) : launch_v2<__bf16, 4, 2>(mp, gs, generated, ks, boxed, nk, st);
-        else rc = rt == 4 ? launch_v2<float, 8, 2>(mp, gs, generated, ks, boxed, nk, st) : launch_v2<float, 4, 2>(mp, gs, generated, ks, boxed, nk, st);
+        CheckParams ck;
+        memset(&ck, 0, sizeof(ck));
+        ck.dbg = pl->dbg;
+        if (generated) {
+            const char *lo[6] = {(const char *)pl->Upack, (const char *)pl->Asplit, (const char *)mp.B, (const char *)mp.C, (const char *)pl->Vpack, (const char *)pl->Q};
+            const size_t sz[6] = {pl->ub, pl->ab, (size_t)pl->d.J * mp.R * 4, (size_t)pl->d.K * mp.R * 4, pl->vb, pl->qb};
+            for (int t = 0; t < 6; t++) { ck.lo[t] = lo[t]; ck.hi[t] = lo[t] + sz[t]; }
+        }
+        if (bf && generated && rt == 4) rc = launch_v2_bf16_8w_gen_checked(mp, gs, ck, ks, boxed, nk, st);
+        else if (bf && generated && rt == 3) rc = launch_v2<__bf16, 4, 3>(mp, gs, ck, true, ks, boxed, nk, st);
+        else if (bf) rc = rt == 4 ? launch_v2<__bf16, 8, 2>(mp, gs, ck, generated, ks, boxed, nk, st) : launch_v2<__bf16, 4, 2>(mp, gs, ck, generated, ks, boxed, nk, st);
+        else rc = rt == 4 ? launch_v2<float, 8, 2>(mp, gs, ck, generated, ks, boxed, nk, st) : launch_v2<float, 4, 2>(mp, gs, ck, generated, ks, boxed, nk, st);
     } else if (pl->d.in_dtype == EXAT_BF16)
         rc = generated ? launch_mode12_bf16<SRC_GENERATED>(rt, mp, nk, st) : launch_mode12_bf16<SRC_MATERIALISED>(rt, mp, nk, st);
     else
@@ -243,7 +265,7 @@ int exat_plan_create(exat_plan_t *plan, const exat_desc_t *desc)
     pl->Jpad = ceil_to(desc->J, 256);
     // every kernel variant the plan may pick must find its row groups inside the padding
     int64_t plpad = 0;
-    const int rts_f32[] = {1, 2, 4}, rts_bf16[] = {2, 4, 5};
+    const int rts_f32[] = {1, 2, 4}, rts_bf16[] = {2, 3, 4, 5};
     if (desc->in_dtype == EXAT_BF16) { for (int rt : rts_bf16) { int64_t v = ceil_to(pl->PL, 128 * rt); if (v > plpad) plpad = v; } }
     else { for (int rt : rts_f32) { int64_t v = ceil_to(pl->PL, 128 * rt); if (v > plpad) plpad = v; } }
     pl->PLpad = (int)plpad;
@@ -252,7 +274,9 @@ int exat_plan_create(exat_plan_t *plan, const exat_desc_t *desc)
     const size_t vb = (size_t)desc->P * pl->Mpad * pl->Jpad * 4;
     const size_t wb = (size_t)desc->P * desc->K * pl->Npad * 4;
     const size_t qb = (size_t)desc->K * pl->PLpad * pl->Mpad * 4;
-    if (hipMalloc((void **)&pl->Asplit, (size_t)3 * pl->Ipad * 64 * 2) != hipSuccess ||
+    pl->ub = ub; pl->vb = vb; pl->qb = qb; pl->ab = (size_t)3 * pl->Ipad * 64 * 2;
+    if (hipMalloc((void **)&pl->dbg, 256 * sizeof(unsigned)) != hipSuccess || hipMemset(pl->dbg, 0, 256 * sizeof(unsigned)) != hipSuccess ||
+        hipMalloc((void **)&pl->Asplit, pl->ab) != hipSuccess ||
         hipMalloc(&pl->Upack, ub) != hipSuccess || hipMalloc((void **)&pl->Vpack, vb) != hipSuccess ||
         hipMalloc((void **)&pl->Wpack, wb) != hipSuccess || hipMalloc((void **)&pl->Q, qb) != hipSuccess) {
         (void)hipGetLastError();
@@ -269,7 +293,7 @@ int exat_plan_destroy(exat_plan_t pl)
 {
     if (!pl) return EXAT_OK;
     (void)hipFree(pl->Upack); (void)hipFree(pl->Vpack); (void)hipFree(pl->Wpack); (void)hipFree(pl->Q);
-    (void)hipFree(pl->slots); (void)hipFree(pl->used_dev); (void)hipFree(pl->Asplit);
+    (void)hipFree(pl->slots); (void)hipFree(pl->used_dev); (void)hipFree(pl->Asplit); (void)hipFree(pl->dbg);
     for (hipEvent_t e : pl->ev) if (e) (void)hipEventDestroy(e);
     delete pl;
     return EXAT_OK;
@@ -418,6 +442,22 @@ int exat_gen_block(const exat_desc_t *desc, const exat_gen_t *gen, int32_t bi, i
         hipLaunchKernelGGL(k_gen_box<float>, dim3(grid_for(n)), dim3(256), 0, st, gp, (float *)out);
     return hipGetLastError() == hipSuccess ? EXAT_OK : EXAT_ERR_HIP;
 }
+
+int exat_plan_check_status(exat_plan_t pl, uint32_t *counters8)
+{
+    if (!pl || !counters8) return EXAT_ERR_NULL;
+    if (hipDeviceSynchronize() != hipSuccess) return EXAT_ERR_HIP;
+    if (hipMemcpy(counters8, pl->dbg, 8 * sizeof(unsigned), hipMemcpyDeviceToHost) != hipSuccess) return EXAT_ERR_HIP;
+    return EXAT_OK;
+}
+
+#ifdef EXAT_TRACE
+extern "C" int exat_plan_trace(exat_plan_t pl, uint32_t *out240)
+{
+    if (hipDeviceSynchronize() != hipSuccess) return EXAT_ERR_HIP;
+    return hipMemcpy(out240, pl->dbg + 16, 240 * sizeof(unsigned), hipMemcpyDeviceToHost) == hipSuccess ? EXAT_OK : EXAT_ERR_HIP;
+}
+#endif
 
 int exat_plan_set_timing(exat_plan_t pl, int enable)
 {

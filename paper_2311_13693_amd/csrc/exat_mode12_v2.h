@@ -28,6 +28,44 @@ struct GenSplitParams {
     int Rpad;
 };
 
+// Optional in-kernel bounds checking of every global access (template flag CHECKED): an address outside
+// its buffer is not dereferenced; the access is counted in dbg[0], its buffer id is flagged in dbg[1 + id],
+// and a zero is used instead.  The host reads the counters back through exat_plan_check_status.
+struct CheckParams {
+    const char *lo[6], *hi[6];  // 0: U, 1: A pieces, 2: B, 3: C, 4: V, 5: Q
+    unsigned *dbg;              // >= 8 counters
+};
+enum { CHK_U = 0, CHK_A = 1, CHK_B = 2, CHK_C = 3, CHK_V = 4, CHK_Q = 5 };
+
+template <bool CHECKED, typename V>
+__device__ __forceinline__ V ld_chk(const V *ptr, const CheckParams &ck, int id)
+{
+    if constexpr (CHECKED) {
+        const char *c = (const char *)ptr;
+        if (c < ck.lo[id] || c + sizeof(V) > ck.hi[id]) {
+            atomicAdd(&ck.dbg[0], 1u);
+            ck.dbg[1 + id] = 1u;
+            V z;
+            __builtin_memset(&z, 0, sizeof(V));
+            return z;
+        }
+    }
+    return *ptr;
+}
+template <bool CHECKED, typename V>
+__device__ __forceinline__ void st_chk(V *ptr, V v, const CheckParams &ck, int id)
+{
+    if constexpr (CHECKED) {
+        const char *c = (const char *)ptr;
+        if (c < ck.lo[id] || c + sizeof(V) > ck.hi[id]) {
+            atomicAdd(&ck.dbg[0], 1u);
+            ck.dbg[1 + id] = 1u;
+            return;
+        }
+    }
+    *ptr = v;
+}
+
 // MFMA 16x16x32 bf16: A lane (row l%16, k 8*(l/16)+e), B lane (col l%16, k 8*(l/16)+e),
 // C lane (col l%16, rows 4*(l/16)+r).
 typedef float f32x4v __attribute__((ext_vector_type(4)));
@@ -56,8 +94,8 @@ __device__ __forceinline__ void split3(float v, __bf16 &h, __bf16 &m, __bf16 &l)
 
 // BOXED: the box is a proper sub-range in i, so elements outside [i0,i1) must be forced to zero
 // (for the full extent the zero padding of U already removes them).
-template <typename T, int NW, int RT, int SRC, int KS, bool BOXED>
-__global__ __launch_bounds__(64 * NW) void k_mode12_v2(const Mode12Params p, const GenSplitParams gs)
+template <typename T, int NW, int RT, int SRC, int KS, bool BOXED, bool CHECKED>
+__global__ __launch_bounds__(64 * NW) void k_mode12_v2(const Mode12Params p, const GenSplitParams gs, const CheckParams ck)
 {
     typedef Mode12V2Cfg<NW, RT> cfg;
     typedef typename mma_frag<T>::type frag_t;
@@ -73,7 +111,8 @@ __global__ __launch_bounds__(64 * NW) void k_mode12_v2(const Mode12Params p, con
     constexpr int SCHED = EXAT_SCHED_VALU_PER_MFMA;
     extern __shared__ __align__(16) unsigned char smem[];
 
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, hi = lane >> 5;
+    // the wave index is the same for all lanes of a wave: say so, which keeps everything derived from it scalar
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, l32 = lane & 31, hi = lane >> 5;
     const int l16 = lane & 15, q16 = lane >> 4;
     const int nk = (int)(p.k1 - p.k0);
     const int bid = blockIdx.x, xcd = bid & 7, t = bid >> 3;
@@ -141,7 +180,7 @@ __global__ __launch_bounds__(64 * NW) void k_mode12_v2(const Mode12Params p, con
                     for (int e = 0; e < 8; e++) {
                         const int r = 32 * ks + 8 * q16 + e;
                         float bc = 0.0f;
-                        if (colok && r < p.R) bc = p.B[jj + p.ldB * r] * p.C[k + p.ldC * r];
+                        if (colok && r < p.R) bc = ld_chk<CHECKED>(p.B + jj + p.ldB * r, ck, CHK_B) * ld_chk<CHECKED>(p.C + k + p.ldC * r, ck, CHK_C);
                         __bf16 h, m, l;
                         split3(bc, h, m, l);
                         bh[e] = h; bm[e] = m; bl[e] = l;
@@ -157,7 +196,7 @@ __global__ __launch_bounds__(64 * NW) void k_mode12_v2(const Mode12Params p, con
         auto load_u = [&](int s) {
             const T *ub = Ug + stage_i(s);
 #pragma unroll
-            for (int u = 0; u < UPT; u++) upre[u] = *(const u32x4 *)(ub + (u_voff + u * u_vstep));
+            for (int u = 0; u < UPT; u++) upre[u] = ld_chk<CHECKED>((const u32x4 *)(ub + (u_voff + u * u_vstep)), ck, CHK_U);
         };
         auto load_x = [&](int s) {
             if constexpr (SRC == SRC_MATERIALISED) {
@@ -179,7 +218,7 @@ __global__ __launch_bounds__(64 * NW) void k_mode12_v2(const Mode12Params p, con
                     for (int ks = 0; ks < KS; ks++)
 #pragma unroll
                         for (int si = 0; si < SUBI; si++)
-                            afrag[(v * KS + ks) * SUBI + si] = *(const bf16x8 *)(gs.Asp + ((int64_t)v * gs.Irows + ib + 16 * si + l16) * gs.Rpad + 32 * ks + 8 * q16);
+                            afrag[(v * KS + ks) * SUBI + si] = ld_chk<CHECKED>((const bf16x8 *)(gs.Asp + ((int64_t)v * gs.Irows + ib + 16 * si + l16) * gs.Rpad + 32 * ks + 8 * q16), ck, CHK_A);
             }
         };
         // low-rank part of the tile of the stage whose A fragments are loaded: accx = A_tile * bc^T
@@ -254,13 +293,17 @@ __global__ __launch_bounds__(64 * NW) void k_mode12_v2(const Mode12Params p, con
         load_a(2);
         __syncthreads();
 
-        for (int s = 0; s < nstage; s++) {
-            const unsigned char *base = smem + (s & 1) * cfg::BUF_BYTES;
-            // stage s+1 (registers) -> the other buffer; everyone finished reading it before the last barrier
+        // One iteration = "fill" (write stage s+1 from registers into the other LDS buffer, start the loads of
+        // stage s+2, generate the tile of stage s+2: vector + memory work) and "multiply" (MFMAs of stage s from
+        // the current buffer).  The two parts touch different LDS buffers and different registers.
+        auto fill = [&](int s) {
             commit(s + 1, (s + 1) & 1);
             load_u(s + 2); load_x(s + 2);
             gen_x();        // tile of stage s+2 from the A fragments loaded one iteration ago
             load_a(s + 3);
+        };
+        auto multiply = [&](int s) {
+            const unsigned char *base = smem + (s & 1) * cfg::BUF_BYTES;
             frag_t a[2][RT], bx[2][CT];
 #pragma unroll
             for (int rt = 0; rt < RT; rt++) a[0][rt] = *(const frag_t *)(base + us_r + rt * 32 * ROWB);
@@ -276,17 +319,110 @@ __global__ __launch_bounds__(64 * NW) void k_mode12_v2(const Mode12Params p, con
                 for (int rt = 0; rt < RT; rt++)
 #pragma unroll
                     for (int ct = 0; ct < CT; ct++) mma_frag<T>::mma(acc[rt][ct], a[g2][rt], bx[g2][ct]);
-            if constexpr (SRC == SRC_GENERATED && SCHED > 0) {
-                // Scheduling hint: one wave per SIMD issues in order, so the vector work of the generator
-                // (hash, Box-Muller, conversions) only overlaps the matrix pipe if it is interleaved with the
-                // MFMAs in program order: ask for SCHED vector instructions after every MFMA.
+        };
+        // Interleaved iteration for one wave per SIMD (4-wave bf16 generator): such a wave issues in order, so
+        // the generator's vector work only overlaps the matrix pipe if it sits between the MFMAs in program
+        // order.  The noise of stage s+1 is cut into 16 pieces (4 hashes, 8 Box-Muller pairs, 4 add/convert/
+        // LDS-write steps), the low-rank MFMAs of stage s+2 into single instructions, and one piece of each is
+        // placed after every MFMA of stage s; scheduling barriers keep the pieces where they are put.
+        constexpr bool WEAVE = (SRC == SRC_GENERATED) && (sizeof(T) == 2) && (NW == 4);
+        uint32_t hw[WEAVE ? 4 : 1][2];
+        float zz[WEAVE ? 4 : 1][4];
+        f32x4v accn[WEAVE ? SUBI * NSJ : 1];
+        unsigned *trp = nullptr;
+        auto woven = [&](int s) {
+            if constexpr (WEAVE) {
+                const unsigned char *base = smem + (s & 1) * cfg::BUF_BYTES;
+                unsigned char *obase = smem + ((s + 1) & 1) * cfg::BUF_BYTES;
+                const int64_t ib1 = stage_i(s + 1);
+                frag_t a[2][RT], bx[2][CT];
 #pragma unroll
-                for (int t = 0; t < 2 * RT * CT + 16; t++) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x002, SCHED, 0);
+                for (int g2 = 0; g2 < 2; g2++) {
+#pragma unroll
+                    for (int rt = 0; rt < RT; rt++) a[g2][rt] = *(const frag_t *)(base + us_r + rt * 32 * ROWB + g2 * 32);
+#pragma unroll
+                    for (int ct = 0; ct < CT; ct++) bx[g2][ct] = *(const frag_t *)(base + xs_r + ct * 32 * ROWB + g2 * 32);
                 }
+#pragma unroll
+                for (int u = 0; u < UPT; u++) *(u32x4 *)(obase + us_w + u * PSTEP * ROWB) = upre[u];
+                load_u(s + 2);
+                __builtin_amdgcn_sched_barrier(0);
+#ifdef EXAT_TRACE
+                if (trp) trp[1] = (unsigned)clock64();
+#endif
+                constexpr int NMAIN = 2 * RT * CT, NGEN = SUBI * NSJ * KS * 3, GPS = (NGEN + 11) / 12;
+                static_assert(NMAIN >= 16, "the 16 noise pieces need 16 MFMA slots");
+#pragma unroll
+                for (int m = 0; m < NMAIN; m++) {
+                    const int g2 = m / (RT * CT), rt = (m / CT) % RT, ct = m % CT;
+                    mma_frag<T>::mma(acc[rt][ct], a[g2][rt], bx[g2][ct]);
+                    __builtin_amdgcn_sched_barrier(0);
+                    // low-rank MFMAs of stage s+2 (A fragments loaded one iteration ago) into accn
+#pragma unroll
+                    for (int gg = 0; gg < GPS; gg++) {
+                        const int n = m * GPS + gg;
+                        if (m < 12 && n < NGEN) {
+                            const int term = n % 3, ks = (n / 3) % KS, sub = n / (3 * KS), si = sub / NSJ, sj = sub % NSJ;
+                            const bf16x8 av = afrag[((term == 0 ? 1 : 0) * KS + ks) * SUBI + si];   // m*h, h*m, h*h
+                            const bf16x8 bv = bfrag[((term == 1 ? 1 : 0) * KS + ks) * NSJ + sj];
+                            const f32x4v zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
+                            const f32x4v c = (term == 0 && ks == 0) ? zero4 : accn[sub];
+                            accn[sub] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, bv, c, 0, 0, 0);
+                        }
+                    }
+                    if (m == 12) load_a(s + 3);  // the A fragments are free now: request those of stage s+3
+                    // noise of stage s+1
+                    if (m < 4) {
+                        const int q = m, si = q / NSJ, sj = q % NSJ;
+                        const uint32_t x = ckey[sj] ^ (uint32_t)((ib1 + 16 * si + 4 * q16) >> 2);
+                        hw[q][0] = mix_a(x);
+                        hw[q][1] = mix_b(x);
+                    } else if (m < 12) {
+                        const int q = (m - 4) >> 1, h = (m - 4) & 1;
+                        box_muller(hw[q][h], amp[q % NSJ], zz[q][2 * h], zz[q][2 * h + 1]);
+                    } else if (m < 16) {
+                        const int q = m - 12, si = q / NSJ, sj = q % NSJ;
+                        const int64_t i = ib1 + 16 * si + 4 * q16;
+                        float x[4];
+#pragma unroll
+                        for (int e = 0; e < 4; e++) {
+                            x[e] = accx[q][e] + zz[q][e];
+                            if (BOXED && (i + e < p.i0 || i + e >= p.i1)) x[e] = 0.0f;
+                        }
+                        bf16x4 v = {(__bf16)x[0], (__bf16)x[1], (__bf16)x[2], (__bf16)x[3]};
+                        *(bf16x4 *)(obase + xg_w + sj * 16 * ROWB + si * 16 * (int)sizeof(T)) = v;
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+#pragma unroll
+                for (int q = 0; q < SUBI * NSJ; q++) accx[q] = accn[q];
             }
+        };
+        for (int s = 0; s < nstage; s++) {
+#ifdef EXAT_TRACE
+            const bool tr = blockIdx.x == 0 && lane == 0 && (wave == 0 || wave == NW / 2) && jc == ja0 && s >= 8 && s < 16;
+            unsigned *tp = ck.dbg + 16 + ((wave ? 1 : 0) * 8 + (s - 8)) * 4;
+            if (tr) tp[0] = (unsigned)clock64();
+#endif
+            if constexpr (WEAVE) {
+#ifdef EXAT_TRACE
+                trp = tr ? tp : nullptr;
+#endif
+                woven(s);
+            } else {
+                fill(s);
+#ifdef EXAT_TRACE
+                if (tr) tp[1] = (unsigned)clock64();
+#endif
+                multiply(s);
+            }
+#ifdef EXAT_TRACE
+            if (tr) tp[2] = (unsigned)clock64();
+#endif
             __syncthreads();
+#ifdef EXAT_TRACE
+            if (tr) tp[3] = (unsigned)clock64();
+#endif
         }
 
         // ---- mode 2 on the finished Z chunk (same as k_mode12) ----
@@ -321,7 +457,7 @@ __global__ __launch_bounds__(64 * NW) void k_mode12_v2(const Mode12Params p, con
 #pragma unroll
                         for (int mt = 0; mt < 2; mt++) {
                             if (mt < p.MT) {
-                                const f32x4 bv = *(const f32x4 *)(Vp + (int64_t)(mt * 32 + l32) * p.Jpad + 8 * g8 + 4 * hi);
+                                const f32x4 bv = ld_chk<CHECKED>((const f32x4 *)(Vp + (int64_t)(mt * 32 + l32) * p.Jpad + 8 * g8 + 4 * hi), ck, CHK_V);
                                 mma_frag<float>::mma(qa[mt], av, bv);
                             }
                         }
@@ -338,8 +474,8 @@ __global__ __launch_bounds__(64 * NW) void k_mode12_v2(const Mode12Params p, con
                                     if (row >= rlo && row < rhi) {
                                         float *dst = p.Q + ((int64_t)kidx * p.PLpad + row) * p.Mpad + mt * 32 + l32;
                                         float v = qa[mt][4 * b4 + r];
-                                        if (!first_chunk) v += *dst;
-                                        *dst = v;
+                                        if (!first_chunk) v += ld_chk<CHECKED>((const float *)dst, ck, CHK_Q);
+                                        st_chk<CHECKED>(dst, v, ck, CHK_Q);
                                     }
                                 }
                         }

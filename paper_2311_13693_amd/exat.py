@@ -15,7 +15,7 @@ OK, ERR_NULL, ERR_SHAPE, ERR_DTYPE, ERR_STATE, ERR_ALLOC, ERR_HIP = 0, -1, -2, -
 
 EXPORTS = ["exat_plan_create", "exat_plan_destroy", "exat_set_factors", "exat_compress",
            "exat_compress_block", "exat_finalize", "exat_compress_gen", "exat_gen_block",
-           "exat_plan_set_timing", "exat_plan_last_timing", "exat_strerror"]
+           "exat_plan_set_timing", "exat_plan_last_timing", "exat_plan_check_status", "exat_strerror"]
 
 
 class Desc(ctypes.Structure):
@@ -63,6 +63,7 @@ def lib():
         L.exat_gen_block.argtypes = [ctypes.POINTER(Desc), ctypes.POINTER(Gen), i32, i32, i32, vp, vp]
         L.exat_plan_set_timing.argtypes = [vp, ctypes.c_int]
         L.exat_plan_last_timing.argtypes = [vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_float)]
+        L.exat_plan_check_status.argtypes = [vp, ctypes.POINTER(ctypes.c_uint32)]
         L.exat_strerror.argtypes = [ctypes.c_int]
         L.exat_strerror.restype = ctypes.c_char_p
         for name in EXPORTS[:-1]:
@@ -150,6 +151,12 @@ class Plan:
         a, b = ctypes.c_float(), ctypes.c_float()
         _check(lib().exat_plan_last_timing(self._h, ctypes.byref(a), ctypes.byref(b)))
         return a.value, b.value
+
+    def check_status(self):
+        """Counters of the bounds-checked kernel variants (all zero in a correct run); synchronises."""
+        out = (ctypes.c_uint32 * 8)()
+        _check(lib().exat_plan_check_status(self._h, out))
+        return list(out)
 
     def new_y(self):
         import torch
