@@ -21,8 +21,6 @@ namespace {
 constexpr int64_t kMaxExtent = 2147483647LL - 64;
 constexpr int64_t kSlotBudgetBytes = 4LL << 30;
 
-struct KernelChoice { int rt, ct; };
-
 }  // namespace
 
 struct exat_plan_s {
@@ -111,9 +109,6 @@ int launch_mode12_inst(const Mode12Params &mp, int nk, hipStream_t st)
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), cfg::LDS_BYTES, st, mp);
     return hipGetLastError() == hipSuccess ? EXAT_OK : EXAT_ERR_HIP;
 }
-
-template <typename T, int SRC>
-int launch_mode12_rt(int rt, const Mode12Params &mp, int nk, hipStream_t st);
 
 template <int SRC>
 int launch_mode12_f32(int rt, const Mode12Params &mp, int nk, hipStream_t st)
@@ -275,7 +270,7 @@ int exat_plan_create(exat_plan_t *plan, const exat_desc_t *desc)
     const size_t wb = (size_t)desc->P * desc->K * pl->Npad * 4;
     const size_t qb = (size_t)desc->K * pl->PLpad * pl->Mpad * 4;
     pl->ub = ub; pl->vb = vb; pl->qb = qb; pl->ab = (size_t)3 * pl->Ipad * 64 * 2;
-    if (hipMalloc((void **)&pl->dbg, 256 * sizeof(unsigned)) != hipSuccess || hipMemset(pl->dbg, 0, 256 * sizeof(unsigned)) != hipSuccess ||
+    if (hipMalloc((void **)&pl->dbg, 8 * sizeof(unsigned)) != hipSuccess || hipMemset(pl->dbg, 0, 8 * sizeof(unsigned)) != hipSuccess ||
         hipMalloc((void **)&pl->Asplit, pl->ab) != hipSuccess ||
         hipMalloc(&pl->Upack, ub) != hipSuccess || hipMalloc((void **)&pl->Vpack, vb) != hipSuccess ||
         hipMalloc((void **)&pl->Wpack, wb) != hipSuccess || hipMalloc((void **)&pl->Q, qb) != hipSuccess) {
@@ -450,14 +445,6 @@ int exat_plan_check_status(exat_plan_t pl, uint32_t *counters8)
     if (hipMemcpy(counters8, pl->dbg, 8 * sizeof(unsigned), hipMemcpyDeviceToHost) != hipSuccess) return EXAT_ERR_HIP;
     return EXAT_OK;
 }
-
-#ifdef EXAT_TRACE
-extern "C" int exat_plan_trace(exat_plan_t pl, uint32_t *out240)
-{
-    if (hipDeviceSynchronize() != hipSuccess) return EXAT_ERR_HIP;
-    return hipMemcpy(out240, pl->dbg + 16, 240 * sizeof(unsigned), hipMemcpyDeviceToHost) == hipSuccess ? EXAT_OK : EXAT_ERR_HIP;
-}
-#endif
 
 int exat_plan_set_timing(exat_plan_t pl, int enable)
 {

@@ -16,9 +16,6 @@
 #pragma once
 #include "exat_mode12.h"
 
-#ifndef EXAT_SCHED_VALU_PER_MFMA
-#define EXAT_SCHED_VALU_PER_MFMA 0  // measured: forcing an MFMA/VALU interleave was slower than hipcc's own schedule
-#endif
 
 namespace exat {
 
@@ -108,7 +105,6 @@ __global__ __launch_bounds__(64 * NW) void k_mode12_v2(const Mode12Params p, con
     constexpr int XPT = COLS * 4 / NT;  // 16-byte pieces of the X tile per thread (materialised)
     constexpr int NSJ = 8 / NW;         // 16-column sub-tiles of the generated tile per wave
     constexpr int WCOLS = COLS / NW;    // columns of the generated tile owned by one wave
-    constexpr int SCHED = EXAT_SCHED_VALU_PER_MFMA;
     extern __shared__ __align__(16) unsigned char smem[];
 
     // the wave index is the same for all lanes of a wave: say so, which keeps everything derived from it scalar
@@ -329,7 +325,6 @@ __global__ __launch_bounds__(64 * NW) void k_mode12_v2(const Mode12Params p, con
         uint32_t hw[WEAVE ? 4 : 1][2];
         float zz[WEAVE ? 4 : 1][4];
         f32x4v accn[WEAVE ? SUBI * NSJ : 1];
-        unsigned *trp = nullptr;
         auto woven = [&](int s) {
             if constexpr (WEAVE) {
                 const unsigned char *base = smem + (s & 1) * cfg::BUF_BYTES;
@@ -347,9 +342,6 @@ __global__ __launch_bounds__(64 * NW) void k_mode12_v2(const Mode12Params p, con
                 for (int u = 0; u < UPT; u++) *(u32x4 *)(obase + us_w + u * PSTEP * ROWB) = upre[u];
                 load_u(s + 2);
                 __builtin_amdgcn_sched_barrier(0);
-#ifdef EXAT_TRACE
-                if (trp) trp[1] = (unsigned)clock64();
-#endif
                 constexpr int NMAIN = 2 * RT * CT, NGEN = SUBI * NSJ * KS * 3, GPS = (NGEN + 11) / 12;
                 static_assert(NMAIN >= 16, "the 16 noise pieces need 16 MFMA slots");
 #pragma unroll
@@ -399,30 +391,13 @@ __global__ __launch_bounds__(64 * NW) void k_mode12_v2(const Mode12Params p, con
             }
         };
         for (int s = 0; s < nstage; s++) {
-#ifdef EXAT_TRACE
-            const bool tr = blockIdx.x == 0 && lane == 0 && (wave == 0 || wave == NW / 2) && jc == ja0 && s >= 8 && s < 16;
-            unsigned *tp = ck.dbg + 16 + ((wave ? 1 : 0) * 8 + (s - 8)) * 4;
-            if (tr) tp[0] = (unsigned)clock64();
-#endif
             if constexpr (WEAVE) {
-#ifdef EXAT_TRACE
-                trp = tr ? tp : nullptr;
-#endif
                 woven(s);
             } else {
                 fill(s);
-#ifdef EXAT_TRACE
-                if (tr) tp[1] = (unsigned)clock64();
-#endif
                 multiply(s);
             }
-#ifdef EXAT_TRACE
-            if (tr) tp[2] = (unsigned)clock64();
-#endif
             __syncthreads();
-#ifdef EXAT_TRACE
-            if (tr) tp[3] = (unsigned)clock64();
-#endif
         }
 
         // ---- mode 2 on the finished Z chunk (same as k_mode12) ----

@@ -49,8 +49,13 @@ def lib():
     global _lib
     if _lib is None:
         if not os.path.exists(_LIB_PATH):
-            raise ImportError("libexat.so is not built: run `python paper_2311_13693_amd/build.py` "
-                              "(there is no CPU fallback)")
+            # nothing built yet: build the HIP library now (needs hipcc); there is no CPU fallback
+            try:
+                from . import build as _b
+                _b.build(force=True)
+            except Exception as e:
+                raise ImportError("libexat.so is not built and building it failed (%s): run "
+                                  "`python paper_2311_13693_amd/build.py`; there is no CPU fallback" % e)
         L = ctypes.CDLL(_LIB_PATH)
         vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
         L.exat_plan_create.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(Desc)]
