@@ -13,6 +13,7 @@
 #include "exat_aux.h"
 #include "exat_mode12.h"
 #include "exat_mode12_v2.h"
+#include "exat_mode12_v3.h"
 
 using namespace exat;
 
@@ -28,6 +29,8 @@ struct exat_plan_s {
     int PL, PLpad, Mpad, MT, Npad;
     int64_t Ipad, Jpad;
     void *Upack = nullptr;
+    void *Ufrag = nullptr;  // U in MFMA fragment order (k_pack_u_frag), same size as Upack
+    void *Vfrag = nullptr;  // bf16 plans: V in bf16 MFMA fragment order (k_pack_v_frag)
     float *Vpack = nullptr, *Wpack = nullptr, *Q = nullptr;
     bool factors_set = false;
     // block-streamed state
@@ -152,6 +155,39 @@ int launch_v2(const Mode12Params &mp, const GenSplitParams &gs, const CheckParam
     return boxed ? launch_v2_inst<T, NW, RT, SRC_GENERATED, 2, true>(mp, gs, ck, nk, st) : launch_v2_inst<T, NW, RT, SRC_GENERATED, 2, false>(mp, gs, ck, nk, st);
 }
 
+template <typename T, int NW, int RT, int SRC, int KS, bool BOXED, int DU, int DX>
+int launch_v3_inst(const Mode12Params &mp, const GenSplitParams &gs, const UFragParams &uf, const CheckParams &ck, int nk, hipStream_t st)
+{
+    typedef Mode12V3Cfg<NW, RT> cfg;
+    auto kern = k_mode12_v3<T, NW, RT, SRC, KS, BOXED, false, DU, DX>;
+    static bool attr_done = false;
+    if (!attr_done) {
+        if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, cfg::LDS_BYTES) != hipSuccess) return EXAT_ERR_HIP;
+        attr_done = true;
+    }
+    const int64_t grid = 8LL * ((nk + 7) / 8) * mp.G;
+    if (grid > 2147483647LL) return EXAT_ERR_SHAPE;
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(64 * NW), cfg::LDS_BYTES, st, mp, gs, uf, ck);
+    return hipGetLastError() == hipSuccess ? EXAT_OK : EXAT_ERR_HIP;
+}
+
+// materialised source: fp32 stages are long (fp32 MFMA), two register sets suffice; bf16 stages are 16 times
+// shorter and want the tiles requested further ahead
+template <typename T, int NW, int RT>
+int launch_v3_mat(const Mode12Params &mp, const GenSplitParams &gs, const UFragParams &uf, const CheckParams &ck, int nk, hipStream_t st)
+{
+    constexpr int D = sizeof(T) == 2 ? 3 : 2, DXV = sizeof(T) == 2 ? 3 : 1;
+    return launch_v3_inst<T, NW, RT, SRC_MATERIALISED, 1, false, D, DXV>(mp, gs, uf, ck, nk, st);
+}
+
+// bf16 generated source, 4 waves
+template <int RT>
+int launch_v3_gen_bf16(const Mode12Params &mp, const GenSplitParams &gs, const UFragParams &uf, const CheckParams &ck, int ks, bool boxed, int nk, hipStream_t st)
+{
+    if (ks == 1) return boxed ? launch_v3_inst<__bf16, 4, RT, SRC_GENERATED, 1, true, 2, 1>(mp, gs, uf, ck, nk, st) : launch_v3_inst<__bf16, 4, RT, SRC_GENERATED, 1, false, 2, 1>(mp, gs, uf, ck, nk, st);
+    return boxed ? launch_v3_inst<__bf16, 4, RT, SRC_GENERATED, 2, true, 2, 1>(mp, gs, uf, ck, nk, st) : launch_v3_inst<__bf16, 4, RT, SRC_GENERATED, 2, false, 2, 1>(mp, gs, uf, ck, nk, st);
+}
+
 // bf16, 8 waves, generated source: every global access of this variant is bounds-checked in the kernel
 int launch_v2_bf16_8w_gen_checked(const Mode12Params &mp, const GenSplitParams &gs, const CheckParams &ck, int ks, bool boxed, int nk, hipStream_t st)
 {
@@ -206,7 +242,16 @@ int run_chain(exat_plan_s *pl, Mode12Params mp, bool generated, float *Yout, int
             const size_t sz[6] = {pl->ub, pl->ab, (size_t)pl->d.J * mp.R * 4, (size_t)pl->d.K * mp.R * 4, pl->vb, pl->qb};
             for (int t = 0; t < 6; t++) { ck.lo[t] = lo[t]; ck.hi[t] = lo[t] + sz[t]; }
         }
-        if (bf && generated && rt == 4) rc = launch_v2_bf16_8w_gen_checked(mp, gs, ck, ks, boxed, nk, st);
+        UFragParams uf;
+        uf.Uf = pl->Ufrag; uf.nig = pl->Ipad / (bf ? 16 : 8); uf.Vf = pl->Vfrag;
+        // fragment-ordered U (no LDS staging of U): every materialised source, and the bf16 generator with
+        // 4 waves; the fp32 generator keeps the LDS-staged kernel (its 8-wave build of this one spills more)
+        const bool v3 = env_int("EXAT_V3", 1) != 0 && (!generated || (bf && rt != 4));
+        if (v3 && !generated) {
+            if (bf) rc = rt == 4 ? launch_v3_mat<__bf16, 8, 2>(mp, gs, uf, ck, nk, st) : launch_v3_mat<__bf16, 4, 2>(mp, gs, uf, ck, nk, st);
+            else rc = rt == 4 ? launch_v3_mat<float, 8, 2>(mp, gs, uf, ck, nk, st) : launch_v3_mat<float, 4, 2>(mp, gs, uf, ck, nk, st);
+        } else if (v3) rc = rt == 3 ? launch_v3_gen_bf16<3>(mp, gs, uf, ck, ks, boxed, nk, st) : launch_v3_gen_bf16<2>(mp, gs, uf, ck, ks, boxed, nk, st);
+        else if (bf && generated && rt == 4) rc = launch_v2_bf16_8w_gen_checked(mp, gs, ck, ks, boxed, nk, st);
         else if (bf && generated && rt == 3) rc = launch_v2<__bf16, 4, 3>(mp, gs, ck, true, ks, boxed, nk, st);
         else if (bf) rc = rt == 4 ? launch_v2<__bf16, 8, 2>(mp, gs, ck, generated, ks, boxed, nk, st) : launch_v2<__bf16, 4, 2>(mp, gs, ck, generated, ks, boxed, nk, st);
         else rc = rt == 4 ? launch_v2<float, 8, 2>(mp, gs, ck, generated, ks, boxed, nk, st) : launch_v2<float, 4, 2>(mp, gs, ck, generated, ks, boxed, nk, st);
@@ -272,7 +317,8 @@ int exat_plan_create(exat_plan_t *plan, const exat_desc_t *desc)
     pl->ub = ub; pl->vb = vb; pl->qb = qb; pl->ab = (size_t)3 * pl->Ipad * 64 * 2;
     if (hipMalloc((void **)&pl->dbg, 8 * sizeof(unsigned)) != hipSuccess || hipMemset(pl->dbg, 0, 8 * sizeof(unsigned)) != hipSuccess ||
         hipMalloc((void **)&pl->Asplit, pl->ab) != hipSuccess ||
-        hipMalloc(&pl->Upack, ub) != hipSuccess || hipMalloc((void **)&pl->Vpack, vb) != hipSuccess ||
+        hipMalloc(&pl->Upack, ub) != hipSuccess || hipMalloc(&pl->Ufrag, ub) != hipSuccess ||
+        (desc->in_dtype == EXAT_BF16 && hipMalloc(&pl->Vfrag, (size_t)desc->P * pl->Jpad * 64 * 2) != hipSuccess) || hipMalloc((void **)&pl->Vpack, vb) != hipSuccess ||
         hipMalloc((void **)&pl->Wpack, wb) != hipSuccess || hipMalloc((void **)&pl->Q, qb) != hipSuccess) {
         (void)hipGetLastError();
         exat_plan_destroy(pl);
@@ -287,7 +333,7 @@ int exat_plan_create(exat_plan_t *plan, const exat_desc_t *desc)
 int exat_plan_destroy(exat_plan_t pl)
 {
     if (!pl) return EXAT_OK;
-    (void)hipFree(pl->Upack); (void)hipFree(pl->Vpack); (void)hipFree(pl->Wpack); (void)hipFree(pl->Q);
+    (void)hipFree(pl->Upack); (void)hipFree(pl->Ufrag); (void)hipFree(pl->Vfrag); (void)hipFree(pl->Vpack); (void)hipFree(pl->Wpack); (void)hipFree(pl->Q);
     (void)hipFree(pl->slots); (void)hipFree(pl->used_dev); (void)hipFree(pl->Asplit); (void)hipFree(pl->dbg);
     for (hipEvent_t e : pl->ev) if (e) (void)hipEventDestroy(e);
     delete pl;
@@ -304,10 +350,13 @@ int exat_set_factors(exat_plan_t pl, const float *U, int64_t ldU, const float *V
     const int64_t nu = (int64_t)pl->PLpad * pl->Ipad, nv = (int64_t)d.P * pl->Mpad * pl->Jpad, nw = (int64_t)d.P * d.K * pl->Npad;
     if (d.in_dtype == EXAT_BF16) {
         hipLaunchKernelGGL(k_pack_u<__bf16>, dim3(grid_for(nu)), dim3(256), 0, st, U, ldU, pl->PL, d.I, (__bf16 *)pl->Upack, pl->PLpad, pl->Ipad);
+        hipLaunchKernelGGL(k_pack_u_frag<__bf16>, dim3(grid_for(nu)), dim3(256), 0, st, U, ldU, pl->PL, d.I, (__bf16 *)pl->Ufrag, pl->PLpad / 32, pl->Ipad / 16);
+        hipLaunchKernelGGL(k_pack_v_frag, dim3(grid_for((int64_t)d.P * pl->Jpad * 64)), dim3(256), 0, st, V, ldV, d.P, d.M, d.J, (__bf16 *)pl->Vfrag, pl->Jpad);
         hipLaunchKernelGGL(k_pack_v<__bf16>, dim3(grid_for(nv)), dim3(256), 0, st, V, ldV, d.P, d.M, d.J, pl->Vpack, pl->Mpad, pl->Jpad);
         hipLaunchKernelGGL(k_pack_w<__bf16>, dim3(grid_for(nw)), dim3(256), 0, st, W, ldW, d.P, d.N, d.K, pl->Wpack, pl->Npad);
     } else {
         hipLaunchKernelGGL(k_pack_u<float>, dim3(grid_for(nu)), dim3(256), 0, st, U, ldU, pl->PL, d.I, (float *)pl->Upack, pl->PLpad, pl->Ipad);
+        hipLaunchKernelGGL(k_pack_u_frag<float>, dim3(grid_for(nu)), dim3(256), 0, st, U, ldU, pl->PL, d.I, (float *)pl->Ufrag, pl->PLpad / 32, pl->Ipad / 8);
         hipLaunchKernelGGL(k_pack_v<float>, dim3(grid_for(nv)), dim3(256), 0, st, V, ldV, d.P, d.M, d.J, pl->Vpack, pl->Mpad, pl->Jpad);
         hipLaunchKernelGGL(k_pack_w<float>, dim3(grid_for(nw)), dim3(256), 0, st, W, ldW, d.P, d.N, d.K, pl->Wpack, pl->Npad);
     }
