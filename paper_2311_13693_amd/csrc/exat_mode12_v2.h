@@ -15,6 +15,7 @@
 //     counter-based generator.
 #pragma once
 #include "exat_mode12.h"
+#include "exat_mode2.h"
 
 
 namespace exat {
@@ -24,44 +25,6 @@ struct GenSplitParams {
     int64_t Irows;
     int Rpad;
 };
-
-// Optional in-kernel bounds checking of every global access (template flag CHECKED): an address outside
-// its buffer is not dereferenced; the access is counted in dbg[0], its buffer id is flagged in dbg[1 + id],
-// and a zero is used instead.  The host reads the counters back through exat_plan_check_status.
-struct CheckParams {
-    const char *lo[6], *hi[6];  // 0: U, 1: A pieces, 2: B, 3: C, 4: V, 5: Q
-    unsigned *dbg;              // >= 8 counters
-};
-enum { CHK_U = 0, CHK_A = 1, CHK_B = 2, CHK_C = 3, CHK_V = 4, CHK_Q = 5 };
-
-template <bool CHECKED, typename V>
-__device__ __forceinline__ V ld_chk(const V *ptr, const CheckParams &ck, int id)
-{
-    if constexpr (CHECKED) {
-        const char *c = (const char *)ptr;
-        if (c < ck.lo[id] || c + sizeof(V) > ck.hi[id]) {
-            atomicAdd(&ck.dbg[0], 1u);
-            ck.dbg[1 + id] = 1u;
-            V z;
-            __builtin_memset(&z, 0, sizeof(V));
-            return z;
-        }
-    }
-    return *ptr;
-}
-template <bool CHECKED, typename V>
-__device__ __forceinline__ void st_chk(V *ptr, V v, const CheckParams &ck, int id)
-{
-    if constexpr (CHECKED) {
-        const char *c = (const char *)ptr;
-        if (c < ck.lo[id] || c + sizeof(V) > ck.hi[id]) {
-            atomicAdd(&ck.dbg[0], 1u);
-            ck.dbg[1 + id] = 1u;
-            return;
-        }
-    }
-    *ptr = v;
-}
 
 // MFMA 16x16x32 bf16: A lane (row l%16, k 8*(l/16)+e), B lane (col l%16, k 8*(l/16)+e),
 // C lane (col l%16, rows 4*(l/16)+r).
@@ -174,9 +137,10 @@ __global__ __launch_bounds__(64 * NW) void k_mode12_v2(const Mode12Params p, con
                     bf16x8 bh, bm, bl;
 #pragma unroll
                     for (int e = 0; e < 8; e++) {
-                        const int r = 32 * ks + 8 * q16 + e;
-                        float bc = 0.0f;
-                        if (colok && r < p.R) bc = ld_chk<CHECKED>(p.B + jj + p.ldB * r, ck, CHK_B) * ld_chk<CHECKED>(p.C + k + p.ldC * r, ck, CHK_C);
+                        // clamped, unconditional loads (no branch per element), masked afterwards
+                        const int r = 32 * ks + 8 * q16 + e, rr = r < p.R ? r : p.R - 1;
+                        float bc = ld_chk<CHECKED>(p.B + jj + p.ldB * rr, ck, CHK_B) * ld_chk<CHECKED>(p.C + k + p.ldC * rr, ck, CHK_C);
+                        bc = (colok && r < p.R) ? bc : 0.0f;
                         __bf16 h, m, l;
                         split3(bc, h, m, l);
                         bh[e] = h; bm[e] = m; bl[e] = l;
@@ -400,66 +364,11 @@ __global__ __launch_bounds__(64 * NW) void k_mode12_v2(const Mode12Params p, con
             __syncthreads();
         }
 
-        // ---- mode 2 on the finished Z chunk (same as k_mode12) ----
+        // ---- mode 2 on the finished Z chunk ----
         float *Zs = (float *)smem + wave * (32 * ZST);
         const bool first_chunk = (jc == ja0);
-#pragma unroll
-        for (int rt = 0; rt < RT; rt++) {
-            const int q0 = wrow0 + rt * 32;  // wave-uniform
-            if (q0 < p.PL) {
-#pragma unroll
-                for (int ct = 0; ct < CT; ct++)
-#pragma unroll
-                    for (int b4 = 0; b4 < 4; b4++)
-#pragma unroll
-                        for (int r = 0; r < 4; r++)
-                            Zs[(8 * b4 + 4 * hi + r) * ZST + ct * 32 + l32] = acc[rt][ct][4 * b4 + r];
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                __builtin_amdgcn_wave_barrier();
-                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-                const int qlast = (q0 + 31 < p.PL - 1) ? q0 + 31 : p.PL - 1;
-                const int pfirst = q0 / p.L, plast = qlast / p.L;
-                for (int pp = pfirst; pp <= plast; pp++) {
-                    f32x16 qa[2];
-#pragma unroll
-                    for (int mt = 0; mt < 2; mt++)
-#pragma unroll
-                        for (int e = 0; e < 16; e++) qa[mt][e] = 0.0f;
-                    const float *Vp = p.V + (int64_t)pp * p.Mpad * p.Jpad + jc;
-#pragma unroll 4
-                    for (int g8 = 0; g8 < COLS / 8; g8++) {
-                        const f32x4 av = *(const f32x4 *)(Zs + l32 * ZST + 8 * g8 + 4 * hi);
-#pragma unroll
-                        for (int mt = 0; mt < 2; mt++) {
-                            if (mt < p.MT) {
-                                const f32x4 bv = ld_chk<CHECKED>((const f32x4 *)(Vp + (int64_t)(mt * 32 + l32) * p.Jpad + 8 * g8 + 4 * hi), ck, CHK_V);
-                                mma_frag<float>::mma(qa[mt], av, bv);
-                            }
-                        }
-                    }
-                    const int rlo = pp * p.L, rhi = rlo + p.L;
-#pragma unroll
-                    for (int mt = 0; mt < 2; mt++) {
-                        if (mt < p.MT) {
-#pragma unroll
-                            for (int b4 = 0; b4 < 4; b4++)
-#pragma unroll
-                                for (int r = 0; r < 4; r++) {
-                                    const int row = q0 + 8 * b4 + 4 * hi + r;
-                                    if (row >= rlo && row < rhi) {
-                                        float *dst = p.Q + ((int64_t)kidx * p.PLpad + row) * p.Mpad + mt * 32 + l32;
-                                        float v = qa[mt][4 * b4 + r];
-                                        if (!first_chunk) v += ld_chk<CHECKED>((const float *)dst, ck, CHK_Q);
-                                        st_chk<CHECKED>(dst, v, ck, CHK_Q);
-                                    }
-                                }
-                        }
-                    }
-                }
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                __builtin_amdgcn_wave_barrier();
-            }
-        }
+        if (p.MT == 2) mode2_chunk<RT, CT, CHECKED, 2, false>(p, nullptr, ck, Zs, acc, wrow0, kidx, jc, first_chunk, lane);
+        else mode2_chunk<RT, CT, CHECKED, 1, false>(p, nullptr, ck, Zs, acc, wrow0, kidx, jc, first_chunk, lane);
     }
 }
 

@@ -55,7 +55,6 @@ template <> struct gen_terms<float> {
     static constexpr int B[6] = {0, 2, 1, 0, 1, 0};
 };
 
-template <int V> struct ic { static constexpr int value = V; };
 template <int... Ms, typename F>
 __device__ __forceinline__ void static_for_seq(std::integer_sequence<int, Ms...>, F &&f) { (f(ic<Ms>()), ...); }
 // f(ic<0>()), ..., f(ic<N-1>()): a loop whose index is a compile-time constant in the body
@@ -380,109 +379,11 @@ __global__ __launch_bounds__(64 * NW) void k_mode12_v3(const Mode12Params p, con
             }
         });
 
-        // ---- mode 2 on the finished Z chunk: per 32-row tile and per replica the tile touches,
-        //      Q[rows of that replica, :] += Z_tile V_p[:, chunk]^T ----
+        // ---- mode 2 on the finished Z chunk ----
         float *Zs = (float *)smem + wave * (32 * ZST);
         const bool first_chunk = (jc == ja0);
-        // MTC = number of 32-column tiles of M (1 or 2), a compile-time constant inside so that the loops below
-        // hold no branches
-        auto mode2 = [&](auto mtc) {
-        constexpr int MTC = decltype(mtc)::value;
-#pragma unroll
-        for (int rt = 0; rt < RT; rt++) {
-            const int q0 = wrow0 + rt * 32;  // wave-uniform
-            if (q0 < p.PL) {
-#pragma unroll
-                for (int ct = 0; ct < CT; ct++)
-#pragma unroll
-                    for (int b4 = 0; b4 < 4; b4++)
-#pragma unroll
-                        for (int r = 0; r < 4; r++)
-                            Zs[(8 * b4 + 4 * hi + r) * ZST + ct * 32 + l32] = acc[rt][ct][4 * b4 + r];
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                __builtin_amdgcn_wave_barrier();
-                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-                const int qlast = (q0 + 31 < p.PL - 1) ? q0 + 31 : p.PL - 1;
-                const int pfirst = q0 / p.L, plast = qlast / p.L;
-                // The 32 x Mpad block of Q this tile adds to: requested before the MFMAs that produce the addends,
-                // all of it and without conditions (the rows exist up to PLpad; rows of the padding hold zeros)
-                float *Qt = p.Q + ((int64_t)kidx * p.PLpad + q0 + 4 * hi) * p.Mpad + l32;  // + (8*b4 + r)*Mpad + 32*mt
-                float qsum[MTC][16];
-#pragma unroll
-                for (int mt = 0; mt < MTC; mt++)
-#pragma unroll
-                    for (int e = 0; e < 16; e++) qsum[mt][e] = 0.0f;
-                if (!first_chunk) {
-#pragma unroll
-                    for (int mt = 0; mt < MTC; mt++)
-#pragma unroll
-                        for (int e = 0; e < 16; e++)
-                            qsum[mt][e] = ld_chk<CHECKED>((const float *)(Qt + (8 * (e >> 2) + (e & 3)) * p.Mpad + 32 * mt), ck, CHK_Q);
-                }
-                for (int pp = pfirst; pp <= plast; pp++) {
-                    const int rlo = pp * p.L, rhi = rlo + p.L;
-                    f32x16 qa[MTC];
-#pragma unroll
-                    for (int mt = 0; mt < MTC; mt++)
-#pragma unroll
-                        for (int e = 0; e < 16; e++) qa[mt][e] = 0.0f;
-                    if constexpr (sizeof(T) == 2) {
-                        // bf16 matrix cores: Z = zh + zl (bf16 pieces), V_p in fragment order
-                        const bf16x8 *vf = (const bf16x8 *)uf.Vf + (((int64_t)pp * (p.Jpad / 16) + jc / 16) * 2) * 64 + lane;
-                        bf16x8 bv[COLS / 16][MTC];
-#pragma unroll
-                        for (int g16 = 0; g16 < COLS / 16; g16++)
-#pragma unroll
-                            for (int mt = 0; mt < MTC; mt++) bv[g16][mt] = vf[(g16 * 2 + mt) * 64];
-#pragma unroll
-                        for (int g16 = 0; g16 < COLS / 16; g16++) {
-                            const f32x4 z0 = *(const f32x4 *)(Zs + l32 * ZST + 16 * g16 + 8 * hi);
-                            const f32x4 z1 = *(const f32x4 *)(Zs + l32 * ZST + 16 * g16 + 8 * hi + 4);
-                            bf16x8 zh, zl;
-#pragma unroll
-                            for (int e = 0; e < 4; e++) {
-                                zh[e] = (__bf16)z0[e]; zl[e] = (__bf16)(z0[e] - (float)zh[e]);
-                                zh[4 + e] = (__bf16)z1[e]; zl[4 + e] = (__bf16)(z1[e] - (float)zh[4 + e]);
-                            }
-#pragma unroll
-                            for (int mt = 0; mt < MTC; mt++) {
-                                qa[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(zl, bv[g16][mt], qa[mt], 0, 0, 0);
-                                qa[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(zh, bv[g16][mt], qa[mt], 0, 0, 0);
-                            }
-                        }
-                    } else {
-                        const float *Vp = p.V + (int64_t)pp * p.Mpad * p.Jpad + jc;
-#pragma unroll 4
-                        for (int g8 = 0; g8 < COLS / 8; g8++) {
-                            const f32x4 av = *(const f32x4 *)(Zs + l32 * ZST + 8 * g8 + 4 * hi);
-#pragma unroll
-                            for (int mt = 0; mt < MTC; mt++) {
-                                const f32x4 bv = ld_chk<CHECKED>((const f32x4 *)(Vp + (int64_t)(mt * 32 + l32) * p.Jpad + 8 * g8 + 4 * hi), ck, CHK_V);
-                                mma_frag<float>::mma(qa[mt], av, bv);
-                            }
-                        }
-                    }
-                    // rows of replica pp take this product (a select, not a branch)
-#pragma unroll
-                    for (int mt = 0; mt < MTC; mt++)
-#pragma unroll
-                        for (int e = 0; e < 16; e++) {
-                            const int row = q0 + 8 * (e >> 2) + 4 * hi + (e & 3);
-                            qsum[mt][e] += (row >= rlo && row < rhi) ? qa[mt][e] : 0.0f;
-                        }
-                }
-#pragma unroll
-                for (int mt = 0; mt < MTC; mt++)
-#pragma unroll
-                    for (int e = 0; e < 16; e++)
-                        st_chk<CHECKED>(Qt + (8 * (e >> 2) + (e & 3)) * p.Mpad + 32 * mt, qsum[mt][e], ck, CHK_Q);
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                __builtin_amdgcn_wave_barrier();
-            }
-        }
-        };
-        if (p.MT == 2) mode2(ic<2>());
-        else mode2(ic<1>());
+        if (p.MT == 2) mode2_chunk<RT, CT, CHECKED, 2, sizeof(T) == 2>(p, uf.Vf, ck, Zs, acc, wrow0, kidx, jc, first_chunk, lane);
+        else mode2_chunk<RT, CT, CHECKED, 1, sizeof(T) == 2>(p, uf.Vf, ck, Zs, acc, wrow0, kidx, jc, first_chunk, lane);
     }
 }
 

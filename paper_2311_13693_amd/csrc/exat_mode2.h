@@ -1,0 +1,156 @@
+// Mode 2 of the compression chain on a finished Z chunk, shared by the pipelined mode-1/2 kernels:
+// per 32-row tile of a wave and per replica p the tile touches,
+//     Q[k][rows of p in the tile, 0..M) += Z_tile[rows, chunk columns] * V_p[:, chunk columns]^T.
+// Each wave passes its tile through a private LDS region (Zs) to turn the MFMA accumulator layout into
+// A-operand layout.  Nothing in the loops is conditional per element: the Q block is read and written whole
+// (its rows exist up to PLpad), V and B/C gathers are unconditional, the rows of a replica are picked with a
+// select.  Per-element branches here cost a scratch reload and a full memory wait each.
+#pragma once
+#include "exat_mode12.h"
+
+namespace exat {
+
+// Optional in-kernel bounds checking of every global access (template flag CHECKED): an address outside
+// its buffer is not dereferenced; the access is counted in dbg[0], its buffer id is flagged in dbg[1 + id],
+// and a zero is used instead.  The host reads the counters back through exat_plan_check_status.
+struct CheckParams {
+    const char *lo[6], *hi[6];  // 0: U, 1: A pieces, 2: B, 3: C, 4: V, 5: Q
+    unsigned *dbg;              // >= 8 counters
+};
+enum { CHK_U = 0, CHK_A = 1, CHK_B = 2, CHK_C = 3, CHK_V = 4, CHK_Q = 5 };
+
+template <bool CHECKED, typename V>
+__device__ __forceinline__ V ld_chk(const V *ptr, const CheckParams &ck, int id)
+{
+    if constexpr (CHECKED) {
+        const char *c = (const char *)ptr;
+        if (c < ck.lo[id] || c + sizeof(V) > ck.hi[id]) {
+            atomicAdd(&ck.dbg[0], 1u);
+            ck.dbg[1 + id] = 1u;
+            V z;
+            __builtin_memset(&z, 0, sizeof(V));
+            return z;
+        }
+    }
+    return *ptr;
+}
+template <bool CHECKED, typename V>
+__device__ __forceinline__ void st_chk(V *ptr, V v, const CheckParams &ck, int id)
+{
+    if constexpr (CHECKED) {
+        const char *c = (const char *)ptr;
+        if (c < ck.lo[id] || c + sizeof(V) > ck.hi[id]) {
+            atomicAdd(&ck.dbg[0], 1u);
+            ck.dbg[1 + id] = 1u;
+            return;
+        }
+    }
+    *ptr = v;
+}
+
+template <int V> struct ic { static constexpr int value = V; };
+
+// MTC: 32-column tiles of M (1 or 2).  BF16V: run on the bf16 matrix cores with Z split into two bf16 pieces
+// (error 2^-17) and V_p read from Vf in fragment order, [P][Jpad/16][2][64 lanes][8 bf16], lane l of fragment
+// (p, j16, mt) holding V_p[m = 32*mt + l%32, j = 16*j16 + 8*(l/32) .. +7]; otherwise fp32 MFMA and p.V.
+template <int RT, int CT, bool CHECKED, int MTC, bool BF16V>
+__device__ __forceinline__ void mode2_chunk(const Mode12Params &p, const void *Vf, const CheckParams &ck, float *Zs, const f32x16 (&acc)[RT][CT],
+                                            int wrow0, int kidx, int64_t jc, bool first_chunk, int lane)
+{
+    constexpr int COLS = 32 * CT, ZST = COLS + 4;
+    const int l32 = lane & 31, hi = lane >> 5;
+#pragma unroll
+    for (int rt = 0; rt < RT; rt++) {
+        const int q0 = wrow0 + rt * 32;  // wave-uniform
+        if (q0 < p.PL) {
+#pragma unroll
+            for (int ct = 0; ct < CT; ct++)
+#pragma unroll
+                for (int b4 = 0; b4 < 4; b4++)
+#pragma unroll
+                    for (int r = 0; r < 4; r++)
+                        Zs[(8 * b4 + 4 * hi + r) * ZST + ct * 32 + l32] = acc[rt][ct][4 * b4 + r];
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            const int qlast = (q0 + 31 < p.PL - 1) ? q0 + 31 : p.PL - 1;
+            const int pfirst = q0 / p.L, plast = qlast / p.L;
+            // The 32 x Mpad block of Q this tile adds to: requested before the MFMAs that produce the addends,
+            // all of it and without conditions (the rows exist up to PLpad; rows of the padding hold zeros)
+            float *Qt = p.Q + ((int64_t)kidx * p.PLpad + q0 + 4 * hi) * p.Mpad + l32;  // + (8*b4 + r)*Mpad + 32*mt
+            float qsum[MTC][16];
+#pragma unroll
+            for (int mt = 0; mt < MTC; mt++)
+#pragma unroll
+                for (int e = 0; e < 16; e++) qsum[mt][e] = 0.0f;
+            if (!first_chunk) {
+#pragma unroll
+                for (int mt = 0; mt < MTC; mt++)
+#pragma unroll
+                    for (int e = 0; e < 16; e++)
+                        qsum[mt][e] = ld_chk<CHECKED>((const float *)(Qt + (8 * (e >> 2) + (e & 3)) * p.Mpad + 32 * mt), ck, CHK_Q);
+            }
+            for (int pp = pfirst; pp <= plast; pp++) {
+                const int rlo = pp * p.L, rhi = rlo + p.L;
+                f32x16 qa[MTC];
+#pragma unroll
+                for (int mt = 0; mt < MTC; mt++)
+#pragma unroll
+                    for (int e = 0; e < 16; e++) qa[mt][e] = 0.0f;
+                if constexpr (BF16V) {
+                    // bf16 matrix cores: Z = zh + zl (bf16 pieces), V_p in fragment order
+                    const bf16x8 *vf = (const bf16x8 *)Vf + (((int64_t)pp * (p.Jpad / 16) + jc / 16) * 2) * 64 + lane;
+                    bf16x8 bv[COLS / 16][MTC];
+#pragma unroll
+                    for (int g16 = 0; g16 < COLS / 16; g16++)
+#pragma unroll
+                        for (int mt = 0; mt < MTC; mt++) bv[g16][mt] = vf[(g16 * 2 + mt) * 64];
+#pragma unroll
+                    for (int g16 = 0; g16 < COLS / 16; g16++) {
+                        const f32x4 z0 = *(const f32x4 *)(Zs + l32 * ZST + 16 * g16 + 8 * hi);
+                        const f32x4 z1 = *(const f32x4 *)(Zs + l32 * ZST + 16 * g16 + 8 * hi + 4);
+                        bf16x8 zh, zl;
+#pragma unroll
+                        for (int e = 0; e < 4; e++) {
+                            zh[e] = (__bf16)z0[e]; zl[e] = (__bf16)(z0[e] - (float)zh[e]);
+                            zh[4 + e] = (__bf16)z1[e]; zl[4 + e] = (__bf16)(z1[e] - (float)zh[4 + e]);
+                        }
+#pragma unroll
+                        for (int mt = 0; mt < MTC; mt++) {
+                            qa[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(zl, bv[g16][mt], qa[mt], 0, 0, 0);
+                            qa[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(zh, bv[g16][mt], qa[mt], 0, 0, 0);
+                        }
+                    }
+                } else {
+                    const float *Vp = p.V + (int64_t)pp * p.Mpad * p.Jpad + jc;
+#pragma unroll 4
+                    for (int g8 = 0; g8 < COLS / 8; g8++) {
+                        const f32x4 av = *(const f32x4 *)(Zs + l32 * ZST + 8 * g8 + 4 * hi);
+#pragma unroll
+                        for (int mt = 0; mt < MTC; mt++) {
+                            const f32x4 bv = ld_chk<CHECKED>((const f32x4 *)(Vp + (int64_t)(mt * 32 + l32) * p.Jpad + 8 * g8 + 4 * hi), ck, CHK_V);
+                            mma_frag<float>::mma(qa[mt], av, bv);
+                        }
+                    }
+                }
+                // rows of replica pp take this product (a select, not a branch)
+#pragma unroll
+                for (int mt = 0; mt < MTC; mt++)
+#pragma unroll
+                    for (int e = 0; e < 16; e++) {
+                        const int row = q0 + 8 * (e >> 2) + 4 * hi + (e & 3);
+                        qsum[mt][e] += (row >= rlo && row < rhi) ? qa[mt][e] : 0.0f;
+                    }
+            }
+#pragma unroll
+            for (int mt = 0; mt < MTC; mt++)
+#pragma unroll
+                for (int e = 0; e < 16; e++)
+                    st_chk<CHECKED>(Qt + (8 * (e >> 2) + (e & 3)) * p.Mpad + 32 * mt, qsum[mt][e], ck, CHK_Q);
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+        }
+    }
+}
+
+}  // namespace exat
