@@ -155,11 +155,11 @@ int launch_v2(const Mode12Params &mp, const GenSplitParams &gs, const CheckParam
     return boxed ? launch_v2_inst<T, NW, RT, SRC_GENERATED, 2, true>(mp, gs, ck, nk, st) : launch_v2_inst<T, NW, RT, SRC_GENERATED, 2, false>(mp, gs, ck, nk, st);
 }
 
-template <typename T, int NW, int RT, int SRC, int KS, bool BOXED, int DU, int DX>
+template <typename T, int NW, int RT, int SRC, int KS, bool BOXED, int DU, int DX, int WPS = (NW + 3) / 4>
 int launch_v3_inst(const Mode12Params &mp, const GenSplitParams &gs, const UFragParams &uf, const CheckParams &ck, int nk, hipStream_t st)
 {
     typedef Mode12V3Cfg<NW, RT> cfg;
-    auto kern = k_mode12_v3<T, NW, RT, SRC, KS, BOXED, false, DU, DX>;
+    auto kern = k_mode12_v3<T, NW, RT, SRC, KS, BOXED, false, DU, DX, WPS>;
     static bool attr_done = false;
     if (!attr_done) {
         if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, cfg::LDS_BYTES) != hipSuccess) return EXAT_ERR_HIP;
@@ -173,11 +173,11 @@ int launch_v3_inst(const Mode12Params &mp, const GenSplitParams &gs, const UFrag
 
 // materialised source: fp32 stages are long (fp32 MFMA), two register sets suffice; bf16 stages are 16 times
 // shorter and want the tiles requested further ahead
-template <typename T, int NW, int RT>
+template <typename T, int NW, int RT, int WPS = (NW + 3) / 4>
 int launch_v3_mat(const Mode12Params &mp, const GenSplitParams &gs, const UFragParams &uf, const CheckParams &ck, int nk, hipStream_t st)
 {
     constexpr int D = sizeof(T) == 2 ? 3 : 2, DXV = sizeof(T) == 2 ? 3 : 1;
-    return launch_v3_inst<T, NW, RT, SRC_MATERIALISED, 1, false, D, DXV>(mp, gs, uf, ck, nk, st);
+    return launch_v3_inst<T, NW, RT, SRC_MATERIALISED, 1, false, D, DXV, WPS>(mp, gs, uf, ck, nk, st);
 }
 
 // bf16 generated source, 4 waves
@@ -216,6 +216,9 @@ int run_chain(exat_plan_s *pl, Mode12Params mp, bool generated, float *Yout, int
         // kernel, violations counted in the plan's check counters), and only on request.
         if (bf && generated && rt == 4 && env_int("EXAT_BF16_8W_CHECKED", 0) == 0) rt = 3;
     }
+    // materialised source: two 4-wave workgroups per compute unit (256 rows each) instead of one 8-wave one
+    const bool two_wg = v2 && !generated && rt == 4 && env_int("EXAT_MAT_2WG", 0) != 0;
+    if (two_wg) rt = 2;
     const int rows = 128 * rt;
     mp.U = pl->Upack; mp.V = pl->Vpack; mp.Q = pl->Q;
     mp.I = pl->d.I; mp.Ipad = pl->Ipad; mp.Jpad = pl->Jpad;
@@ -248,7 +251,8 @@ int run_chain(exat_plan_s *pl, Mode12Params mp, bool generated, float *Yout, int
         // 4 waves; the fp32 generator keeps the LDS-staged kernel (its 8-wave build of this one spills more)
         const bool v3 = env_int("EXAT_V3", 1) != 0 && (!generated || (bf && rt != 4));
         if (v3 && !generated) {
-            if (bf) rc = rt == 4 ? launch_v3_mat<__bf16, 8, 2>(mp, gs, uf, ck, nk, st) : launch_v3_mat<__bf16, 4, 2>(mp, gs, uf, ck, nk, st);
+            if (two_wg) rc = bf ? launch_v3_mat<__bf16, 4, 2, 2>(mp, gs, uf, ck, nk, st) : launch_v3_mat<float, 4, 2, 2>(mp, gs, uf, ck, nk, st);
+            else if (bf) rc = rt == 4 ? launch_v3_mat<__bf16, 8, 2>(mp, gs, uf, ck, nk, st) : launch_v3_mat<__bf16, 4, 2>(mp, gs, uf, ck, nk, st);
             else rc = rt == 4 ? launch_v3_mat<float, 8, 2>(mp, gs, uf, ck, nk, st) : launch_v3_mat<float, 4, 2>(mp, gs, uf, ck, nk, st);
         } else if (v3) rc = rt == 3 ? launch_v3_gen_bf16<3>(mp, gs, uf, ck, ks, boxed, nk, st) : launch_v3_gen_bf16<2>(mp, gs, uf, ck, ks, boxed, nk, st);
         else if (bf && generated && rt == 4) rc = launch_v2_bf16_8w_gen_checked(mp, gs, ck, ks, boxed, nk, st);

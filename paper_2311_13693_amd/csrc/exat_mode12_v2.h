@@ -29,6 +29,9 @@ struct GenSplitParams {
 // MFMA 16x16x32 bf16: A lane (row l%16, k 8*(l/16)+e), B lane (col l%16, k 8*(l/16)+e),
 // C lane (col l%16, rows 4*(l/16)+r).
 typedef float f32x4v __attribute__((ext_vector_type(4)));
+#ifndef V2_VB
+#define V2_VB 4
+#endif
 
 template <typename T> struct v2geom;
 template <> struct v2geom<float> { static constexpr int EI = 16, NV = 3, NTERM = 6, SUBI = 1; };
@@ -367,8 +370,10 @@ __global__ __launch_bounds__(64 * NW) void k_mode12_v2(const Mode12Params p, con
         // ---- mode 2 on the finished Z chunk ----
         float *Zs = (float *)smem + wave * (32 * ZST);
         const bool first_chunk = (jc == ja0);
-        if (p.MT == 2) mode2_chunk<RT, CT, CHECKED, 2, false>(p, nullptr, ck, Zs, acc, wrow0, kidx, jc, first_chunk, lane);
-        else mode2_chunk<RT, CT, CHECKED, 1, false>(p, nullptr, ck, Zs, acc, wrow0, kidx, jc, first_chunk, lane);
+        // the generator's registers leave less room for V fragments in flight
+        constexpr int VB = SRC == SRC_GENERATED ? V2_VB : 16;
+        if (p.MT == 2) mode2_chunk<RT, CT, CHECKED, 2, false, VB>(p, nullptr, ck, Zs, acc, wrow0, kidx, jc, first_chunk, lane);
+        else mode2_chunk<RT, CT, CHECKED, 1, false, VB>(p, nullptr, ck, Zs, acc, wrow0, kidx, jc, first_chunk, lane);
     }
 }
 

@@ -81,8 +81,10 @@ constexpr int lcm_i(int a, int b) { return a / gcd_i(a, b) * b; }
 // DU: register sets of U fragments (fragments are requested DU stages ahead); DX: register sets of the
 // materialised X tile (requested DX + 1 stages ahead).  The stage loop is unrolled by lcm(2, DU, DX) so that
 // every set is addressed statically.
-template <typename T, int NW, int RT, int SRC, int KS, bool BOXED, bool CHECKED, int DU = 2, int DX = 1>
-__global__ __launch_bounds__(64 * NW) void k_mode12_v3(const Mode12Params p, const GenSplitParams gs, const UFragParams uf, const CheckParams ck)
+// WPS: waves per SIMD the register allocation must allow (2 with NW = 4 lets two workgroups share a compute unit,
+// so that one's chunk set-up and mode-2 phases run under the other's MFMA phase).
+template <typename T, int NW, int RT, int SRC, int KS, bool BOXED, bool CHECKED, int DU = 2, int DX = 1, int WPS = (NW + 3) / 4>
+__global__ __launch_bounds__(64 * NW, WPS) void k_mode12_v3(const Mode12Params p, const GenSplitParams gs, const UFragParams uf, const CheckParams ck)
 {
     typedef Mode12V3Cfg<NW, RT> cfg;
     typedef typename mma_frag<T>::type frag_t;
@@ -98,8 +100,7 @@ __global__ __launch_bounds__(64 * NW) void k_mode12_v3(const Mode12Params p, con
     static_assert(DU >= 2 && DX >= 1, "prefetch depths");
     extern __shared__ __align__(16) unsigned char smem[];
 
-    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, l32 = lane & 31, hi = lane >> 5;
-    const int l16 = lane & 15, q16 = lane >> 4;
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int nk = (int)(p.k1 - p.k0);
     const int bid = blockIdx.x, xcd = bid & 7, t = bid >> 3;
     // Workgroup ids go round-robin over the 8 XCDs.  Materialised source: the G row groups of one slice sit
@@ -117,13 +118,7 @@ __global__ __launch_bounds__(64 * NW) void k_mode12_v3(const Mode12Params p, con
     const int nstage = (int)((p.i1 - ia0 + EI - 1) / EI);
     const int64_t ja0 = (p.j0 / COLS) * COLS;
 
-    // A fragments of this wave: row tiles (row0/32 + wave*RT + rt), i group ig
-    const T *ufl = (const T *)uf.Uf + ((int64_t)(wrow0 >> 5) * uf.nig) * (64 * E16) + lane * E16;
     const int64_t u_rt_step = uf.nig * (64 * E16);
-    const int pr0 = tid >> 2, pf = tid & 3;
-    const int xs_w = pr0 * ROWB + pf * 16;                                        // materialised tile: + u*PSTEP*ROWB
-    const int xs_r = l32 * ROWB + hi * 16;                                        // + ct*32*ROWB + g2*32
-    const int xg_w = (WCOLS * wave + l16) * ROWB + (4 * q16) * (int)sizeof(T);    // generated tile: + sj*16*ROWB + si*16*sizeof(T)
 
     frag_t ufr[DU][RT][2];
     u32x4 xpre[SRC == SRC_MATERIALISED ? DX : 1][SRC == SRC_MATERIALISED ? XPT : 1];
@@ -136,6 +131,18 @@ __global__ __launch_bounds__(64 * NW) void k_mode12_v3(const Mode12Params p, con
     float amp[NSJ];
 
     for (int64_t jc = ja0; jc < p.j1; jc += COLS) {
+        // Per-lane offsets and pointers of the stage loop are derived again in every chunk from a copy of the
+        // thread id the compiler cannot see through.  Kept live across chunks they would sit in registers during
+        // the mode-2 phase, which then spills, and every reload of a spilled value is a full memory wait.
+        int tidc = tid;
+        asm volatile("" : "+v"(tidc));
+        const int lane = tidc & 63, l32 = lane & 31, hi = lane >> 5, l16 = lane & 15, q16 = lane >> 4;
+        // A fragments of this wave: row tiles (row0/32 + wave*RT + rt), i group ig
+        const T *ufl = (const T *)uf.Uf + ((int64_t)(wrow0 >> 5) * uf.nig) * (64 * E16) + lane * E16;
+        const int pr0 = tidc >> 2, pf = tidc & 3;
+        const int xs_w = pr0 * ROWB + pf * 16;                                        // materialised tile: + u*PSTEP*ROWB
+        const int xs_r = l32 * ROWB + hi * 16;                                        // + ct*32*ROWB + g2*32
+        const int xg_w = (WCOLS * wave + l16) * ROWB + (4 * q16) * (int)sizeof(T);    // generated tile: + sj*16*ROWB + si*16*sizeof(T)
         f32x16 acc[RT][CT];
 #pragma unroll
         for (int rt = 0; rt < RT; rt++)
@@ -382,8 +389,8 @@ __global__ __launch_bounds__(64 * NW) void k_mode12_v3(const Mode12Params p, con
         // ---- mode 2 on the finished Z chunk ----
         float *Zs = (float *)smem + wave * (32 * ZST);
         const bool first_chunk = (jc == ja0);
-        if (p.MT == 2) mode2_chunk<RT, CT, CHECKED, 2, sizeof(T) == 2>(p, uf.Vf, ck, Zs, acc, wrow0, kidx, jc, first_chunk, lane);
-        else mode2_chunk<RT, CT, CHECKED, 1, sizeof(T) == 2>(p, uf.Vf, ck, Zs, acc, wrow0, kidx, jc, first_chunk, lane);
+        if (p.MT == 2) mode2_chunk<RT, CT, CHECKED, 2, sizeof(T) == 2>(p, uf.Vf, ck, Zs, acc, wrow0, kidx, jc, first_chunk, tid & 63);
+        else mode2_chunk<RT, CT, CHECKED, 1, sizeof(T) == 2>(p, uf.Vf, ck, Zs, acc, wrow0, kidx, jc, first_chunk, tid & 63);
     }
 }
 

@@ -53,11 +53,13 @@ template <int V> struct ic { static constexpr int value = V; };
 // MTC: 32-column tiles of M (1 or 2).  BF16V: run on the bf16 matrix cores with Z split into two bf16 pieces
 // (error 2^-17) and V_p read from Vf in fragment order, [P][Jpad/16][2][64 lanes][8 bf16], lane l of fragment
 // (p, j16, mt) holding V_p[m = 32*mt + l%32, j = 16*j16 + 8*(l/32) .. +7]; otherwise fp32 MFMA and p.V.
-template <int RT, int CT, bool CHECKED, int MTC, bool BF16V>
+// VB: V fragments (of 8 columns) requested together on the fp32 path; 16 = a whole chunk, fewer where registers are short.
+template <int RT, int CT, bool CHECKED, int MTC, bool BF16V, int VB = 16>
 __device__ __forceinline__ void mode2_chunk(const Mode12Params &p, const void *Vf, const CheckParams &ck, float *Zs, const f32x16 (&acc)[RT][CT],
                                             int wrow0, int kidx, int64_t jc, bool first_chunk, int lane)
 {
     constexpr int COLS = 32 * CT, ZST = COLS + 4;
+    constexpr int MP = 32 * MTC;  // = p.Mpad; a constant here so that the 32 Q accesses of a tile differ by immediates
     const int l32 = lane & 31, hi = lane >> 5;
 #pragma unroll
     for (int rt = 0; rt < RT; rt++) {
@@ -77,7 +79,7 @@ __device__ __forceinline__ void mode2_chunk(const Mode12Params &p, const void *V
             const int pfirst = q0 / p.L, plast = qlast / p.L;
             // The 32 x Mpad block of Q this tile adds to: requested before the MFMAs that produce the addends,
             // all of it and without conditions (the rows exist up to PLpad; rows of the padding hold zeros)
-            float *Qt = p.Q + ((int64_t)kidx * p.PLpad + q0 + 4 * hi) * p.Mpad + l32;  // + (8*b4 + r)*Mpad + 32*mt
+            float *Qt = p.Q + ((int64_t)kidx * p.PLpad + q0 + 4 * hi) * MP + l32;  // + (8*b4 + r)*Mpad + 32*mt
             float qsum[MTC][16];
 #pragma unroll
             for (int mt = 0; mt < MTC; mt++)
@@ -88,7 +90,7 @@ __device__ __forceinline__ void mode2_chunk(const Mode12Params &p, const void *V
                 for (int mt = 0; mt < MTC; mt++)
 #pragma unroll
                     for (int e = 0; e < 16; e++)
-                        qsum[mt][e] = ld_chk<CHECKED>((const float *)(Qt + (8 * (e >> 2) + (e & 3)) * p.Mpad + 32 * mt), ck, CHK_Q);
+                        qsum[mt][e] = ld_chk<CHECKED>((const float *)(Qt + (8 * (e >> 2) + (e & 3)) * MP + 32 * mt), ck, CHK_Q);
             }
             for (int pp = pfirst; pp <= plast; pp++) {
                 const int rlo = pp * p.L, rhi = rlo + p.L;
@@ -105,6 +107,7 @@ __device__ __forceinline__ void mode2_chunk(const Mode12Params &p, const void *V
                     for (int g16 = 0; g16 < COLS / 16; g16++)
 #pragma unroll
                         for (int mt = 0; mt < MTC; mt++) bv[g16][mt] = vf[(g16 * 2 + mt) * 64];
+                    __builtin_amdgcn_sched_barrier(0);  // keeps the requests together, ahead of the first MFMA
 #pragma unroll
                     for (int g16 = 0; g16 < COLS / 16; g16++) {
                         const f32x4 z0 = *(const f32x4 *)(Zs + l32 * ZST + 16 * g16 + 8 * hi);
@@ -122,16 +125,24 @@ __device__ __forceinline__ void mode2_chunk(const Mode12Params &p, const void *V
                         }
                     }
                 } else {
-                    const float *Vp = p.V + (int64_t)pp * p.Mpad * p.Jpad + jc;
-#pragma unroll 4
-                    for (int g8 = 0; g8 < COLS / 8; g8++) {
-                        const f32x4 av = *(const f32x4 *)(Zs + l32 * ZST + 8 * g8 + 4 * hi);
+                    // all V fragments of one 32-column tile of M are requested together, then multiplied: left
+                    // to itself the compiler waits for each 16-byte load before its four MFMAs
+                    const float *Vp = p.V + (int64_t)pp * MP * p.Jpad + jc + (int64_t)l32 * p.Jpad + 4 * hi;
 #pragma unroll
-                        for (int mt = 0; mt < MTC; mt++) {
-                            const f32x4 bv = ld_chk<CHECKED>((const f32x4 *)(Vp + (int64_t)(mt * 32 + l32) * p.Jpad + 8 * g8 + 4 * hi), ck, CHK_V);
-                            mma_frag<float>::mma(qa[mt], av, bv);
+                    for (int mt = 0; mt < MTC; mt++)
+#pragma unroll
+                        for (int g0 = 0; g0 < COLS / 8; g0 += VB) {
+                            f32x4 bv[VB];
+#pragma unroll
+                            for (int g8 = 0; g8 < VB; g8++)
+                                bv[g8] = ld_chk<CHECKED>((const f32x4 *)(Vp + (int64_t)(mt * 32) * p.Jpad + 8 * (g0 + g8)), ck, CHK_V);
+                            __builtin_amdgcn_sched_barrier(0);  // keeps the requests together, ahead of the first MFMA
+#pragma unroll
+                            for (int g8 = 0; g8 < VB; g8++) {
+                                const f32x4 av = *(const f32x4 *)(Zs + l32 * ZST + 8 * (g0 + g8) + 4 * hi);
+                                mma_frag<float>::mma(qa[mt], av, bv[g8]);
+                            }
                         }
-                    }
                 }
                 // rows of replica pp take this product (a select, not a branch)
 #pragma unroll
@@ -146,7 +157,7 @@ __device__ __forceinline__ void mode2_chunk(const Mode12Params &p, const void *V
             for (int mt = 0; mt < MTC; mt++)
 #pragma unroll
                 for (int e = 0; e < 16; e++)
-                    st_chk<CHECKED>(Qt + (8 * (e >> 2) + (e & 3)) * p.Mpad + 32 * mt, qsum[mt][e], ck, CHK_Q);
+                    st_chk<CHECKED>(Qt + (8 * (e >> 2) + (e & 3)) * MP + 32 * mt, qsum[mt][e], ck, CHK_Q);
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
         }
