@@ -155,11 +155,11 @@ int launch_v2(const Mode12Params &mp, const GenSplitParams &gs, const CheckParam
     return boxed ? launch_v2_inst<T, NW, RT, SRC_GENERATED, 2, true>(mp, gs, ck, nk, st) : launch_v2_inst<T, NW, RT, SRC_GENERATED, 2, false>(mp, gs, ck, nk, st);
 }
 
-template <typename T, int NW, int RT, int SRC, int KS, bool BOXED, int DU, int DX, int WPS = (NW + 3) / 4>
+template <typename T, int NW, int RT, int SRC, int KS, bool BOXED, int DU, int DX, int WPS = (NW + 3) / 4, bool CHECKED = false>
 int launch_v3_inst(const Mode12Params &mp, const GenSplitParams &gs, const UFragParams &uf, const CheckParams &ck, int nk, hipStream_t st)
 {
     typedef Mode12V3Cfg<NW, RT> cfg;
-    auto kern = k_mode12_v3<T, NW, RT, SRC, KS, BOXED, false, DU, DX, WPS>;
+    auto kern = k_mode12_v3<T, NW, RT, SRC, KS, BOXED, CHECKED, DU, DX, WPS>;
     static bool attr_done = false;
     if (!attr_done) {
         if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, cfg::LDS_BYTES) != hipSuccess) return EXAT_ERR_HIP;
@@ -186,6 +186,13 @@ int launch_v3_gen_bf16(const Mode12Params &mp, const GenSplitParams &gs, const U
 {
     if (ks == 1) return boxed ? launch_v3_inst<__bf16, 4, RT, SRC_GENERATED, 1, true, 2, 1>(mp, gs, uf, ck, nk, st) : launch_v3_inst<__bf16, 4, RT, SRC_GENERATED, 1, false, 2, 1>(mp, gs, uf, ck, nk, st);
     return boxed ? launch_v3_inst<__bf16, 4, RT, SRC_GENERATED, 2, true, 2, 1>(mp, gs, uf, ck, nk, st) : launch_v3_inst<__bf16, 4, RT, SRC_GENERATED, 2, false, 2, 1>(mp, gs, uf, ck, nk, st);
+}
+
+// bf16 generated source, 8 waves x 2 row tiles (512 stacked rows), every global access bounds-checked in the kernel
+int launch_v3_gen_bf16_8w_checked(const Mode12Params &mp, const GenSplitParams &gs, const UFragParams &uf, const CheckParams &ck, int ks, bool boxed, int nk, hipStream_t st)
+{
+    if (ks == 1) return boxed ? launch_v3_inst<__bf16, 8, 2, SRC_GENERATED, 1, true, 2, 1, 2, true>(mp, gs, uf, ck, nk, st) : launch_v3_inst<__bf16, 8, 2, SRC_GENERATED, 1, false, 2, 1, 2, true>(mp, gs, uf, ck, nk, st);
+    return boxed ? launch_v3_inst<__bf16, 8, 2, SRC_GENERATED, 2, true, 2, 1, 2, true>(mp, gs, uf, ck, nk, st) : launch_v3_inst<__bf16, 8, 2, SRC_GENERATED, 2, false, 2, 1, 2, true>(mp, gs, uf, ck, nk, st);
 }
 
 // bf16, 8 waves, generated source: every global access of this variant is bounds-checked in the kernel
@@ -249,12 +256,17 @@ int run_chain(exat_plan_s *pl, Mode12Params mp, bool generated, float *Yout, int
         uf.Uf = pl->Ufrag; uf.nig = pl->Ipad / (bf ? 16 : 8); uf.Vf = pl->Vfrag;
         // fragment-ordered U (no LDS staging of U): every materialised source, and the bf16 generator with
         // 4 waves; the fp32 generator keeps the LDS-staged kernel (its 8-wave build of this one spills more)
-        const bool v3 = env_int("EXAT_V3", 1) != 0 && (!generated || (bf && rt != 4));
+        const bool v3 = env_int("EXAT_V3", 1) != 0 && (!generated || bf);
+        if (v3 && generated) {  // the bounds of the buffers this kernel reads U and V from
+            ck.lo[CHK_U] = (const char *)pl->Ufrag; ck.hi[CHK_U] = ck.lo[CHK_U] + pl->ub;
+            ck.lo[CHK_V] = (const char *)pl->Vfrag; ck.hi[CHK_V] = ck.lo[CHK_V] + (size_t)pl->d.P * pl->Jpad * 64 * 2;
+        }
         if (v3 && !generated) {
             if (two_wg) rc = bf ? launch_v3_mat<__bf16, 4, 2, 2>(mp, gs, uf, ck, nk, st) : launch_v3_mat<float, 4, 2, 2>(mp, gs, uf, ck, nk, st);
             else if (bf) rc = rt == 4 ? launch_v3_mat<__bf16, 8, 2>(mp, gs, uf, ck, nk, st) : launch_v3_mat<__bf16, 4, 2>(mp, gs, uf, ck, nk, st);
             else rc = rt == 4 ? launch_v3_mat<float, 8, 2>(mp, gs, uf, ck, nk, st) : launch_v3_mat<float, 4, 2>(mp, gs, uf, ck, nk, st);
-        } else if (v3) rc = rt == 3 ? launch_v3_gen_bf16<3>(mp, gs, uf, ck, ks, boxed, nk, st) : launch_v3_gen_bf16<2>(mp, gs, uf, ck, ks, boxed, nk, st);
+        } else if (v3 && rt == 4) rc = launch_v3_gen_bf16_8w_checked(mp, gs, uf, ck, ks, boxed, nk, st);
+        else if (v3) rc = rt == 3 ? launch_v3_gen_bf16<3>(mp, gs, uf, ck, ks, boxed, nk, st) : launch_v3_gen_bf16<2>(mp, gs, uf, ck, ks, boxed, nk, st);
         else if (bf && generated && rt == 4) rc = launch_v2_bf16_8w_gen_checked(mp, gs, ck, ks, boxed, nk, st);
         else if (bf && generated && rt == 3) rc = launch_v2<__bf16, 4, 3>(mp, gs, ck, true, ks, boxed, nk, st);
         else if (bf) rc = rt == 4 ? launch_v2<__bf16, 8, 2>(mp, gs, ck, generated, ks, boxed, nk, st) : launch_v2<__bf16, 4, 2>(mp, gs, ck, generated, ks, boxed, nk, st);

@@ -122,7 +122,7 @@ __global__ __launch_bounds__(64 * NW, WPS) void k_mode12_v3(const Mode12Params p
 
     frag_t ufr[DU][RT][2];
     u32x4 xpre[SRC == SRC_MATERIALISED ? DX : 1][SRC == SRC_MATERIALISED ? XPT : 1];
-    bf16x8 afrag[SRC == SRC_GENERATED ? NV * KS * SUBI : 1];
+    bf16x8 afrag[2][SRC == SRC_GENERATED ? NV * KS * SUBI : 1];  // A pieces of the stages whose low-rank tiles are next: [stage parity]
     bf16x8 bfrag[SRC == SRC_GENERATED ? NV * KS * NSJ : 1];
     f32x4v accg[2][SRC == SRC_GENERATED ? NQ : 1];  // low-rank part of the X tiles of stages s+1, s+2: [stage parity][quad]
     uint32_t nw[SRC == SRC_GENERATED ? NWD : 1];
@@ -205,7 +205,7 @@ __global__ __launch_bounds__(64 * NW, WPS) void k_mode12_v3(const Mode12Params p
                 }
             }
         };
-        auto load_a = [&](int s) {
+        auto load_a = [&](int s, bf16x8 *af) {
             if constexpr (SRC == SRC_GENERATED) {
                 const int64_t ib = stage_i(s);
 #pragma unroll
@@ -214,13 +214,13 @@ __global__ __launch_bounds__(64 * NW, WPS) void k_mode12_v3(const Mode12Params p
                     for (int ks = 0; ks < KS; ks++)
 #pragma unroll
                         for (int si = 0; si < SUBI; si++)
-                            afrag[(v * KS + ks) * SUBI + si] = ld_chk<CHECKED>((const bf16x8 *)(gs.Asp + ((int64_t)v * gs.Irows + ib + 16 * si + l16) * gs.Rpad + 32 * ks + 8 * q16), ck, CHK_A);
+                            af[(v * KS + ks) * SUBI + si] = ld_chk<CHECKED>((const bf16x8 *)(gs.Asp + ((int64_t)v * gs.Irows + ib + 16 * si + l16) * gs.Rpad + 32 * ks + 8 * q16), ck, CHK_A);
             }
         };
-        // one low-rank MFMA of the tile whose A fragments are loaded: term n of accumulator `dst`
-        auto gen_one = [&](int n, f32x4v *dst) {
+        // one low-rank MFMA of the tile whose A pieces are in af: term n of accumulator `dst`
+        auto gen_one = [&](int n, f32x4v *dst, const bf16x8 *af) {
             const int term = n % NTERM, ks = (n / NTERM) % KS, sub = n / (NTERM * KS), si = sub / NSJ, sj = sub % NSJ;
-            const bf16x8 av = afrag[(gen_terms<T>::A[term] * KS + ks) * SUBI + si];
+            const bf16x8 av = af[(gen_terms<T>::A[term] * KS + ks) * SUBI + si];
             const bf16x8 bv = bfrag[(gen_terms<T>::B[term] * KS + ks) * NSJ + sj];
             const f32x4v zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
             const f32x4v c = (term == 0 && ks == 0) ? zero4 : dst[sub];
@@ -333,13 +333,13 @@ __global__ __launch_bounds__(64 * NW, WPS) void k_mode12_v3(const Mode12Params p
                     __builtin_amdgcn_sched_barrier(0);
                     static_for<g1 - g0>([&](auto gc) {
                         constexpr int g = g0 + decltype(gc)::value;
-                        gen_one(g, accg[PH]);
+                        gen_one(g, accg[PH], afrag[PH]);
                         __builtin_amdgcn_sched_barrier(0);
                         constexpr int v0 = plan::uop_at(wb + 2 + g - g0), v1 = plan::uop_at(wb + 3 + g - g0);
                         static_for<v1 - v0>([&](auto uc) { uop(ic<v0 + decltype(uc)::value>(), ib1, oth, accg[PH ^ 1]); });
                         __builtin_amdgcn_sched_barrier(0);
                     });
-                    if constexpr (g1 == NGEN && g0 < NGEN) load_a(s + 3);  // the A pieces are free now: request those of stage s+3
+                    if constexpr (g1 == NGEN && g0 < NGEN) load_a(s + 4, afrag[PH]);  // these A pieces are free now: request those of stage s+4
                 }
             });
         };
@@ -358,19 +358,19 @@ __global__ __launch_bounds__(64 * NW, WPS) void k_mode12_v3(const Mode12Params p
 #pragma unroll
             for (int d = 0; d < DX; d++) load_x(d, xpre[d]);
         }
-        load_a(0);
+        load_a(0, afrag[0]); load_a(1, afrag[1]);
         if constexpr (SRC == SRC_GENERATED) {
 #pragma unroll
-            for (int n = 0; n < NGEN; n++) gen_one(n, accg[0]);
+            for (int n = 0; n < NGEN; n++) gen_one(n, accg[0], afrag[0]);
         }
         __syncthreads();  // the previous chunk's epilogue is done with the LDS
         commit_plain(0, smem, accg[0]);
-        load_x(DX, xpre[0]); load_a(1);
+        load_x(DX, xpre[0]); load_a(2, afrag[0]);
         if constexpr (SRC == SRC_GENERATED) {
 #pragma unroll
-            for (int n = 0; n < NGEN; n++) gen_one(n, accg[1]);
+            for (int n = 0; n < NGEN; n++) gen_one(n, accg[1], afrag[1]);
         }
-        load_a(2);
+        load_a(3, afrag[1]);
         __syncthreads();
 
         int s = 0;

@@ -106,7 +106,7 @@ __device__ __forceinline__ void mode2_chunk(const Mode12Params &p, const void *V
 #pragma unroll
                     for (int g16 = 0; g16 < COLS / 16; g16++)
 #pragma unroll
-                        for (int mt = 0; mt < MTC; mt++) bv[g16][mt] = vf[(g16 * 2 + mt) * 64];
+                        for (int mt = 0; mt < MTC; mt++) bv[g16][mt] = ld_chk<CHECKED>(vf + (g16 * 2 + mt) * 64, ck, CHK_V);
                     __builtin_amdgcn_sched_barrier(0);  // keeps the requests together, ahead of the first MFMA
 #pragma unroll
                     for (int g16 = 0; g16 < COLS / 16; g16++) {

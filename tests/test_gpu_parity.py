@@ -296,6 +296,7 @@ def test_pipelined_materialised_variants(dtype, P, L):
 def test_bf16_8wave_generator_runs_bounds_checked_and_clean():
     # this variant only runs with every global access validated in the kernel; the counters must stay zero
     os.environ["EXAT_BF16_8W_CHECKED"] = "1"
+    os.environ["EXAT_RT"] = "4"
     try:
         cfg = wl.small(name="bf16_8w_chk", index=340, dtype="bf16", I=96, J=140, K=5, R=32, P=11, L=50, M=50, N=50,
                        dI=48, dJ=70, dK=5)
@@ -314,3 +315,4 @@ def test_bf16_8wave_generator_runs_bounds_checked_and_clean():
         plan.close()
     finally:
         os.environ.pop("EXAT_BF16_8W_CHECKED", None)
+        os.environ.pop("EXAT_RT", None)
