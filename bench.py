@@ -21,7 +21,7 @@ PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}   # MI355X dense MFMA peaks
 # HBM-side bytes of one launch of the fused mode-1/2 kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE passes,
 # scaled by the same counters on a plain device copy (figures and commands: profiles/*_hbm_counters.txt).
 # Counter passes are separate runs, so this is a recorded value, not one measured by this script.
-TRAFFIC_BYTES = {"cfg2": 1.335e9}
+TRAFFIC_BYTES = {"cfg2": 1.163e9}
 
 
 def parse():
@@ -152,7 +152,7 @@ def main():
         "ttm_frac_of_mfma_peak": cfg.flops * frac / (ms_step * 1e-3) / 1e12 / peak,
         "kernel_ms": {"mode12": ms12, "mode3": ms3},
         "operand_prep_ms": t_prep * 1e3,
-        "roofline": {"bound": "mfma", "kernel": "k_mode12", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
+        "roofline": {"bound": "mfma", "kernel": "k_mode12_v2" if cfg.name == "cfg4" else "k_mode12_v3", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
                      "frac": achieved / peak,
                      "traffic": TRAFFIC_BYTES.get(cfg.name) if frac == 1.0 else None},
     }
