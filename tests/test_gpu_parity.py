@@ -293,6 +293,33 @@ def test_pipelined_materialised_variants(dtype, P, L):
     plan.close()
 
 
+# The stage loop of the fragment-ordered kernel is unrolled by the number of register sets (2 for fp32, 6 for
+# bf16 materialised tiles) and finishes with a guarded remainder: every stage count from 1 up to past two
+# unrolled bodies, for the 4- and the 8-wave tile, materialised and generated.
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("P", [2, 6])
+def test_stage_count_sweep(dtype, P):
+    ei = 32 if dtype == "bf16" else 16
+    worst_m, worst_g = 0.0, 0.0
+    for nstage in (1, 2, 3, 5, 6, 7, 13):
+        cfg = wl.small(name="stages", index=400 + nstage, dtype=dtype, I=ei * nstage, J=140, K=3, R=5, P=P, L=50, M=34, N=5,
+                       dI=ei * nstage, dJ=70, dK=3)
+        A, B, C, U, V, W = _inputs(cfg)
+        plan = gu.plan_with_factors(cfg, U, V, W)
+        bf = dtype == "bf16"
+        X = oracle.gen_box(A, B, C, cfg.seed, cfg.sigma, to_bf16=bf)
+        rb = oracle.round_bf16 if bf else (lambda a: a)
+        Yr = oracle.comp_multi(X, rb(U), rb(V), rb(W), cfg.P)
+        em = oracle.rel_fro(gu.y_to_numpy(plan.compress(gu.to_dev_x(X, bf16=bf)), cfg), Yr)
+        Yo = oracle.comp_multi(oracle.gen_box(A, B, C, cfg.seed, cfg.sigma), U, V, W, cfg.P)
+        eg = oracle.rel_fro(gu.y_to_numpy(plan.compress_gen(gu.gen_of(cfg, A, B, C)), cfg), Yo)
+        _say("  %s P=%d stages=%d: materialised %.3e, generated %.3e" % (dtype, P, nstage, em, eg))
+        worst_m, worst_g = max(worst_m, em), max(worst_g, eg)
+        plan.close()
+    assert worst_m <= 1e-5
+    assert worst_g <= (TOL_BF16 if dtype == "bf16" else TOL_F32)
+
+
 def test_bf16_8wave_generator_runs_bounds_checked_and_clean():
     # this variant only runs with every global access validated in the kernel; the counters must stay zero
     os.environ["EXAT_BF16_8W_CHECKED"] = "1"
