@@ -147,12 +147,12 @@ int launch_v2_inst(const Mode12Params &mp, const GenSplitParams &gs, const Check
     return hipGetLastError() == hipSuccess ? EXAT_OK : EXAT_ERR_HIP;
 }
 
-template <typename T, int NW, int RT>
-int launch_v2(const Mode12Params &mp, const GenSplitParams &gs, const CheckParams &ck, bool generated, int ks, bool boxed, int nk, hipStream_t st)
+// fp32 generated source (LDS-staged U)
+template <int NW, int RT>
+int launch_v2_gen_f32(const Mode12Params &mp, const GenSplitParams &gs, const CheckParams &ck, int ks, bool boxed, int nk, hipStream_t st)
 {
-    if (!generated) return launch_v2_inst<T, NW, RT, SRC_MATERIALISED, 1, false>(mp, gs, ck, nk, st);
-    if (ks == 1) return boxed ? launch_v2_inst<T, NW, RT, SRC_GENERATED, 1, true>(mp, gs, ck, nk, st) : launch_v2_inst<T, NW, RT, SRC_GENERATED, 1, false>(mp, gs, ck, nk, st);
-    return boxed ? launch_v2_inst<T, NW, RT, SRC_GENERATED, 2, true>(mp, gs, ck, nk, st) : launch_v2_inst<T, NW, RT, SRC_GENERATED, 2, false>(mp, gs, ck, nk, st);
+    if (ks == 1) return boxed ? launch_v2_inst<float, NW, RT, SRC_GENERATED, 1, true>(mp, gs, ck, nk, st) : launch_v2_inst<float, NW, RT, SRC_GENERATED, 1, false>(mp, gs, ck, nk, st);
+    return boxed ? launch_v2_inst<float, NW, RT, SRC_GENERATED, 2, true>(mp, gs, ck, nk, st) : launch_v2_inst<float, NW, RT, SRC_GENERATED, 2, false>(mp, gs, ck, nk, st);
 }
 
 template <typename T, int NW, int RT, int SRC, int KS, bool BOXED, int DU, int DX, int WPS = (NW + 3) / 4, bool CHECKED = false>
@@ -173,11 +173,11 @@ int launch_v3_inst(const Mode12Params &mp, const GenSplitParams &gs, const UFrag
 
 // materialised source: fp32 stages are long (fp32 MFMA), two register sets suffice; bf16 stages are 16 times
 // shorter and want the tiles requested further ahead
-template <typename T, int NW, int RT, int WPS = (NW + 3) / 4>
+template <typename T, int NW, int RT>
 int launch_v3_mat(const Mode12Params &mp, const GenSplitParams &gs, const UFragParams &uf, const CheckParams &ck, int nk, hipStream_t st)
 {
     constexpr int D = sizeof(T) == 2 ? 3 : 2, DXV = sizeof(T) == 2 ? 3 : 1;
-    return launch_v3_inst<T, NW, RT, SRC_MATERIALISED, 1, false, D, DXV, WPS>(mp, gs, uf, ck, nk, st);
+    return launch_v3_inst<T, NW, RT, SRC_MATERIALISED, 1, false, D, DXV>(mp, gs, uf, ck, nk, st);
 }
 
 // bf16 generated source, 4 waves
@@ -195,37 +195,30 @@ int launch_v3_gen_bf16_8w_checked(const Mode12Params &mp, const GenSplitParams &
     return boxed ? launch_v3_inst<__bf16, 8, 2, SRC_GENERATED, 2, true, 2, 1, 2, true>(mp, gs, uf, ck, nk, st) : launch_v3_inst<__bf16, 8, 2, SRC_GENERATED, 2, false, 2, 1, 2, true>(mp, gs, uf, ck, nk, st);
 }
 
-// bf16, 8 waves, generated source: every global access of this variant is bounds-checked in the kernel
-int launch_v2_bf16_8w_gen_checked(const Mode12Params &mp, const GenSplitParams &gs, const CheckParams &ck, int ks, bool boxed, int nk, hipStream_t st)
-{
-    if (ks == 1) return boxed ? launch_v2_inst<__bf16, 8, 2, SRC_GENERATED, 1, true, true>(mp, gs, ck, nk, st) : launch_v2_inst<__bf16, 8, 2, SRC_GENERATED, 1, false, true>(mp, gs, ck, nk, st);
-    return boxed ? launch_v2_inst<__bf16, 8, 2, SRC_GENERATED, 2, true, true>(mp, gs, ck, nk, st) : launch_v2_inst<__bf16, 8, 2, SRC_GENERATED, 2, false, true>(mp, gs, ck, nk, st);
-}
-
 // fills the plan-dependent part of the parameters and launches mode 1+2 followed by mode 3
 int run_chain(exat_plan_s *pl, Mode12Params mp, bool generated, float *Yout, int accumulate, hipStream_t st)
 {
-    // the pipelined kernel needs whole 64-byte stages of i inside the box (materialised source) or a
-    // factor rank that fits its generator (generated source); everything else takes the generic kernel
+    // The pipelined kernels need whole 64-byte stages of i inside the box (materialised source) or a factor
+    // rank that fits their generator (generated source); everything else takes the generic kernel.
+    // EXAT_PIPELINED=0 forces the generic kernel (a testing aid).
     const bool bf = pl->d.in_dtype == EXAT_BF16;
     const int ei = bf ? 32 : 16;
-    bool v2 = env_int("EXAT_V2", 1) != 0;
-    if (generated) v2 = v2 && mp.R <= 64;
-    else v2 = v2 && mp.x_vec && (mp.i0 % ei == 0) && ((mp.i1 - mp.i0) % ei == 0);
+    bool pipelined = env_int("EXAT_PIPELINED", 1) != 0;
+    if (generated) pipelined = pipelined && mp.R <= 64;
+    else pipelined = pipelined && mp.x_vec && (mp.i0 % ei == 0) && ((mp.i1 - mp.i0) % ei == 0);
     int rt = choose_rt(pl, generated);
-    if (v2) {
+    if (pipelined) {
+        // rt = 128-row units of the workgroup tile: 2 = 4 waves x 2 row tiles, 3 = 4 waves x 3, 4 = 8 waves x 2
         const int forced = env_int("EXAT_RT", 0);
-        rt = (forced == 2 || forced == 4) ? forced : (pl->PL > 256 ? 4 : 2);  // rt 4 = 8 waves x 2 row tiles
-        // bf16 generated source: 4 waves x 3 row tiles (384 stacked rows) unless told otherwise
+        rt = (forced == 2 || forced == 4) ? forced : (pl->PL > 256 ? 4 : 2);
+        // bf16 generated source: 4 waves x 3 row tiles (384 stacked rows), one wave per SIMD, unless told otherwise
         if (bf && generated && pl->PL > 256 && forced != 2 && forced != 4) rt = 3;
-        // The 8-wave bf16 generator variant faulted on the GPU at the 10000^3 size for a reason not yet
-        // found by reading.  It only runs in its bounds-checked form (every global access validated in the
-        // kernel, violations counted in the plan's check counters), and only on request.
+        // An 8-wave bf16 generator build (of an earlier kernel) faulted on the GPU at the 10000^3 size for a
+        // reason not found by reading.  8-wave bf16 generator variants only run in their bounds-checked form
+        // (every global access validated in the kernel, violations counted in the plan's check counters), and
+        // only on request.
         if (bf && generated && rt == 4 && env_int("EXAT_BF16_8W_CHECKED", 0) == 0) rt = 3;
     }
-    // materialised source: two 4-wave workgroups per compute unit (256 rows each) instead of one 8-wave one
-    const bool two_wg = v2 && !generated && rt == 4 && env_int("EXAT_MAT_2WG", 0) != 0;
-    if (two_wg) rt = 2;
     const int rows = 128 * rt;
     mp.U = pl->Upack; mp.V = pl->Vpack; mp.Q = pl->Q;
     mp.I = pl->d.I; mp.Ipad = pl->Ipad; mp.Jpad = pl->Jpad;
@@ -235,42 +228,39 @@ int run_chain(exat_plan_s *pl, Mode12Params mp, bool generated, float *Yout, int
     int rc;
     GenSplitParams gs;
     gs.Asp = pl->Asplit; gs.Irows = pl->Ipad; gs.Rpad = 32 * ((mp.R + 31) / 32);
-    if (v2 && generated) {
+    if (pipelined && generated) {
         const int64_t n = gs.Irows * gs.Rpad;
         hipLaunchKernelGGL(k_split_a, dim3(grid_for(n)), dim3(256), 0, st, mp.A, pl->d.I, mp.R, pl->Asplit, gs.Irows, gs.Rpad, bf ? 2 : 3);
         if (hipGetLastError() != hipSuccess) return EXAT_ERR_HIP;
     }
     if (pl->timing && hipEventRecord(pl->ev[0], st) != hipSuccess) return EXAT_ERR_HIP;
-    if (v2) {
+    if (pipelined) {
         const bool boxed = generated && (mp.i0 != 0 || mp.i1 != pl->d.I);
         const int ks = gs.Rpad / 32;
+        // Fragment-ordered U (k_mode12_v3): every materialised source and the bf16 generator.  The fp32
+        // generator keeps the LDS-staged kernel (k_mode12_v2): its 8-wave build of the other one spills in
+        // the stage loop.
+        const bool frag = !generated || bf;
         CheckParams ck;
         memset(&ck, 0, sizeof(ck));
         ck.dbg = pl->dbg;
-        if (generated) {
-            const char *lo[6] = {(const char *)pl->Upack, (const char *)pl->Asplit, (const char *)mp.B, (const char *)mp.C, (const char *)pl->Vpack, (const char *)pl->Q};
-            const size_t sz[6] = {pl->ub, pl->ab, (size_t)pl->d.J * mp.R * 4, (size_t)pl->d.K * mp.R * 4, pl->vb, pl->qb};
+        if (generated) {  // buffer bounds for the bounds-checked variants
+            const char *lo[6] = {(const char *)(frag ? pl->Ufrag : pl->Upack), (const char *)pl->Asplit, (const char *)mp.B, (const char *)mp.C,
+                                 (const char *)(frag ? pl->Vfrag : (void *)pl->Vpack), (const char *)pl->Q};
+            const size_t sz[6] = {pl->ub, pl->ab, (size_t)pl->d.J * mp.R * 4, (size_t)pl->d.K * mp.R * 4,
+                                  frag ? (size_t)pl->d.P * pl->Jpad * 64 * 2 : pl->vb, pl->qb};
             for (int t = 0; t < 6; t++) { ck.lo[t] = lo[t]; ck.hi[t] = lo[t] + sz[t]; }
         }
         UFragParams uf;
         uf.Uf = pl->Ufrag; uf.nig = pl->Ipad / (bf ? 16 : 8); uf.Vf = pl->Vfrag;
-        // fragment-ordered U (no LDS staging of U): every materialised source, and the bf16 generator with
-        // 4 waves; the fp32 generator keeps the LDS-staged kernel (its 8-wave build of this one spills more)
-        const bool v3 = env_int("EXAT_V3", 1) != 0 && (!generated || bf);
-        if (v3 && generated) {  // the bounds of the buffers this kernel reads U and V from
-            ck.lo[CHK_U] = (const char *)pl->Ufrag; ck.hi[CHK_U] = ck.lo[CHK_U] + pl->ub;
-            ck.lo[CHK_V] = (const char *)pl->Vfrag; ck.hi[CHK_V] = ck.lo[CHK_V] + (size_t)pl->d.P * pl->Jpad * 64 * 2;
-        }
-        if (v3 && !generated) {
-            if (two_wg) rc = bf ? launch_v3_mat<__bf16, 4, 2, 2>(mp, gs, uf, ck, nk, st) : launch_v3_mat<float, 4, 2, 2>(mp, gs, uf, ck, nk, st);
-            else if (bf) rc = rt == 4 ? launch_v3_mat<__bf16, 8, 2>(mp, gs, uf, ck, nk, st) : launch_v3_mat<__bf16, 4, 2>(mp, gs, uf, ck, nk, st);
+        if (!generated) {
+            if (bf) rc = rt == 4 ? launch_v3_mat<__bf16, 8, 2>(mp, gs, uf, ck, nk, st) : launch_v3_mat<__bf16, 4, 2>(mp, gs, uf, ck, nk, st);
             else rc = rt == 4 ? launch_v3_mat<float, 8, 2>(mp, gs, uf, ck, nk, st) : launch_v3_mat<float, 4, 2>(mp, gs, uf, ck, nk, st);
-        } else if (v3 && rt == 4) rc = launch_v3_gen_bf16_8w_checked(mp, gs, uf, ck, ks, boxed, nk, st);
-        else if (v3) rc = rt == 3 ? launch_v3_gen_bf16<3>(mp, gs, uf, ck, ks, boxed, nk, st) : launch_v3_gen_bf16<2>(mp, gs, uf, ck, ks, boxed, nk, st);
-        else if (bf && generated && rt == 4) rc = launch_v2_bf16_8w_gen_checked(mp, gs, ck, ks, boxed, nk, st);
-        else if (bf && generated && rt == 3) rc = launch_v2<__bf16, 4, 3>(mp, gs, ck, true, ks, boxed, nk, st);
-        else if (bf) rc = rt == 4 ? launch_v2<__bf16, 8, 2>(mp, gs, ck, generated, ks, boxed, nk, st) : launch_v2<__bf16, 4, 2>(mp, gs, ck, generated, ks, boxed, nk, st);
-        else rc = rt == 4 ? launch_v2<float, 8, 2>(mp, gs, ck, generated, ks, boxed, nk, st) : launch_v2<float, 4, 2>(mp, gs, ck, generated, ks, boxed, nk, st);
+        } else if (bf) {
+            if (rt == 4) rc = launch_v3_gen_bf16_8w_checked(mp, gs, uf, ck, ks, boxed, nk, st);
+            else rc = rt == 3 ? launch_v3_gen_bf16<3>(mp, gs, uf, ck, ks, boxed, nk, st) : launch_v3_gen_bf16<2>(mp, gs, uf, ck, ks, boxed, nk, st);
+        } else
+            rc = rt == 4 ? launch_v2_gen_f32<8, 2>(mp, gs, ck, ks, boxed, nk, st) : launch_v2_gen_f32<4, 2>(mp, gs, ck, ks, boxed, nk, st);
     } else if (pl->d.in_dtype == EXAT_BF16)
         rc = generated ? launch_mode12_bf16<SRC_GENERATED>(rt, mp, nk, st) : launch_mode12_bf16<SRC_MATERIALISED>(rt, mp, nk, st);
     else

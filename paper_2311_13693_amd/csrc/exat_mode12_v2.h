@@ -1,4 +1,6 @@
-// Fused mode-1 + mode-2 kernel, software-pipelined variant for the large configurations.
+// Fused mode-1 + mode-2 kernel, software-pipelined variant with the U tile staged through LDS.  The host uses
+// it for the fp32 generated source (two waves per SIMD); every other aligned case runs k_mode12_v3, which
+// includes this header for the pieces the two share (generator operand splitting, geometry).
 //
 // Same decomposition as k_mode12 (one workgroup = one slice k x one group of ROWS stacked rows,
 // full i reduction per 128-fibre column chunk, mode 2 on the finished Z chunk), with
@@ -283,87 +285,9 @@ __global__ __launch_bounds__(64 * NW) void k_mode12_v2(const Mode12Params p, con
 #pragma unroll
                     for (int ct = 0; ct < CT; ct++) mma_frag<T>::mma(acc[rt][ct], a[g2][rt], bx[g2][ct]);
         };
-        // Interleaved iteration for one wave per SIMD (4-wave bf16 generator): such a wave issues in order, so
-        // the generator's vector work only overlaps the matrix pipe if it sits between the MFMAs in program
-        // order.  The noise of stage s+1 is cut into 16 pieces (4 hashes, 8 Box-Muller pairs, 4 add/convert/
-        // LDS-write steps), the low-rank MFMAs of stage s+2 into single instructions, and one piece of each is
-        // placed after every MFMA of stage s; scheduling barriers keep the pieces where they are put.
-        constexpr bool WEAVE = (SRC == SRC_GENERATED) && (sizeof(T) == 2) && (NW == 4);
-        uint32_t hw[WEAVE ? 4 : 1][2];
-        float zz[WEAVE ? 4 : 1][4];
-        f32x4v accn[WEAVE ? SUBI * NSJ : 1];
-        auto woven = [&](int s) {
-            if constexpr (WEAVE) {
-                const unsigned char *base = smem + (s & 1) * cfg::BUF_BYTES;
-                unsigned char *obase = smem + ((s + 1) & 1) * cfg::BUF_BYTES;
-                const int64_t ib1 = stage_i(s + 1);
-                frag_t a[2][RT], bx[2][CT];
-#pragma unroll
-                for (int g2 = 0; g2 < 2; g2++) {
-#pragma unroll
-                    for (int rt = 0; rt < RT; rt++) a[g2][rt] = *(const frag_t *)(base + us_r + rt * 32 * ROWB + g2 * 32);
-#pragma unroll
-                    for (int ct = 0; ct < CT; ct++) bx[g2][ct] = *(const frag_t *)(base + xs_r + ct * 32 * ROWB + g2 * 32);
-                }
-#pragma unroll
-                for (int u = 0; u < UPT; u++) *(u32x4 *)(obase + us_w + u * PSTEP * ROWB) = upre[u];
-                load_u(s + 2);
-                __builtin_amdgcn_sched_barrier(0);
-                constexpr int NMAIN = 2 * RT * CT, NGEN = SUBI * NSJ * KS * 3, GPS = (NGEN + 11) / 12;
-                static_assert(NMAIN >= 16, "the 16 noise pieces need 16 MFMA slots");
-#pragma unroll
-                for (int m = 0; m < NMAIN; m++) {
-                    const int g2 = m / (RT * CT), rt = (m / CT) % RT, ct = m % CT;
-                    mma_frag<T>::mma(acc[rt][ct], a[g2][rt], bx[g2][ct]);
-                    __builtin_amdgcn_sched_barrier(0);
-                    // low-rank MFMAs of stage s+2 (A fragments loaded one iteration ago) into accn
-#pragma unroll
-                    for (int gg = 0; gg < GPS; gg++) {
-                        const int n = m * GPS + gg;
-                        if (m < 12 && n < NGEN) {
-                            const int term = n % 3, ks = (n / 3) % KS, sub = n / (3 * KS), si = sub / NSJ, sj = sub % NSJ;
-                            const bf16x8 av = afrag[((term == 0 ? 1 : 0) * KS + ks) * SUBI + si];   // m*h, h*m, h*h
-                            const bf16x8 bv = bfrag[((term == 1 ? 1 : 0) * KS + ks) * NSJ + sj];
-                            const f32x4v zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
-                            const f32x4v c = (term == 0 && ks == 0) ? zero4 : accn[sub];
-                            accn[sub] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, bv, c, 0, 0, 0);
-                        }
-                    }
-                    if (m == 12) load_a(s + 3);  // the A fragments are free now: request those of stage s+3
-                    // noise of stage s+1
-                    if (m < 4) {
-                        const int q = m, si = q / NSJ, sj = q % NSJ;
-                        const uint32_t x = ckey[sj] ^ (uint32_t)((ib1 + 16 * si + 4 * q16) >> 2);
-                        hw[q][0] = mix_a(x);
-                        hw[q][1] = mix_b(x);
-                    } else if (m < 12) {
-                        const int q = (m - 4) >> 1, h = (m - 4) & 1;
-                        box_muller(hw[q][h], amp[q % NSJ], zz[q][2 * h], zz[q][2 * h + 1]);
-                    } else if (m < 16) {
-                        const int q = m - 12, si = q / NSJ, sj = q % NSJ;
-                        const int64_t i = ib1 + 16 * si + 4 * q16;
-                        float x[4];
-#pragma unroll
-                        for (int e = 0; e < 4; e++) {
-                            x[e] = accx[q][e] + zz[q][e];
-                            if (BOXED && (i + e < p.i0 || i + e >= p.i1)) x[e] = 0.0f;
-                        }
-                        bf16x4 v = {(__bf16)x[0], (__bf16)x[1], (__bf16)x[2], (__bf16)x[3]};
-                        *(bf16x4 *)(obase + xg_w + sj * 16 * ROWB + si * 16 * (int)sizeof(T)) = v;
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-#pragma unroll
-                for (int q = 0; q < SUBI * NSJ; q++) accx[q] = accn[q];
-            }
-        };
         for (int s = 0; s < nstage; s++) {
-            if constexpr (WEAVE) {
-                woven(s);
-            } else {
-                fill(s);
-                multiply(s);
-            }
+            fill(s);
+            multiply(s);
             __syncthreads();
         }
 

@@ -32,7 +32,7 @@ def _say(msg):
 @pytest.fixture(autouse=True)
 def _announce(request):
     _say("[case] " + request.node.nodeid)
-    for v in ("EXAT_RT", "EXAT_V2"):
+    for v in ("EXAT_RT", "EXAT_PIPELINED"):
         os.environ.pop(v, None)
     yield
     torch.cuda.synchronize()
