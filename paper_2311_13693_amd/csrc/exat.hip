@@ -218,6 +218,8 @@ int run_chain(exat_plan_s *pl, Mode12Params mp, bool generated, float *Yout, int
         // (every global access validated in the kernel, violations counted in the plan's check counters), and
         // only on request.
         if (bf && generated && rt == 4 && env_int("EXAT_BF16_8W_CHECKED", 0) == 0) rt = 3;
+        // a small box (one streamed block) with 512-row groups would not give every compute unit a workgroup
+        if (!generated && rt == 4 && forced == 0 && (mp.k1 - mp.k0) * ((pl->PL + 511) / 512) < 256) rt = 2;
     }
     const int rows = 128 * rt;
     mp.U = pl->Upack; mp.V = pl->Vpack; mp.Q = pl->Q;

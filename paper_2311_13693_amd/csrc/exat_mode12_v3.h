@@ -122,7 +122,10 @@ __global__ __launch_bounds__(64 * NW, WPS) void k_mode12_v3(const Mode12Params p
 
     frag_t ufr[DU][RT][2];
     u32x4 xpre[SRC == SRC_MATERIALISED ? DX : 1][SRC == SRC_MATERIALISED ? XPT : 1];
-    bf16x8 afrag[2][SRC == SRC_GENERATED ? NV * KS * SUBI : 1];  // A pieces of the stages whose low-rank tiles are next: [stage parity]
+    // A pieces of the stages whose low-rank tiles are next.  With one wave per SIMD there is room for two sets
+    // (requested two stages ahead, [stage parity]); with two waves per SIMD one set, requested one stage ahead.
+    constexpr int NAB = NW == 4 ? 2 : 1;
+    bf16x8 afrag[NAB][SRC == SRC_GENERATED ? NV * KS * SUBI : 1];
     bf16x8 bfrag[SRC == SRC_GENERATED ? NV * KS * NSJ : 1];
     f32x4v accg[2][SRC == SRC_GENERATED ? NQ : 1];  // low-rank part of the X tiles of stages s+1, s+2: [stage parity][quad]
     uint32_t nw[SRC == SRC_GENERATED ? NWD : 1];
@@ -333,13 +336,13 @@ __global__ __launch_bounds__(64 * NW, WPS) void k_mode12_v3(const Mode12Params p
                     __builtin_amdgcn_sched_barrier(0);
                     static_for<g1 - g0>([&](auto gc) {
                         constexpr int g = g0 + decltype(gc)::value;
-                        gen_one(g, accg[PH], afrag[PH]);
+                        gen_one(g, accg[PH], afrag[PH % NAB]);
                         __builtin_amdgcn_sched_barrier(0);
                         constexpr int v0 = plan::uop_at(wb + 2 + g - g0), v1 = plan::uop_at(wb + 3 + g - g0);
                         static_for<v1 - v0>([&](auto uc) { uop(ic<v0 + decltype(uc)::value>(), ib1, oth, accg[PH ^ 1]); });
                         __builtin_amdgcn_sched_barrier(0);
                     });
-                    if constexpr (g1 == NGEN && g0 < NGEN) load_a(s + 4, afrag[PH]);  // these A pieces are free now: request those of stage s+4
+                    if constexpr (g1 == NGEN && g0 < NGEN) load_a(s + 2 + NAB, afrag[PH % NAB]);  // these A pieces are free now
                 }
             });
         };
@@ -358,19 +361,21 @@ __global__ __launch_bounds__(64 * NW, WPS) void k_mode12_v3(const Mode12Params p
 #pragma unroll
             for (int d = 0; d < DX; d++) load_x(d, xpre[d]);
         }
-        load_a(0, afrag[0]); load_a(1, afrag[1]);
+        load_a(0, afrag[0]);
+        if constexpr (NAB == 2) load_a(1, afrag[1]);
         if constexpr (SRC == SRC_GENERATED) {
 #pragma unroll
             for (int n = 0; n < NGEN; n++) gen_one(n, accg[0], afrag[0]);
         }
         __syncthreads();  // the previous chunk's epilogue is done with the LDS
         commit_plain(0, smem, accg[0]);
-        load_x(DX, xpre[0]); load_a(2, afrag[0]);
+        load_x(DX, xpre[0]);
+        load_a(NAB == 2 ? 2 : 1, afrag[0]);
         if constexpr (SRC == SRC_GENERATED) {
 #pragma unroll
-            for (int n = 0; n < NGEN; n++) gen_one(n, accg[1], afrag[1]);
+            for (int n = 0; n < NGEN; n++) gen_one(n, accg[1], afrag[NAB - 1]);
         }
-        load_a(3, afrag[1]);
+        load_a(NAB == 2 ? 3 : 2, afrag[NAB - 1]);
         __syncthreads();
 
         int s = 0;
