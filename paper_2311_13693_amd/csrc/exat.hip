@@ -260,7 +260,22 @@ int run_chain(exat_plan_s *pl, Mode12Params mp, bool generated, float *Yout, int
             else rc = rt == 4 ? launch_v3_mat<float, 8, 2>(mp, gs, uf, ck, nk, st) : launch_v3_mat<float, 4, 2>(mp, gs, uf, ck, nk, st);
         } else if (bf) {
             if (rt == 4) rc = launch_v3_gen_bf16_8w_checked(mp, gs, uf, ck, ks, boxed, nk, st);
-            else rc = rt == 3 ? launch_v3_gen_bf16<3>(mp, gs, uf, ck, ks, boxed, nk, st) : launch_v3_gen_bf16<2>(mp, gs, uf, ck, ks, boxed, nk, st);
+            else if (rt == 3) {
+                // 384-row groups; a remainder of at most 256 rows gets a launch of its own with a smaller tile
+                // instead of a mostly empty group (the generator's vector work per group does not shrink with
+                // the rows, the MFMA work does)
+                const int full = pl->PL / 384, rem = pl->PL - 384 * full;
+                rc = EXAT_OK;
+                if (full > 0 && (rem == 0 || rem <= 256)) {
+                    mp.G = full;
+                    rc = launch_v3_gen_bf16<3>(mp, gs, uf, ck, ks, boxed, nk, st);
+                    if (rc == EXAT_OK && rem > 0) {
+                        mp.row_base = 384 * full; mp.G = 1;
+                        rc = rem <= 128 ? launch_v3_gen_bf16<1>(mp, gs, uf, ck, ks, boxed, nk, st) : launch_v3_gen_bf16<2>(mp, gs, uf, ck, ks, boxed, nk, st);
+                    }
+                } else
+                    rc = launch_v3_gen_bf16<3>(mp, gs, uf, ck, ks, boxed, nk, st);
+            } else rc = launch_v3_gen_bf16<2>(mp, gs, uf, ck, ks, boxed, nk, st);
         } else
             rc = rt == 4 ? launch_v2_gen_f32<8, 2>(mp, gs, ck, ks, boxed, nk, st) : launch_v2_gen_f32<4, 2>(mp, gs, ck, ks, boxed, nk, st);
     } else if (pl->d.in_dtype == EXAT_BF16)

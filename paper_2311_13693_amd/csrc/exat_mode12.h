@@ -34,6 +34,7 @@ struct Mode12Params {
     float amp2_ln2;  // -2 ln2 sigma^2, 0 when sigma == 0
     int64_t I, Ipad, Jpad;
     int L, PL, PLpad, Mpad, MT, G;
+    int row_base;  // first stacked row of row group 0 of this launch (k_mode12_v3; a multiple of 32, else 0)
     int64_t i0, i1, j0, j1, k0, k1;
 };
 

@@ -112,7 +112,7 @@ __global__ __launch_bounds__(64 * NW, WPS) void k_mode12_v3(const Mode12Params p
     const int kidx = (SRC == SRC_GENERATED ? t % nkx : t / p.G) * 8 + xcd;
     if (kidx >= nk) return;
     const int64_t k = p.k0 + kidx;
-    const int row0 = g * ROWS;
+    const int row0 = p.row_base + g * ROWS;
     const int wrow0 = row0 + wave * (RT * 32);
     const int64_t ia0 = p.i0 & ~(int64_t)(EI - 1);
     const int nstage = (int)((p.i1 - ia0 + EI - 1) / EI);

@@ -320,6 +320,24 @@ def test_stage_count_sweep(dtype, P):
     assert worst_g <= (TOL_BF16 if dtype == "bf16" else TOL_F32)
 
 
+# bf16 generator: 384-row groups plus a remainder launch with a 128- or 256-row tile (P*L = 450, 600),
+# and the case where the remainder is a group of its own (P*L = 700 = 384 + 316).
+@pytest.mark.parametrize("P", [9, 12, 14])
+def test_bf16_generator_remainder_rows(P):
+    cfg = wl.small(name="remainder", index=420 + P, dtype="bf16", I=96, J=140, K=4, R=20, P=P, L=50, M=50, N=6, dI=48, dJ=70, dK=2)
+    A, B, C, U, V, W = _inputs(cfg)
+    plan = gu.plan_with_factors(cfg, U, V, W)
+    gen = gu.gen_of(cfg, A, B, C)
+    Yo = oracle.comp_multi(oracle.gen_box(A, B, C, cfg.seed, cfg.sigma), U, V, W, cfg.P)
+    e = oracle.rel_fro(gu.y_to_numpy(plan.compress_gen(gen), cfg), Yo)
+    box = (48, 96, 0, 70, 1, 3)
+    Yb = oracle.comp_box(oracle.gen_box(A, B, C, cfg.seed, cfg.sigma, box), U, V, W, cfg.P, box)
+    eb = oracle.rel_fro(gu.y_to_numpy(plan.compress_gen(gen, box), cfg), Yb)
+    _say("  P*L=%d: full %.3e, box %.3e" % (P * 50, e, eb))
+    assert max(e, eb) <= TOL_BF16
+    plan.close()
+
+
 def test_bf16_8wave_generator_runs_bounds_checked_and_clean():
     # this variant only runs with every global access validated in the kernel; the counters must stay zero
     os.environ["EXAT_BF16_8W_CHECKED"] = "1"
