@@ -52,7 +52,14 @@ typedef enum {
  * accumulated in fp32 and Y is always fp32.  With EXAT_BF16 the elements of X, U, V, W
  * are rounded to bf16 (round-to-nearest-even) before use; the intermediates of the
  * mode-1 and mode-2 contractions stay fp32. */
-typedef enum { EXAT_F32 = 0, EXAT_BF16 = 1 } exat_dtype_t;
+typedef enum { EXAT_F32 = 0, EXAT_BF16 = 1, EXAT_F32_SPLIT = 2 } exat_dtype_t;
+/* EXAT_F32_SPLIT (the residual split of Eq. 5): X, U, V, W are fp32 in memory exactly as with EXAT_F32,
+ * but exat_compress / exat_compress_block run the mode-1 and mode-2 contractions on the fp16 matrix
+ * cores: every operand element is used as the sum of two fp16 pieces, x = fl16(x) + fl16(x - fl16(x)),
+ * and every product as its three significant cross terms accumulated in fp32 (the dropped term is
+ * 2^-22 of the product).  Results agree with EXAT_F32 to fp32 rounding level provided |X|, |U|, |V| and
+ * the mode-1 intermediate stay below the fp16 maximum (65504); nothing checks that.  Sources the
+ * split kernel does not cover (exat_compress_gen, unaligned blocks) run the EXAT_F32 kernels. */
 
 /* Problem statement: the inputs of Alg. 2 plus the block edge of Sec. 4.3. */
 typedef struct {

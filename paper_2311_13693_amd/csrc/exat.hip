@@ -14,6 +14,7 @@
 #include "exat_mode12.h"
 #include "exat_mode12_v2.h"
 #include "exat_mode12_v3.h"
+#include "exat_mode12_split.h"
 
 using namespace exat;
 
@@ -31,6 +32,7 @@ struct exat_plan_s {
     void *Upack = nullptr;
     void *Ufrag = nullptr;  // U in MFMA fragment order (k_pack_u_frag), same size as Upack
     void *Vfrag = nullptr;  // bf16 plans: V in bf16 MFMA fragment order (k_pack_v_frag)
+    _Float16 *Ufh = nullptr, *Ufl = nullptr, *Vfh = nullptr, *Vfl = nullptr;  // split plans: fp16 pieces in fragment order
     float *Vpack = nullptr, *Wpack = nullptr, *Q = nullptr;
     bool factors_set = false;
     // block-streamed state
@@ -76,7 +78,7 @@ int choose_rt(const exat_plan_s *pl, bool generated)
 int validate_desc(const exat_desc_t *d)
 {
     if (!d) return EXAT_ERR_NULL;
-    if (d->in_dtype != EXAT_F32 && d->in_dtype != EXAT_BF16) return EXAT_ERR_DTYPE;
+    if (d->in_dtype != EXAT_F32 && d->in_dtype != EXAT_BF16 && d->in_dtype != EXAT_F32_SPLIT) return EXAT_ERR_DTYPE;
     if (d->I < 1 || d->J < 1 || d->K < 1 || d->I > kMaxExtent || d->J > kMaxExtent || d->K > kMaxExtent) return EXAT_ERR_SHAPE;
     if (d->L < 1 || d->M < 1 || d->N < 1 || d->P < 1 || d->M > 64) return EXAT_ERR_SHAPE;
     if ((int64_t)d->P * d->L >= (1 << 24) || (int64_t)d->P * d->N >= (1 << 24)) return EXAT_ERR_SHAPE;
@@ -195,6 +197,23 @@ int launch_v3_gen_bf16_8w_checked(const Mode12Params &mp, const GenSplitParams &
     return boxed ? launch_v3_inst<__bf16, 8, 2, SRC_GENERATED, 2, true, 2, 1, 2, true>(mp, gs, uf, ck, nk, st) : launch_v3_inst<__bf16, 8, 2, SRC_GENERATED, 2, false, 2, 1, 2, true>(mp, gs, uf, ck, nk, st);
 }
 
+// fp32 data on the fp16 matrix cores (two-piece split), materialised source, 4 waves x RT row tiles
+template <int RT>
+int launch_split(const Mode12Params &mp, const SplitParams &sp, int nk, hipStream_t st)
+{
+    typedef Mode12SplitCfg<4, RT> cfg;
+    auto kern = k_mode12_split<4, RT, 2, 2>;
+    static bool attr_done = false;
+    if (!attr_done) {
+        if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, cfg::LDS_BYTES) != hipSuccess) return EXAT_ERR_HIP;
+        attr_done = true;
+    }
+    const int64_t grid = 8LL * ((nk + 7) / 8) * mp.G;
+    if (grid > 2147483647LL) return EXAT_ERR_SHAPE;
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), cfg::LDS_BYTES, st, mp, sp);
+    return hipGetLastError() == hipSuccess ? EXAT_OK : EXAT_ERR_HIP;
+}
+
 // fills the plan-dependent part of the parameters and launches mode 1+2 followed by mode 3
 int run_chain(exat_plan_s *pl, Mode12Params mp, bool generated, float *Yout, int accumulate, hipStream_t st)
 {
@@ -221,6 +240,8 @@ int run_chain(exat_plan_s *pl, Mode12Params mp, bool generated, float *Yout, int
         // a small box (one streamed block) with 512-row groups would not give every compute unit a workgroup
         if (!generated && rt == 4 && forced == 0 && (mp.k1 - mp.k0) * ((pl->PL + 511) / 512) < 256) rt = 2;
     }
+    // fp32 data on the fp16 matrix cores: materialised sources with whole 32-value stages of i inside the box
+    const bool split = pl->d.in_dtype == EXAT_F32_SPLIT && !generated && mp.x_vec && (mp.i0 % 32 == 0) && ((mp.i1 - mp.i0) % 32 == 0);
     const int rows = 128 * rt;
     mp.U = pl->Upack; mp.V = pl->Vpack; mp.Q = pl->Q;
     mp.I = pl->d.I; mp.Ipad = pl->Ipad; mp.Jpad = pl->Jpad;
@@ -236,7 +257,19 @@ int run_chain(exat_plan_s *pl, Mode12Params mp, bool generated, float *Yout, int
         if (hipGetLastError() != hipSuccess) return EXAT_ERR_HIP;
     }
     if (pl->timing && hipEventRecord(pl->ev[0], st) != hipSuccess) return EXAT_ERR_HIP;
-    if (pipelined) {
+    if (split) {
+        SplitParams sp;
+        sp.Ufh = pl->Ufh; sp.Ufl = pl->Ufl; sp.nig = pl->Ipad / 16; sp.Vfh = pl->Vfh; sp.Vfl = pl->Vfl;
+        // 256-row groups (one wave per SIMD, 2 row tiles; measured a little faster than 384-row groups); a
+        // remainder of at most 128 rows gets a launch of its own with one row tile per wave
+        const int full = pl->PL / 256, rem = pl->PL - 256 * full;
+        rc = EXAT_OK;
+        if (full > 0 || rem > 128) { mp.G = rem > 128 ? full + 1 : full; rc = launch_split<2>(mp, sp, nk, st); }
+        if (rc == EXAT_OK && rem > 0 && rem <= 128) {
+            mp.row_base = 256 * full; mp.G = 1;
+            rc = launch_split<1>(mp, sp, nk, st);
+        }
+    } else if (pipelined) {
         const bool boxed = generated && (mp.i0 != 0 || mp.i1 != pl->d.I);
         const int ks = gs.Rpad / 32;
         // Fragment-ordered U (k_mode12_v3): every materialised source and the bf16 generator.  The fp32
@@ -328,7 +361,7 @@ int exat_plan_create(exat_plan_t *plan, const exat_desc_t *desc)
     pl->Jpad = ceil_to(desc->J, 256);
     // every kernel variant the plan may pick must find its row groups inside the padding
     int64_t plpad = 0;
-    const int rts_f32[] = {1, 2, 4}, rts_bf16[] = {2, 3, 4, 5};
+    const int rts_f32[] = {1, 2, 3, 4}, rts_bf16[] = {2, 3, 4, 5};
     if (desc->in_dtype == EXAT_BF16) { for (int rt : rts_bf16) { int64_t v = ceil_to(pl->PL, 128 * rt); if (v > plpad) plpad = v; } }
     else { for (int rt : rts_f32) { int64_t v = ceil_to(pl->PL, 128 * rt); if (v > plpad) plpad = v; } }
     pl->PLpad = (int)plpad;
@@ -341,7 +374,10 @@ int exat_plan_create(exat_plan_t *plan, const exat_desc_t *desc)
     if (hipMalloc((void **)&pl->dbg, 8 * sizeof(unsigned)) != hipSuccess || hipMemset(pl->dbg, 0, 8 * sizeof(unsigned)) != hipSuccess ||
         hipMalloc((void **)&pl->Asplit, pl->ab) != hipSuccess ||
         hipMalloc(&pl->Upack, ub) != hipSuccess || hipMalloc(&pl->Ufrag, ub) != hipSuccess ||
-        (desc->in_dtype == EXAT_BF16 && hipMalloc(&pl->Vfrag, (size_t)desc->P * pl->Jpad * 64 * 2) != hipSuccess) || hipMalloc((void **)&pl->Vpack, vb) != hipSuccess ||
+        (desc->in_dtype == EXAT_BF16 && hipMalloc(&pl->Vfrag, (size_t)desc->P * pl->Jpad * 64 * 2) != hipSuccess) ||
+        (desc->in_dtype == EXAT_F32_SPLIT &&
+         (hipMalloc((void **)&pl->Ufh, (size_t)pl->PLpad * pl->Ipad * 2) != hipSuccess || hipMalloc((void **)&pl->Ufl, (size_t)pl->PLpad * pl->Ipad * 2) != hipSuccess ||
+          hipMalloc((void **)&pl->Vfh, (size_t)desc->P * pl->Jpad * 64 * 2) != hipSuccess || hipMalloc((void **)&pl->Vfl, (size_t)desc->P * pl->Jpad * 64 * 2) != hipSuccess)) || hipMalloc((void **)&pl->Vpack, vb) != hipSuccess ||
         hipMalloc((void **)&pl->Wpack, wb) != hipSuccess || hipMalloc((void **)&pl->Q, qb) != hipSuccess) {
         (void)hipGetLastError();
         exat_plan_destroy(pl);
@@ -356,7 +392,8 @@ int exat_plan_create(exat_plan_t *plan, const exat_desc_t *desc)
 int exat_plan_destroy(exat_plan_t pl)
 {
     if (!pl) return EXAT_OK;
-    (void)hipFree(pl->Upack); (void)hipFree(pl->Ufrag); (void)hipFree(pl->Vfrag); (void)hipFree(pl->Vpack); (void)hipFree(pl->Wpack); (void)hipFree(pl->Q);
+    (void)hipFree(pl->Upack); (void)hipFree(pl->Ufrag); (void)hipFree(pl->Vfrag);
+    (void)hipFree(pl->Ufh); (void)hipFree(pl->Ufl); (void)hipFree(pl->Vfh); (void)hipFree(pl->Vfl); (void)hipFree(pl->Vpack); (void)hipFree(pl->Wpack); (void)hipFree(pl->Q);
     (void)hipFree(pl->slots); (void)hipFree(pl->used_dev); (void)hipFree(pl->Asplit); (void)hipFree(pl->dbg);
     for (hipEvent_t e : pl->ev) if (e) (void)hipEventDestroy(e);
     delete pl;
@@ -378,6 +415,10 @@ int exat_set_factors(exat_plan_t pl, const float *U, int64_t ldU, const float *V
         hipLaunchKernelGGL(k_pack_v<__bf16>, dim3(grid_for(nv)), dim3(256), 0, st, V, ldV, d.P, d.M, d.J, pl->Vpack, pl->Mpad, pl->Jpad);
         hipLaunchKernelGGL(k_pack_w<__bf16>, dim3(grid_for(nw)), dim3(256), 0, st, W, ldW, d.P, d.N, d.K, pl->Wpack, pl->Npad);
     } else {
+        if (d.in_dtype == EXAT_F32_SPLIT) {
+            hipLaunchKernelGGL(k_pack_u_split, dim3(grid_for(nu)), dim3(256), 0, st, U, ldU, pl->PL, d.I, pl->Ufh, pl->Ufl, pl->PLpad / 32, pl->Ipad / 16);
+            hipLaunchKernelGGL(k_pack_v_split, dim3(grid_for((int64_t)d.P * pl->Jpad * 64)), dim3(256), 0, st, V, ldV, d.P, d.M, d.J, pl->Vfh, pl->Vfl, pl->Jpad);
+        }
         hipLaunchKernelGGL(k_pack_u<float>, dim3(grid_for(nu)), dim3(256), 0, st, U, ldU, pl->PL, d.I, (float *)pl->Upack, pl->PLpad, pl->Ipad);
         hipLaunchKernelGGL(k_pack_u_frag<float>, dim3(grid_for(nu)), dim3(256), 0, st, U, ldU, pl->PL, d.I, (float *)pl->Ufrag, pl->PLpad / 32, pl->Ipad / 8);
         hipLaunchKernelGGL(k_pack_v<float>, dim3(grid_for(nv)), dim3(256), 0, st, V, ldV, d.P, d.M, d.J, pl->Vpack, pl->Mpad, pl->Jpad);

@@ -296,8 +296,8 @@ __global__ __launch_bounds__(64 * NW) void k_mode12_v2(const Mode12Params p, con
         const bool first_chunk = (jc == ja0);
         // the generator's registers leave less room for V fragments in flight
         constexpr int VB = SRC == SRC_GENERATED ? V2_VB : 16;
-        if (p.MT == 2) mode2_chunk<RT, CT, CHECKED, 2, false, VB>(p, nullptr, ck, Zs, acc, wrow0, kidx, jc, first_chunk, lane);
-        else mode2_chunk<RT, CT, CHECKED, 1, false, VB>(p, nullptr, ck, Zs, acc, wrow0, kidx, jc, first_chunk, lane);
+        if (p.MT == 2) mode2_chunk<RT, CT, CHECKED, 2, VM_F32, VB>(p, nullptr, ck, Zs, acc, wrow0, kidx, jc, first_chunk, lane);
+        else mode2_chunk<RT, CT, CHECKED, 1, VM_F32, VB>(p, nullptr, ck, Zs, acc, wrow0, kidx, jc, first_chunk, lane);
     }
 }
 

@@ -394,8 +394,8 @@ __global__ __launch_bounds__(64 * NW, WPS) void k_mode12_v3(const Mode12Params p
         // ---- mode 2 on the finished Z chunk ----
         float *Zs = (float *)smem + wave * (32 * ZST);
         const bool first_chunk = (jc == ja0);
-        if (p.MT == 2) mode2_chunk<RT, CT, CHECKED, 2, sizeof(T) == 2>(p, uf.Vf, ck, Zs, acc, wrow0, kidx, jc, first_chunk, tid & 63);
-        else mode2_chunk<RT, CT, CHECKED, 1, sizeof(T) == 2>(p, uf.Vf, ck, Zs, acc, wrow0, kidx, jc, first_chunk, tid & 63);
+        if (p.MT == 2) mode2_chunk<RT, CT, CHECKED, 2, sizeof(T) == 2 ? VM_BF16 : VM_F32>(p, uf.Vf, ck, Zs, acc, wrow0, kidx, jc, first_chunk, tid & 63);
+        else mode2_chunk<RT, CT, CHECKED, 1, sizeof(T) == 2 ? VM_BF16 : VM_F32>(p, uf.Vf, ck, Zs, acc, wrow0, kidx, jc, first_chunk, tid & 63);
     }
 }
 

@@ -50,13 +50,20 @@ __device__ __forceinline__ void st_chk(V *ptr, V v, const CheckParams &ck, int i
 
 template <int V> struct ic { static constexpr int value = V; };
 
-// MTC: 32-column tiles of M (1 or 2).  BF16V: run on the bf16 matrix cores with Z split into two bf16 pieces
-// (error 2^-17) and V_p read from Vf in fragment order, [P][Jpad/16][2][64 lanes][8 bf16], lane l of fragment
-// (p, j16, mt) holding V_p[m = 32*mt + l%32, j = 16*j16 + 8*(l/32) .. +7]; otherwise fp32 MFMA and p.V.
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+
+// MTC: 32-column tiles of M (1 or 2).  VM selects the arithmetic:
+//   VM_F32   fp32 MFMA, V_p from p.V;
+//   VM_BF16  bf16 matrix cores, Z split into two bf16 pieces (error 2^-17), V_p (bf16) from Vf in fragment
+//            order, [P][Jpad/16][2][64 lanes][8], lane l of fragment (p, j16, mt) holding
+//            V_p[m = 32*mt + l%32, j = 16*j16 + 8*(l/32) .. +7];
+//   VM_F16X2 fp16 matrix cores, Z and V_p each split into two fp16 pieces (Vf: high pieces, Vf2: low pieces,
+//            same fragment order), the three significant cross terms accumulated in fp32 (error 2^-22).
 // VB: V fragments (of 8 columns) requested together on the fp32 path; 16 = a whole chunk, fewer where registers are short.
-template <int RT, int CT, bool CHECKED, int MTC, bool BF16V, int VB = 16>
+enum { VM_F32 = 0, VM_BF16 = 1, VM_F16X2 = 2 };
+template <int RT, int CT, bool CHECKED, int MTC, int VM, int VB = 16>
 __device__ __forceinline__ void mode2_chunk(const Mode12Params &p, const void *Vf, const CheckParams &ck, float *Zs, const f32x16 (&acc)[RT][CT],
-                                            int wrow0, int kidx, int64_t jc, bool first_chunk, int lane)
+                                            int wrow0, int kidx, int64_t jc, bool first_chunk, int lane, const void *Vf2 = nullptr)
 {
     constexpr int COLS = 32 * CT, ZST = COLS + 4;
     constexpr int MP = 32 * MTC;  // = p.Mpad; a constant here so that the 32 Q accesses of a tile differ by immediates
@@ -99,7 +106,40 @@ __device__ __forceinline__ void mode2_chunk(const Mode12Params &p, const void *V
                 for (int mt = 0; mt < MTC; mt++)
 #pragma unroll
                     for (int e = 0; e < 16; e++) qa[mt][e] = 0.0f;
-                if constexpr (BF16V) {
+                if constexpr (VM == VM_F16X2) {
+                    const int64_t fo = (((int64_t)pp * (p.Jpad / 16) + jc / 16) * 2) * 64 + lane;
+                    const f16x8 *vh = (const f16x8 *)Vf + fo, *vl = (const f16x8 *)Vf2 + fo;
+                    constexpr int GB = 4;  // 16-column groups per batch of V fragments
+#pragma unroll
+                    for (int g0 = 0; g0 < COLS / 16; g0 += GB) {
+                        f16x8 bh[GB][MTC], bl[GB][MTC];
+#pragma unroll
+                        for (int g = 0; g < GB; g++)
+#pragma unroll
+                            for (int mt = 0; mt < MTC; mt++) {
+                                bh[g][mt] = vh[((g0 + g) * 2 + mt) * 64];
+                                bl[g][mt] = vl[((g0 + g) * 2 + mt) * 64];
+                            }
+                        __builtin_amdgcn_sched_barrier(0);  // keeps the requests together, ahead of the first MFMA
+#pragma unroll
+                        for (int g = 0; g < GB; g++) {
+                            const f32x4 z0 = *(const f32x4 *)(Zs + l32 * ZST + 16 * (g0 + g) + 8 * hi);
+                            const f32x4 z1 = *(const f32x4 *)(Zs + l32 * ZST + 16 * (g0 + g) + 8 * hi + 4);
+                            f16x8 zh, zl;
+#pragma unroll
+                            for (int e = 0; e < 4; e++) {
+                                zh[e] = (_Float16)z0[e]; zl[e] = (_Float16)(z0[e] - (float)zh[e]);
+                                zh[4 + e] = (_Float16)z1[e]; zl[4 + e] = (_Float16)(z1[e] - (float)zh[4 + e]);
+                            }
+#pragma unroll
+                            for (int mt = 0; mt < MTC; mt++) {
+                                qa[mt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(zl, bh[g][mt], qa[mt], 0, 0, 0);
+                                qa[mt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(zh, bl[g][mt], qa[mt], 0, 0, 0);
+                                qa[mt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(zh, bh[g][mt], qa[mt], 0, 0, 0);
+                            }
+                        }
+                    }
+                } else if constexpr (VM == VM_BF16) {
                     // bf16 matrix cores: Z = zh + zl (bf16 pieces), V_p in fragment order
                     const bf16x8 *vf = (const bf16x8 *)Vf + (((int64_t)pp * (p.Jpad / 16) + jc / 16) * 2) * 64 + lane;
                     bf16x8 bv[COLS / 16][MTC];

@@ -10,7 +10,7 @@ import os
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libexat.so")
 
-EXAT_F32, EXAT_BF16 = 0, 1
+EXAT_F32, EXAT_BF16, EXAT_F32_SPLIT = 0, 1, 2
 OK, ERR_NULL, ERR_SHAPE, ERR_DTYPE, ERR_STATE, ERR_ALLOC, ERR_HIP = 0, -1, -2, -3, -4, -5, -6
 
 EXPORTS = ["exat_plan_create", "exat_plan_destroy", "exat_set_factors", "exat_compress",

@@ -31,7 +31,8 @@ class Config:
     dI: int
     dJ: int
     dK: int
-    dtype: str           # "f32" or "bf16": type of the X tile and of U,V,W as the kernels consume them
+    dtype: str           # "f32" or "bf16": type of the X tile and of U,V,W as the kernels consume them;
+                         # "f32s": fp32 data, contractions on the fp16 matrix cores with two-piece operands
     materialised: bool   # X resident in HBM (True) or generated tile by tile inside the kernel (False)
     sigma: float = 0.01
     index: int = 0

@@ -26,7 +26,7 @@ def y_to_numpy(Y, cfg):
 
 def desc_of(cfg):
     return exat.make_desc(cfg.I, cfg.J, cfg.K, cfg.L, cfg.M, cfg.N, cfg.P, cfg.dI, cfg.dJ, cfg.dK,
-                          exat.EXAT_BF16 if cfg.dtype == "bf16" else exat.EXAT_F32)
+                          {"bf16": exat.EXAT_BF16, "f32s": exat.EXAT_F32_SPLIT}.get(cfg.dtype, exat.EXAT_F32))
 
 
 def plan_with_factors(cfg, U, V, W):

@@ -78,6 +78,20 @@ def test_cfg2_full_parity_materialised_generated_and_block_streamed():
     _say("  cfg2 rel_fro: materialised %.3e, generated on chip %.3e, block-streamed %.3e" % (e1, e2, e3))
     assert max(e1, e2, e3) <= TOL["f32"]
     plan.close()
+    # the same tensor through the fp16 matrix cores with two-piece operands: same tolerance
+    from dataclasses import replace
+    cfgs = replace(cfg, dtype="f32s")
+    plan = gu.plan_with_factors(cfgs, U, V, W)
+    e4 = oracle.rel_fro(gu.y_to_numpy(plan.compress(Xd), cfg), Yo)
+    for bk in range(cfg.K // d):
+        for bj in range(cfg.J // d):
+            for bi in range(cfg.I // d):
+                blk = Xv[bk * d:(bk + 1) * d, bj * d:(bj + 1) * d, bi * d:(bi + 1) * d].contiguous()
+                plan.compress_block(blk, bi, bj, bk)
+    e5 = oracle.rel_fro(gu.y_to_numpy(plan.finalize(), cfg), Yo)
+    _say("  cfg2 rel_fro, fp16 two-piece split: one shot %.3e, block-streamed %.3e" % (e4, e5))
+    assert max(e4, e5) <= TOL["f32"]
+    plan.close()
 
 
 def test_cfg3_replica_sampled_parity_and_noise_energy():

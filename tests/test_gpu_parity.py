@@ -338,6 +338,52 @@ def test_bf16_generator_remainder_rows(P):
     plan.close()
 
 
+# fp32 data on the fp16 matrix cores (two-piece operands, Eq. 5's residual split): same tolerance as the fp32 path.
+# Stage counts around the unrolled loop, row counts that take the 1-, 2- and 3-tile variants and a remainder
+# launch, M above and below 32, a ragged last column chunk, block streaming, and a box the split kernel does not
+# cover (falls back to the fp32 kernels).
+@pytest.mark.parametrize("P", [2, 5, 9, 14])
+def test_split_fp16_matches_oracle(P):
+    worst = 0.0
+    for nstage, M in ((1, 34), (2, 20), (3, 50), (5, 34), (8, 64)):
+        cfg = wl.small(name="split", index=440 + nstage, dtype="f32s", I=32 * nstage, J=140, K=3, R=5, P=P, L=50, M=M, N=5,
+                       dI=32 * nstage, dJ=70, dK=3)
+        A, B, C, U, V, W = _inputs(cfg)
+        plan = gu.plan_with_factors(cfg, U, V, W)
+        X = oracle.gen_box(A, B, C, cfg.seed, cfg.sigma)
+        Yo = oracle.comp_multi(X, U, V, W, cfg.P)
+        e = oracle.rel_fro(gu.y_to_numpy(plan.compress(gu.to_dev_x(X)), cfg), Yo)
+        _say("  P*L=%d stages=%d M=%d: %.3e" % (P * 50, nstage, M, e))
+        worst = max(worst, e)
+        plan.close()
+    assert worst <= TOL_F32
+
+
+def test_split_fp16_block_streamed_and_fallbacks():
+    cfg = wl.small(name="splitblk", index=450, dtype="f32s", I=96, J=60, K=8, R=6, P=7, L=40, M=33, N=9, dI=32, dJ=30, dK=4)
+    A, B, C, U, V, W = _inputs(cfg)
+    plan = gu.plan_with_factors(cfg, U, V, W)
+    X = oracle.gen_box(A, B, C, cfg.seed, cfg.sigma)
+    Yo = oracle.comp_multi(X, U, V, W, cfg.P)
+    for bk in range(2):
+        for bj in range(2):
+            for bi in range(3):
+                Xb = np.asfortranarray(X[bi * 32:(bi + 1) * 32, bj * 30:(bj + 1) * 30, bk * 4:(bk + 1) * 4])
+                plan.compress_block(gu.to_dev_x(Xb), bi, bj, bk)
+    e_blk = oracle.rel_fro(gu.y_to_numpy(plan.finalize(), cfg), Yo)
+    e_gen = oracle.rel_fro(gu.y_to_numpy(plan.compress_gen(gu.gen_of(cfg, A, B, C)), cfg), Yo)   # fp32 generator kernels
+    plan.close()
+    # extent 37 is not a multiple of the stage: fp32 kernels
+    cfg2 = wl.small(name="splitodd", index=451, dtype="f32s", I=37, J=29, K=5, R=4, P=3, L=7, M=5, N=4, dI=37, dJ=29, dK=5)
+    A, B, C, U, V, W = _inputs(cfg2)
+    plan = gu.plan_with_factors(cfg2, U, V, W)
+    X = oracle.gen_box(A, B, C, cfg2.seed, cfg2.sigma)
+    e_odd = oracle.rel_fro(gu.y_to_numpy(plan.compress(gu.to_dev_x(X)), cfg2), oracle.comp_multi(X, U, V, W, cfg2.P))
+    plan.close()
+    _say("  block-streamed %.3e, generated %.3e, odd extents %.3e" % (e_blk, e_gen, e_odd))
+    assert max(e_blk, e_gen, e_odd) <= TOL_F32
+
+
 def test_bf16_8wave_generator_runs_bounds_checked_and_clean():
     # this variant only runs with every global access validated in the kernel; the counters must stay zero
     os.environ["EXAT_BF16_8W_CHECKED"] = "1"
