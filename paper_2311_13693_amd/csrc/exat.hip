@@ -202,7 +202,7 @@ template <int RT>
 int launch_split(const Mode12Params &mp, const SplitParams &sp, int nk, hipStream_t st)
 {
     typedef Mode12SplitCfg<4, RT> cfg;
-    auto kern = k_mode12_split<4, RT, 2, 2>;
+    auto kern = k_mode12_split<4, RT, 2, 4>;
     static bool attr_done = false;
     if (!attr_done) {
         if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, cfg::LDS_BYTES) != hipSuccess) return EXAT_ERR_HIP;

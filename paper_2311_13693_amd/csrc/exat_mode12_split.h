@@ -3,7 +3,8 @@
 // X and the stacked U stay fp32 in memory.  Every operand element is taken as the sum of two fp16 pieces,
 // x = x_h + x_l with x_h = fl16(x), x_l = fl16(x - x_h) (22 significand bits together), and a product u*x as the
 // three cross terms u_h x_h + u_h x_l + u_l x_h accumulated in fp32; the dropped term u_l x_l is 2^-22 of the
-// product.  One 32x32x16 block then costs three fp16 MFMAs (96 clk) instead of eight fp32 MFMAs (512 clk).
+// product.  (The X tile is split on the fly with the packed round-toward-zero conversion, x_h = rtz16(x),
+// x_l = rtz16(x - x_h): x - x_h is exact, and the pair still carries 21 bits.)  One 32x32x16 block then costs three fp16 MFMAs (96 clk) instead of eight fp32 MFMAs (512 clk).
 // Magnitudes must stay inside the fp16 range (|x|, |u|, |Z| < 65504); pieces below 2^-24 are lost.
 //
 // Same decomposition, tile shape and fragment-ordered U as k_mode12_v3 (materialised source only): U is split
@@ -40,7 +41,7 @@ __global__ __launch_bounds__(64 * NW) void k_mode12_split(const Mode12Params p, 
     typedef Mode12SplitCfg<NW, RT> cfg;
     constexpr int CT = 4, ROWS = cfg::ROWS, COLS = cfg::COLS, ROWB = cfg::ROWB, ZST = cfg::ZST, XBUF = cfg::XBUF_BYTES, STAGE = cfg::STAGE_BYTES;
     constexpr int EI = 32, GI = 16;            // i per stage, i per U fragment
-    constexpr int NT = 64 * NW, PCOLS = NT / 8, XPT = COLS / PCOLS;  // 8 threads x 4 floats cover the 32 i of one column
+    constexpr int NT = 64 * NW, PCOLS = NT / 4, XPT = COLS / PCOLS;  // 4 threads x 8 floats cover the 32 i of one column
     constexpr int NMAIN = 2 * RT * CT;
     constexpr int UNR = lcm_i(lcm_i(2, DU), DX);
     extern __shared__ __align__(16) unsigned char smem[];
@@ -60,7 +61,7 @@ __global__ __launch_bounds__(64 * NW) void k_mode12_split(const Mode12Params p, 
     const int64_t u_rt_step = sp.nig * (64 * 8);
 
     f16x8 uh[DU][RT][2], ul[DU][RT][2];
-    f32x4 xpre[DX][XPT];
+    f32x4 xpre[DX][2 * XPT];
     const CheckParams ck = {};
 
     for (int64_t jc = ja0; jc < p.j1; jc += COLS) {
@@ -70,8 +71,8 @@ __global__ __launch_bounds__(64 * NW) void k_mode12_split(const Mode12Params p, 
         const int lane = tidc & 63, l32 = lane & 31, hi = lane >> 5;
         const int64_t ufo = ((int64_t)(wrow0 >> 5) * sp.nig) * (64 * 8) + lane * 8;
         const _Float16 *ufh = sp.Ufh + ufo, *ufl = sp.Ufl + ufo;
-        const int pr0 = tidc >> 3, pf = tidc & 7;
-        const int xs_w = pr0 * ROWB + pf * 8;       // + u*PCOLS*ROWB; low tile at + XBUF
+        const int pr0 = tidc >> 2, pf = tidc & 3;
+        const int xs_w = pr0 * ROWB + pf * 16;      // + u*PCOLS*ROWB; low tile at + XBUF
         const int xs_r = l32 * ROWB + hi * 16;      // + ct*32*ROWB + g2*32; low tile at + XBUF
         f32x16 acc[RT][CT];
 #pragma unroll
@@ -86,7 +87,7 @@ __global__ __launch_bounds__(64 * NW) void k_mode12_split(const Mode12Params p, 
         for (int u = 0; u < XPT; u++) {
             const int64_t j = jc + pr0 + PCOLS * u;
             x_ok[u] = (j >= p.j0) && (j < p.j1);
-            x_off[u] = (pf * 4 - p.xo_i) + (j - p.xo_j) * p.x_sj + (k - p.xo_k) * p.x_sk;
+            x_off[u] = (pf * 8 - p.xo_i) + (j - p.xo_j) * p.x_sj + (k - p.xo_k) * p.x_sk;
         }
 
         auto stage_i = [&](int s) -> int64_t { return ia0 + (int64_t)(s < nstage ? s : nstage - 1) * EI; };
@@ -99,23 +100,32 @@ __global__ __launch_bounds__(64 * NW) void k_mode12_split(const Mode12Params p, 
             const float *xb = (const float *)p.X + stage_i(s);
 #pragma unroll
             for (int u = 0; u < XPT; u++) {
-                f32x4 v = {0.0f, 0.0f, 0.0f, 0.0f};
-                if (x_ok[u]) v = *(const f32x4 *)(xb + x_off[u]);
-                slot[u] = v;
+                f32x4 v0 = {0.0f, 0.0f, 0.0f, 0.0f}, v1 = v0;
+                if (x_ok[u]) {
+                    v0 = *(const f32x4 *)(xb + x_off[u]);
+                    v1 = *(const f32x4 *)(xb + x_off[u] + 4);
+                }
+                slot[2 * u] = v0;
+                slot[2 * u + 1] = v1;
             }
         };
         // splits the tile pieces held in `slot` and writes the two fp16 tiles of a stage into LDS at `base`
         auto commit = [&](const f32x4 *slot, unsigned char *base) {
+            typedef __fp16 h2 __attribute__((ext_vector_type(2)));
+            typedef unsigned int u32x4w __attribute__((ext_vector_type(4)));
 #pragma unroll
             for (int u = 0; u < XPT; u++) {
-                f16x4 h, l;
+                u32x4w hw, lw;
 #pragma unroll
-                for (int e = 0; e < 4; e++) {
-                    h[e] = (_Float16)slot[u][e];
-                    l[e] = (_Float16)(slot[u][e] - (float)h[e]);
+                for (int e = 0; e < 4; e++) {  // pairs (2e, 2e+1) of the 8 values of this lane
+                    const float a = slot[2 * u + (e >> 1)][2 * (e & 1)], b = slot[2 * u + (e >> 1)][2 * (e & 1) + 1];
+                    const h2 h = __builtin_amdgcn_cvt_pkrtz(a, b);
+                    const h2 l = __builtin_amdgcn_cvt_pkrtz(a - (float)h[0], b - (float)h[1]);
+                    hw[e] = __builtin_bit_cast(unsigned int, h);
+                    lw[e] = __builtin_bit_cast(unsigned int, l);
                 }
-                *(f16x4 *)(base + xs_w + u * PCOLS * ROWB) = h;
-                *(f16x4 *)(base + XBUF + xs_w + u * PCOLS * ROWB) = l;
+                *(u32x4w *)(base + xs_w + u * PCOLS * ROWB) = hw;
+                *(u32x4w *)(base + XBUF + xs_w + u * PCOLS * ROWB) = lw;
             }
         };
         // one stage: MFMAs of stage s (tiles in LDS buffer s&1, U fragments in register set s%DU) while the tile of
