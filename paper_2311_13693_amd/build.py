@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libexat.so")
 SOURCES = [os.path.join(CSRC, "exat.hip")]
-HEADERS = [os.path.join(CSRC, h) for h in ("exat_device.h", "exat_mode12.h", "exat_mode2.h", "exat_mode12_v2.h", "exat_mode12_v3.h", "exat_mode12_split.h", "exat_aux.h")] + \
+HEADERS = [os.path.join(CSRC, h) for h in ("exat_device.h", "exat_common.h", "exat_mode12.h", "exat_mode2.h", "exat_mode12_v2.h", "exat_mode12_v3.h", "exat_mode12_split.h", "exat_aux.h")] + \
           [os.path.join(os.path.dirname(HERE), "include", "exat.h")]
 
 

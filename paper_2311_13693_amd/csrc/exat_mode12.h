@@ -15,49 +15,10 @@
 // repeated per block.  Mode 3 (over k) is a separate small kernel.
 #pragma once
 #include "exat_device.h"
+#include "exat_common.h"
+#include "exat_mode2.h"
 
 namespace exat {
-
-struct Mode12Params {
-    const void *U;   // packed [PLpad][Ipad] of T, zero padded
-    const float *V;  // packed [P][Mpad][Jpad] fp32, zero padded (bf16-rounded values for bf16 plans)
-    float *Q;        // [k1-k0][PLpad][Mpad] fp32
-    // materialised source: element (i,j,k) at X[(i-xo_i) + (j-xo_j)*x_sj + (k-xo_k)*x_sk]
-    const void *X;
-    int64_t x_sj, x_sk, xo_i, xo_j, xo_k;
-    int x_vec;  // 16-byte loads of X are aligned
-    // generated source
-    const float *A, *B, *C;
-    int64_t ldA, ldB, ldC;
-    int R, a_vec;  // a_vec: 16-byte loads of A rows are aligned
-    uint32_t skey;
-    float amp2_ln2;  // -2 ln2 sigma^2, 0 when sigma == 0
-    int64_t I, Ipad, Jpad;
-    int L, PL, PLpad, Mpad, MT, G;
-    int row_base;  // first stacked row of row group 0 of this launch (k_mode12_v3; a multiple of 32, else 0)
-    int64_t i0, i1, j0, j1, k0, k1;
-};
-
-enum { SRC_MATERIALISED = 0, SRC_GENERATED = 1 };
-
-template <typename T> struct mma_frag;
-template <> struct mma_frag<float> {
-    typedef f32x4 type;
-    __device__ static __forceinline__ void mma(f32x16 &c, const f32x4 &a, const f32x4 &b)
-    {
-        c = __builtin_amdgcn_mfma_f32_32x32x2f32(a[0], b[0], c, 0, 0, 0);
-        c = __builtin_amdgcn_mfma_f32_32x32x2f32(a[1], b[1], c, 0, 0, 0);
-        c = __builtin_amdgcn_mfma_f32_32x32x2f32(a[2], b[2], c, 0, 0, 0);
-        c = __builtin_amdgcn_mfma_f32_32x32x2f32(a[3], b[3], c, 0, 0, 0);
-    }
-};
-template <> struct mma_frag<__bf16> {
-    typedef bf16x8 type;
-    __device__ static __forceinline__ void mma(f32x16 &c, const bf16x8 &a, const bf16x8 &b)
-    {
-        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
-    }
-};
 
 template <typename T, int RT, int CT>
 struct Mode12Cfg {
@@ -284,64 +245,9 @@ __global__ __launch_bounds__(256) void k_mode12(const Mode12Params p)
         __syncthreads();  // staging LDS is free now
         float *Zs = (float *)smem + wave * (32 * ZST);
         const bool first_chunk = (jc == ja0);
-#pragma unroll
-        for (int rt = 0; rt < RT; rt++) {
-            const int q0 = wrow0 + rt * 32;  // wave-uniform
-            if (q0 < p.PL) {
-                // C layout of the 32x32 MFMA: acc[4b + r] is row 8b + 4*hi + r, column l32
-#pragma unroll
-                for (int ct = 0; ct < CT; ct++)
-#pragma unroll
-                    for (int b4 = 0; b4 < 4; b4++)
-#pragma unroll
-                        for (int r = 0; r < 4; r++)
-                            Zs[(8 * b4 + 4 * hi + r) * ZST + ct * 32 + l32] = acc[rt][ct][4 * b4 + r];
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                __builtin_amdgcn_wave_barrier();
-                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-                const int qlast = (q0 + 31 < p.PL - 1) ? q0 + 31 : p.PL - 1;
-                const int pfirst = q0 / p.L, plast = qlast / p.L;
-                for (int pp = pfirst; pp <= plast; pp++) {
-                    f32x16 qa[2];
-#pragma unroll
-                    for (int mt = 0; mt < 2; mt++)
-#pragma unroll
-                        for (int e = 0; e < 16; e++) qa[mt][e] = 0.0f;
-                    const float *Vp = p.V + (int64_t)pp * p.Mpad * p.Jpad + jc;
-#pragma unroll 4
-                    for (int g8 = 0; g8 < COLS / 8; g8++) {
-                        const f32x4 a = *(const f32x4 *)(Zs + l32 * ZST + 8 * g8 + 4 * hi);
-#pragma unroll
-                        for (int mt = 0; mt < 2; mt++) {
-                            if (mt < p.MT) {
-                                const f32x4 bv = *(const f32x4 *)(Vp + (int64_t)(mt * 32 + l32) * p.Jpad + 8 * g8 + 4 * hi);
-                                mma_frag<float>::mma(qa[mt], a, bv);
-                            }
-                        }
-                    }
-                    const int rlo = pp * p.L, rhi = rlo + p.L;  // rows of replica pp
-#pragma unroll
-                    for (int mt = 0; mt < 2; mt++) {
-                        if (mt < p.MT) {
-#pragma unroll
-                            for (int b4 = 0; b4 < 4; b4++)
-#pragma unroll
-                                for (int r = 0; r < 4; r++) {
-                                    const int row = q0 + 8 * b4 + 4 * hi + r;
-                                    if (row >= rlo && row < rhi) {
-                                        float *dst = p.Q + ((int64_t)kidx * p.PLpad + row) * p.Mpad + mt * 32 + l32;
-                                        float v = qa[mt][4 * b4 + r];
-                                        if (!first_chunk) v += *dst;
-                                        *dst = v;
-                                    }
-                                }
-                        }
-                    }
-                }
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                __builtin_amdgcn_wave_barrier();
-            }
-        }
+        const CheckParams ck = {};
+        if (p.MT == 2) mode2_chunk<RT, CT, false, 2, VM_F32, 4>(p, nullptr, ck, Zs, acc, wrow0, kidx, jc, first_chunk, lane);
+        else mode2_chunk<RT, CT, false, 1, VM_F32, 4>(p, nullptr, ck, Zs, acc, wrow0, kidx, jc, first_chunk, lane);
     }
 }
 

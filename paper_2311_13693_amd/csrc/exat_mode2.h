@@ -6,7 +6,7 @@
 // (its rows exist up to PLpad), V and B/C gathers are unconditional, the rows of a replica are picked with a
 // select.  Per-element branches here cost a scratch reload and a full memory wait each.
 #pragma once
-#include "exat_mode12.h"
+#include "exat_common.h"
 
 namespace exat {
 
