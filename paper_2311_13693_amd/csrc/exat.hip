@@ -323,8 +323,12 @@ int run_chain(exat_plan_s *pl, Mode12Params mp, bool generated, float *Yout, int
     m3.Npad = pl->Npad;
     m3.K = pl->d.K; m3.k0 = mp.k0; m3.k1 = mp.k1; m3.accumulate = accumulate;
     const int64_t ntile = ((int64_t)pl->PL * pl->Mpad + 31) / 32;
-    dim3 grid((unsigned)((ntile + 3) / 4), (unsigned)((pl->Npad + 63) / 64));
-    hipLaunchKernelGGL(k_mode3, grid, dim3(256), 0, st, m3);
+    dim3 grid((unsigned)ntile, (unsigned)((pl->Npad + 63) / 64));
+    if (pl->Npad % 64 == 0) hipLaunchKernelGGL(k_mode3<2>, grid, dim3(64 * M3_WAVES), 0, st, m3);
+    else {  // 32-column tiles, so that no launch carries an idle second tile
+        grid.y = (unsigned)(pl->Npad / 32);
+        hipLaunchKernelGGL(k_mode3<1>, grid, dim3(64 * M3_WAVES), 0, st, m3);
+    }
     if (hipGetLastError() != hipSuccess) return EXAT_ERR_HIP;
     if (pl->timing) {
         if (hipEventRecord(pl->ev[2], st) != hipSuccess) return EXAT_ERR_HIP;

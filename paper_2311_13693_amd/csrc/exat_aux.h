@@ -61,58 +61,95 @@ struct Mode3Params {
     int accumulate;
 };
 
-__global__ __launch_bounds__(256) void k_mode3(const Mode3Params p)
+// One workgroup per 32 (q, m) positions x <= 64 columns n; its M3_WAVES waves split the k range into contiguous
+// slabs (the outputs are few and the k range long, so k is where the parallelism is) and wave 0 adds the partial
+// sums in wave order, which keeps the result independent of timing.
+constexpr int M3_WAVES = 4;
+
+template <int NT>  // NT = 32-column tiles of n per workgroup (1 or 2)
+__global__ __launch_bounds__(64 * M3_WAVES) void k_mode3(const Mode3Params p)
 {
     constexpr int KFLUSH = 512;
+    __shared__ float part[M3_WAVES - 1][NT][16][64];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, l32 = lane & 31, hi = lane >> 5;
-    const int64_t pos0 = ((int64_t)blockIdx.x * 4 + wave) * 32;
-    if (pos0 >= (int64_t)p.PL * p.Mpad) return;  // whole wave; the kernel has no barriers
+    const int64_t pos0 = (int64_t)blockIdx.x * 32;
+    if (pos0 >= (int64_t)p.PL * p.Mpad) return;  // whole workgroup
     const int q = (int)(pos0 / p.Mpad), m0 = (int)(pos0 % p.Mpad);
-    if (m0 >= p.M) return;                       // a tile made of padding columns only
+    if (m0 >= p.M) return;                       // a tile made of padding columns only (whole workgroup)
     const int pr = q / p.L, l = q % p.L;
-    const int n0 = blockIdx.y * 64;
-    const int ntiles = (p.Npad - n0 >= 64) ? 2 : 1;
-    const int64_t nk = p.k1 - p.k0, qs = (int64_t)p.PLpad * p.Mpad;
-    const float *qp = p.Q + pos0 + l32;                                       // + kk*qs
-    const float *wp = p.W + ((int64_t)pr * p.K + p.k0) * p.Npad + n0 + l32;   // + kk*Npad (+32 for tile 1)
-    double tot[2][16];
+    const int n0 = blockIdx.y * 32 * NT;
+    const int64_t nkall = p.k1 - p.k0, qs = (int64_t)p.PLpad * p.Mpad;
+    const int64_t slab = (((nkall + M3_WAVES - 1) / M3_WAVES) + 1) & ~(int64_t)1;  // even: lanes 32..63 take odd k
+    const int64_t kbeg = wave * slab;
+    const int64_t nk = (kbeg >= nkall) ? 0 : ((kbeg + slab < nkall) ? slab : nkall - kbeg);
+    const float *qp = p.Q + kbeg * qs + pos0 + l32;                                    // + kk*qs
+    const float *wp = p.W + ((int64_t)pr * p.K + p.k0 + kbeg) * p.Npad + n0 + l32;     // + kk*Npad (+32 for tile 1)
+    double tot[NT][16];
 #pragma unroll
-    for (int t = 0; t < 2; t++)
+    for (int t = 0; t < NT; t++)
 #pragma unroll
         for (int e = 0; e < 16; e++) tot[t][e] = 0.0;
     for (int64_t kc = 0; kc < nk; kc += KFLUSH) {
-        f32x16 acc[2];
+        f32x16 acc[NT];
 #pragma unroll
-        for (int t = 0; t < 2; t++)
+        for (int t = 0; t < NT; t++)
 #pragma unroll
             for (int e = 0; e < 16; e++) acc[t][e] = 0.0f;
         const int64_t kend = (kc + KFLUSH < nk) ? kc + KFLUSH : nk;
-        for (int64_t kk = kc; kk < kend; kk += 8) {
-            float a[4], b0[4], b1[4];
+        // 16 values of k per batch, two register sets: the loads of the next batch are issued before the MFMAs
+        // of the current one (the kernel runs at well under one wave per SIMD, so nothing else hides the latency)
+        constexpr int KB = 16, NS = KB / 2;
+        float a0[NS], b00[NS], b10[NS], a1[NS], b01[NS], b11[NS];  // b1* unused when NT == 1
+        auto load_batch = [&](float *a, float *b0, float *b1, int64_t kk) {
 #pragma unroll
-            for (int t = 0; t < 4; t++) {
+            for (int t = 0; t < NS; t++) {
                 const int64_t kx = kk + 2 * t + hi;
                 const bool ok = kx < kend;
                 a[t] = ok ? qp[kx * qs] : 0.0f;
                 b0[t] = ok ? wp[kx * p.Npad] : 0.0f;
-                b1[t] = (ok && ntiles == 2) ? wp[kx * p.Npad + 32] : 0.0f;
+                if (NT == 2) b1[t] = ok ? wp[kx * p.Npad + 32] : 0.0f;
             }
+        };
+        auto mma_batch = [&](const float *a, const float *b0, const float *b1) {
 #pragma unroll
-            for (int t = 0; t < 4; t++) {
+            for (int t = 0; t < NS; t++) {
                 acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[t], b0[t], acc[0], 0, 0, 0);
-                if (ntiles == 2) acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[t], b1[t], acc[1], 0, 0, 0);
+                if (NT == 2) acc[NT - 1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[t], b1[t], acc[1], 0, 0, 0);
             }
+        };
+        load_batch(a0, b00, b10, kc);
+        for (int64_t kk = kc; kk < kend; kk += 2 * KB) {
+            load_batch(a1, b01, b11, kk + KB);       // zeros beyond kend
+            __builtin_amdgcn_sched_barrier(0);
+            mma_batch(a0, b00, b10);
+            load_batch(a0, b00, b10, kk + 2 * KB);
+            __builtin_amdgcn_sched_barrier(0);
+            mma_batch(a1, b01, b11);
         }
 #pragma unroll
-        for (int t = 0; t < 2; t++)
+        for (int t = 0; t < NT; t++)
 #pragma unroll
             for (int e = 0; e < 16; e++) tot[t][e] += (double)acc[t][e];
     }
+    if (wave > 0) {
+#pragma unroll
+        for (int t = 0; t < NT; t++)
+#pragma unroll
+            for (int e = 0; e < 16; e++) part[wave - 1][t][e][lane] = (float)tot[t][e];
+    }
+    __syncthreads();
+    if (wave > 0) return;
+#pragma unroll
+    for (int w = 0; w < M3_WAVES - 1; w++)
+#pragma unroll
+        for (int t = 0; t < NT; t++)
+#pragma unroll
+            for (int e = 0; e < 16; e++) tot[t][e] += (double)part[w][t][e][lane];
     // C layout: element 4b+r of the accumulator is row (position) 8b + 4*hi + r, column n = l32
 #pragma unroll
-    for (int t = 0; t < 2; t++) {
+    for (int t = 0; t < NT; t++) {
         const int n = n0 + 32 * t + l32;
-        if (t < ntiles && n < p.N) {
+        if (n < p.N) {
 #pragma unroll
             for (int b4 = 0; b4 < 4; b4++)
 #pragma unroll
