@@ -5,7 +5,8 @@ cpu_baseline leg may import this package; the product (the HIP library and its
 Python binding) never does, and this package never imports the product.
 
 Every function is a numpy-facing wrapper over oracle/exat_oracle.c (plain C,
-fp64 accumulation), plus two pure-numpy cross-checks used only by the pins.
+fp64 accumulation), except the two-stage functions at the end (Sec. 4.4), which are
+plain numpy in fp64.
 
 Conventions (paper Sec. 3, Eq. 3 and Sec. 4.1):
   X   float32 array of shape (I, J, K), Fortran (column-major) order
@@ -184,3 +185,49 @@ def rel_fro(Y, Yref):
     num = np.sqrt(((Y - Yref) ** 2).sum(axis=(0, 1, 2)))
     den = np.sqrt((Yref ** 2).sum(axis=(0, 1, 2)))
     return float((num / den).max())
+
+
+# ---- Two-stage compression (Sec. 4.4): U_p = U'_p U with sparse U, V, W ---------------------------
+# Plain numpy in fp64.  The sparse matrices are expanded to dense ones and the definition of the
+# mode products is applied with numpy's tensordot; nothing here exploits the sparsity.
+
+def csr_dense(csr, cols):
+    """Dense float64 (rows, cols) matrix of a CSR triple (rowptr, colidx, val); duplicates add."""
+    rowptr, colidx, val = csr
+    rows = len(rowptr) - 1
+    D = np.zeros((rows, cols), dtype=np.float64)
+    for r in range(rows):
+        for e in range(int(rowptr[r]), int(rowptr[r + 1])):
+            D[r, int(colidx[e])] += float(val[e])
+    return D
+
+
+def ttm_chain64(X, U, V, W):
+    """X x1 U x2 V x3 W (Eq. 3) for float64 matrices U (L,I), V (M,J), W (N,K); returns (L,M,N) float64."""
+    Z = np.tensordot(np.asarray(U, dtype=np.float64), np.asarray(X, dtype=np.float64), axes=(1, 0))  # (L,J,K)
+    Z = np.tensordot(np.asarray(V, dtype=np.float64), Z, axes=(1, 1))                                # (M,L,K)
+    Z = np.tensordot(np.asarray(W, dtype=np.float64), Z, axes=(1, 2))                                # (N,M,L)
+    return np.asfortranarray(Z.transpose(2, 1, 0))
+
+
+def first_stage(X, Ucsr, Vcsr, Wcsr):
+    """The implicit first compression of Sec. 4.4: X x1 U x2 V x3 W with the shared sparse matrices."""
+    I, J, K = X.shape
+    return ttm_chain64(X, csr_dense(Ucsr, I), csr_dense(Vcsr, J), csr_dense(Wcsr, K))
+
+
+def two_stage(X, Ucsr, Vcsr, Wcsr, U2, V2, W2, P, replicas=None):
+    """Y_p = Comp(X, U'_p U, V'_p V, W'_p W) (Sec. 4.4) with the composed matrices formed explicitly.
+    U2 is the stacked (P*L, alpha L) matrix etc.  Returns float64 (L, M, N, len(replicas)), Fortran order."""
+    I, J, K = X.shape
+    Ud, Vd, Wd = csr_dense(Ucsr, I), csr_dense(Vcsr, J), csr_dense(Wcsr, K)
+    L, M, N = U2.shape[0] // P, V2.shape[0] // P, W2.shape[0] // P
+    reps = list(range(P)) if replicas is None else list(replicas)
+    Y = np.zeros((L, M, N, len(reps)), dtype=np.float64, order="F")
+    X64 = np.asarray(X, dtype=np.float64)
+    for t, p in enumerate(reps):
+        Up = U2[p * L:(p + 1) * L].astype(np.float64) @ Ud
+        Vp = V2[p * M:(p + 1) * M].astype(np.float64) @ Vd
+        Wp = W2[p * N:(p + 1) * N].astype(np.float64) @ Wd
+        Y[:, :, :, t] = ttm_chain64(X64, Up, Vp, Wp)
+    return Y

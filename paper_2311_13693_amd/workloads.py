@@ -98,3 +98,70 @@ def small(name="tiny", index=100, I=24, J=20, K=28, R=3, P=3, L=5, M=4, N=6, dI=
           dtype="f32", materialised=True, sigma=0.01) -> Config:
     """An arbitrary small non-cubic configuration for tests."""
     return Config(name, I, J, K, R, P, L, M, N, dI, dJ, dK, dtype, materialised, sigma, index)
+
+
+# ---- Two-stage compression (Sec. 4.4): sparse first-stage matrices, dense second-stage replicas ----
+
+@dataclass(frozen=True)
+class TwoStage:
+    """First stage I x J x K -> (alpha L) x (beta M) x (gamma N) with sparse U, V, W shared by all
+    replicas, second stage with dense U'_p (L x alpha L) etc.  The paper leaves the sparsity pattern
+    open; the inputs drawn here are sparse sign matrices with `nnz_per_col` entries +-1/sqrt(nnz_per_col)
+    in every column, at distinct rows drawn uniformly (a standard compressed-sensing ensemble)."""
+    base: Config
+    alpha: int = 2
+    beta: int = 2
+    gamma: int = 2
+    nnz_per_col: int = 4
+
+    @property
+    def A1(self) -> int:
+        return self.alpha * self.base.L
+
+    @property
+    def B1(self) -> int:
+        return self.beta * self.base.M
+
+    @property
+    def C1(self) -> int:
+        return self.gamma * self.base.N
+
+    @property
+    def second(self) -> Config:
+        """The dense multi-replica problem on the first stage's output (one block)."""
+        b = self.base
+        return replace(b, name=b.name + "_stage2", I=self.A1, J=self.B1, K=self.C1,
+                       dI=self.A1, dJ=self.B1, dK=self.C1, materialised=True)
+
+
+def sparse_sign_csr(seed, stream, rows, cols, nnz_per_col):
+    """CSR arrays (rowptr int64 [rows+1], colidx int32, val float32) of a rows x cols matrix whose every
+    column holds nnz_per_col entries +-1/sqrt(nnz_per_col) at distinct rows; columns sorted inside a row."""
+    s = min(nnz_per_col, rows)
+    g = np.random.Generator(np.random.Philox(key=[seed & 0xFFFFFFFFFFFFFFFF, stream]))
+    r = np.argsort(g.random((cols, rows)), axis=1)[:, :s].astype(np.int64)      # s distinct rows per column
+    sign = np.where(g.random((cols, s)) < 0.5, -1.0, 1.0)
+    c = np.repeat(np.arange(cols, dtype=np.int64), s)
+    r = r.reshape(-1)
+    v = (sign.reshape(-1) / np.sqrt(s)).astype(np.float32)
+    order = np.lexsort((c, r))
+    r, c, v = r[order], c[order], v[order]
+    rowptr = np.zeros(rows + 1, dtype=np.int64)
+    np.add.at(rowptr, r + 1, 1)
+    return np.cumsum(rowptr), c.astype(np.int32), v
+
+
+def first_stage_matrices(ts: TwoStage):
+    """Sparse U (alpha L x I), V (beta M x J), W (gamma N x K) as CSR triples."""
+    b = ts.base
+    return (sparse_sign_csr(b.seed, 7, ts.A1, b.I, ts.nnz_per_col),
+            sparse_sign_csr(b.seed, 8, ts.B1, b.J, ts.nnz_per_col),
+            sparse_sign_csr(b.seed, 9, ts.C1, b.K, ts.nnz_per_col))
+
+
+def second_stage_matrices(ts: TwoStage):
+    """Stacked dense U' (P*L x alpha L), V' (P*M x beta M), W' (P*N x gamma N), iid N(0, 1/L) etc."""
+    b = ts.base
+    return (_normal(b.seed, 10, (b.P * b.L, ts.A1), b.L ** -0.5),
+            _normal(b.seed, 11, (b.P * b.M, ts.B1), b.M ** -0.5),
+            _normal(b.seed, 12, (b.P * b.N, ts.C1), b.N ** -0.5))
