@@ -162,6 +162,54 @@ int exat_plan_check_status(exat_plan_t plan, uint32_t *counters8);
 int exat_plan_set_timing(exat_plan_t plan, int enable);
 int exat_plan_last_timing(exat_plan_t plan, float *ms_mode12, float *ms_mode3);
 
+/* ---- Two-stage compression (Sec. 4.4) --------------------------------------------------------------
+ * The paper builds the compression matrices as U_p = U'_p U, V_p = V'_p V, W_p = W'_p W with sparse
+ * U (A1 x I), V (B1 x J), W (C1 x K) shared by all replicas (A1 = alpha L etc., alpha > 1), which turns
+ * the compression into I x J x K -> A1 x B1 x C1 -> L x M x N.  The first stage,
+ *
+ *     X1[a,b,c] = sum_{i,j,k} U[a,i] V[b,j] W[c,k] X[i,j,k],
+ *
+ * is what exat_stage1_apply computes: one pass over X that is bound by reading it (no matrix cores).
+ * The second stage is the dense multi-replica compression of X1: an ordinary plan with I,J,K = A1,B1,C1
+ * and U', V', W' as its factors, fed with X1 through exat_compress.
+ *
+ * A sparse matrix is handed over in CSR form in HOST memory and copied at creation: rowptr[rows+1]
+ * (rowptr[0] = 0, non-decreasing), colidx/val[rowptr[rows]] (0 <= colidx < cols; any order inside a row;
+ * repeated entries add).  The paper fixes neither pattern nor density; any CSR matrix is accepted. */
+typedef struct {
+    int32_t rows;           /* U, V: 1..128; W: 1..65535                         */
+    int64_t cols;           /* must equal I, J, K respectively                   */
+    const int64_t *rowptr;  /* host */
+    const int32_t *colidx;  /* host */
+    const float *val;       /* host */
+} exat_csr_t;
+
+typedef struct exat_stage1_s *exat_stage1_t; /* opaque */
+
+/* Creates the first-stage operator for an I x J x K tensor on the current device: validates and copies
+ * the three matrices (re-tiled for the kernels) and allocates the K x B1 x A1 float intermediate.
+ * Synchronous (blocking host-to-device copies).  Errors: NULL, SHAPE (extents, rows out of range, cols
+ * mismatch, malformed CSR, more than 2^31-256 entries), ALLOC, HIP. */
+int exat_stage1_create(exat_stage1_t *s, int64_t I, int64_t J, int64_t K, const exat_csr_t *U,
+                       const exat_csr_t *V, const exat_csr_t *W);
+
+/* Frees the operator; the caller must have synchronised the streams it was used on.  NULL is accepted. */
+int exat_stage1_destroy(exat_stage1_t s);
+
+/* Output extents A1, B1, C1 (the row counts of U, V, W).  Errors: NULL. */
+int exat_stage1_dims(exat_stage1_t s, int32_t *A1, int32_t *B1, int32_t *C1);
+
+/* X1 = X x1 U x2 V x3 W.  X: device, fp32, column-major I x J x K.  X1: device, A1*B1*C1 floats,
+ * column-major (X1[a + A1*(b + B1*c)]), overwritten.  fp32 arithmetic with a fixed summation order
+ * (bit-identical from run to run).  Asynchronous on `stream`; calls on one operator must not overlap
+ * (they share its intermediate).  Errors: NULL, HIP. */
+int exat_stage1_apply(exat_stage1_t s, const float *X, float *X1, void *stream);
+
+/* Measurement aid, as exat_plan_set_timing / exat_plan_last_timing: durations of the fused mode-1/2
+ * kernel and of the mode-3 kernel of the most recent exat_stage1_apply. */
+int exat_stage1_set_timing(exat_stage1_t s, int enable);
+int exat_stage1_last_timing(exat_stage1_t s, float *ms_mode12, float *ms_mode3);
+
 /* Static description of a status code (never NULL). */
 const char *exat_strerror(int status);
 

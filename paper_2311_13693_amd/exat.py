@@ -15,7 +15,9 @@ OK, ERR_NULL, ERR_SHAPE, ERR_DTYPE, ERR_STATE, ERR_ALLOC, ERR_HIP = 0, -1, -2, -
 
 EXPORTS = ["exat_plan_create", "exat_plan_destroy", "exat_set_factors", "exat_compress",
            "exat_compress_block", "exat_finalize", "exat_compress_gen", "exat_gen_block",
-           "exat_plan_set_timing", "exat_plan_last_timing", "exat_plan_check_status", "exat_strerror"]
+           "exat_plan_set_timing", "exat_plan_last_timing", "exat_plan_check_status",
+           "exat_stage1_create", "exat_stage1_destroy", "exat_stage1_dims", "exat_stage1_apply",
+           "exat_stage1_set_timing", "exat_stage1_last_timing", "exat_strerror"]
 
 
 class Desc(ctypes.Structure):
@@ -33,6 +35,11 @@ class Gen(ctypes.Structure):
 class Box(ctypes.Structure):
     _fields_ = [("i0", ctypes.c_int64), ("i1", ctypes.c_int64), ("j0", ctypes.c_int64),
                 ("j1", ctypes.c_int64), ("k0", ctypes.c_int64), ("k1", ctypes.c_int64)]
+
+
+class Csr(ctypes.Structure):
+    _fields_ = [("rows", ctypes.c_int32), ("cols", ctypes.c_int64), ("rowptr", ctypes.c_void_p),
+                ("colidx", ctypes.c_void_p), ("val", ctypes.c_void_p)]
 
 
 class ExatError(RuntimeError):
@@ -69,6 +76,13 @@ def lib():
         L.exat_plan_set_timing.argtypes = [vp, ctypes.c_int]
         L.exat_plan_last_timing.argtypes = [vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_float)]
         L.exat_plan_check_status.argtypes = [vp, ctypes.POINTER(ctypes.c_uint32)]
+        L.exat_stage1_create.argtypes = [ctypes.POINTER(vp), i64, i64, i64, ctypes.POINTER(Csr), ctypes.POINTER(Csr),
+                                         ctypes.POINTER(Csr)]
+        L.exat_stage1_destroy.argtypes = [vp]
+        L.exat_stage1_dims.argtypes = [vp, ctypes.POINTER(i32), ctypes.POINTER(i32), ctypes.POINTER(i32)]
+        L.exat_stage1_apply.argtypes = [vp, vp, vp, vp]
+        L.exat_stage1_set_timing.argtypes = [vp, ctypes.c_int]
+        L.exat_stage1_last_timing.argtypes = [vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_float)]
         L.exat_strerror.argtypes = [ctypes.c_int]
         L.exat_strerror.restype = ctypes.c_char_p
         for name in EXPORTS[:-1]:
@@ -186,3 +200,59 @@ class Plan:
         b = None if box is None else ctypes.byref(Box(*box))
         _check(lib().exat_compress_gen(self._h, ctypes.byref(gen), b, _ptr(Y), _stream_handle(stream)))
         return Y
+
+
+def make_csr(rowptr, colidx, val, cols):
+    """Host CSR arrays (numpy) -> exat_csr_t; the arrays are converted to int64 / int32 / float32 and kept alive."""
+    import numpy as np
+    rp = np.ascontiguousarray(rowptr, dtype=np.int64)
+    ci = np.ascontiguousarray(colidx, dtype=np.int32)
+    v = np.ascontiguousarray(val, dtype=np.float32)
+    c = Csr(len(rp) - 1, cols, rp.ctypes.data, ci.ctypes.data, v.ctypes.data)
+    c._keep = (rp, ci, v)
+    return c
+
+
+class Stage1:
+    """Owns an exat_stage1_t: the sparse first stage X1 = X x1 U x2 V x3 W of the two-stage compression.
+    U, V, W are (rowptr, colidx, val) CSR triples in host memory."""
+
+    def __init__(self, I, J, K, U, V, W):
+        self._h = ctypes.c_void_p()
+        cu, cv, cw = make_csr(*U, I), make_csr(*V, J), make_csr(*W, K)
+        _check(lib().exat_stage1_create(ctypes.byref(self._h), I, J, K, ctypes.byref(cu), ctypes.byref(cv),
+                                        ctypes.byref(cw)))
+        a, b, c = ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int32()
+        _check(lib().exat_stage1_dims(self._h, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)))
+        self.dims = (a.value, b.value, c.value)
+
+    def close(self):
+        if self._h:
+            import torch
+            torch.cuda.synchronize()
+            lib().exat_stage1_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def set_timing(self, enable=True):
+        _check(lib().exat_stage1_set_timing(self._h, 1 if enable else 0))
+
+    def last_timing(self):
+        a, b = ctypes.c_float(), ctypes.c_float()
+        _check(lib().exat_stage1_last_timing(self._h, ctypes.byref(a), ctypes.byref(b)))
+        return a.value, b.value
+
+    def apply(self, X, X1=None, stream=None):
+        """X: float32 CUDA tensor holding the column-major I x J x K tensor; returns the flat column-major
+        A1 x B1 x C1 result."""
+        import torch
+        assert X.is_cuda and X.dtype == torch.float32 and X.is_contiguous()
+        if X1 is None:
+            X1 = torch.empty(self.dims[0] * self.dims[1] * self.dims[2], dtype=torch.float32, device="cuda")
+        _check(lib().exat_stage1_apply(self._h, _ptr(X), _ptr(X1), _stream_handle(stream)))
+        return X1

@@ -4,6 +4,7 @@ import ctypes
 import os
 import re
 
+import numpy as np
 import pytest
 
 from paper_2311_13693_amd import exat
@@ -70,3 +71,20 @@ def test_null_arguments_are_errors_not_crashes():
     assert L.exat_gen_block(ctypes.byref(d), ctypes.byref(g2), 0, 0, 0, ctypes.c_void_p(1), None) == exat.ERR_SHAPE
     g3 = exat.Gen(1, 1, 1, 2, 1, 0.0)
     assert L.exat_gen_block(ctypes.byref(d), ctypes.byref(g3), 2, 0, 0, ctypes.c_void_p(1), None) == exat.ERR_SHAPE
+
+
+def test_stage1_argument_errors():
+    # validation happens before the first HIP call, so this runs without a GPU
+    L = exat.lib()
+    h = ctypes.c_void_p()
+    rp = np.array([0, 1, 2], dtype=np.int64); ci = np.array([0, 1], dtype=np.int32); v = np.ones(2, dtype=np.float32)
+    good = exat.make_csr(rp, ci, v, 4)
+    for bad, code in ((exat.make_csr(rp, ci, v, 5), exat.ERR_SHAPE),                                  # cols != I
+                      (exat.make_csr(rp, np.array([0, 4], dtype=np.int32), v, 4), exat.ERR_SHAPE),    # column out of range
+                      (exat.make_csr(np.array([0, 2, 1], dtype=np.int64), ci, v, 4), exat.ERR_SHAPE),  # decreasing rowptr
+                      (exat.make_csr(np.zeros(130, dtype=np.int64), ci[:0], v[:0], 4), exat.ERR_SHAPE)):  # 129 rows
+        assert L.exat_stage1_create(ctypes.byref(h), 4, 4, 4, ctypes.byref(bad), ctypes.byref(good), ctypes.byref(good)) == code
+    assert L.exat_stage1_create(ctypes.byref(h), 4, 4, 4, None, ctypes.byref(good), ctypes.byref(good)) == exat.ERR_NULL
+    assert L.exat_stage1_create(ctypes.byref(h), 0, 4, 4, ctypes.byref(good), ctypes.byref(good), ctypes.byref(good)) == exat.ERR_SHAPE
+    assert L.exat_stage1_apply(None, None, None, None) == exat.ERR_NULL
+    assert L.exat_stage1_destroy(None) == exat.OK

@@ -1,0 +1,107 @@
+"""GPU parity of the two-stage compression (paper Sec. 4.4) against the CPU oracle, through the C ABI:
+the sparse first stage on its own (element by element) and the whole chain first stage -> dense
+multi-replica compression.  Tolerance: relative Frobenius error <= 1e-5 (fp32 arithmetic)."""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2311_13693_amd import exat, workloads as wl
+from tests import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-5
+
+
+def _ts(I, J, K, L, M, N, P=3, alpha=2, beta=2, gamma=2, s=4, index=300):
+    base = wl.small(index=index, I=I, J=J, K=K, L=L, M=M, N=N, P=P, dI=I, dJ=J, dK=K)
+    return wl.TwoStage(base, alpha, beta, gamma, s)
+
+
+def _x(seed, I, J, K):
+    return np.asfortranarray(np.random.default_rng(seed).standard_normal((I, J, K)).astype(np.float32))
+
+
+def _rel(a, b):
+    return float(np.linalg.norm(a - b) / np.linalg.norm(b))
+
+
+def _first_stage_gpu(ts, X, mats):
+    b = ts.base
+    st = exat.Stage1(b.I, b.J, b.K, *mats)
+    assert st.dims == (ts.A1, ts.B1, ts.C1)
+    X1 = st.apply(gu.to_dev_x(X))
+    torch.cuda.synchronize()
+    out = X1.cpu().numpy().astype(np.float64).reshape(st.dims, order="F")
+    st.close()
+    return out
+
+
+# several tiles in i (128) and j (64) with ragged tails, both row-count instantiations of a and b
+@pytest.mark.parametrize("shape", [
+    dict(I=300, J=150, K=9, L=8, M=5, N=3),                              # A1=16, B1=10: small row counts
+    dict(I=129, J=65, K=5, L=32, M=32, N=4),                             # A1=B1=64: exactly one lane tile
+    dict(I=257, J=200, K=7, L=50, M=20, N=6),                            # A1=100 (two lane tiles), B1=40
+    dict(I=140, J=70, K=6, L=11, M=45, N=9, beta=2),                     # A1=22, B1=90
+    dict(I=384, J=130, K=4, L=64, M=64, N=2),                            # A1=B1=128: the largest supported
+    dict(I=5, J=3, K=2, L=1, M=1, N=1, alpha=1, beta=1, gamma=1, s=1),   # everything smaller than a tile
+])
+def test_first_stage_matches_oracle(shape):
+    ts = _ts(**shape)
+    b = ts.base
+    print("case", shape, flush=True)
+    X = _x(11, b.I, b.J, b.K)
+    mats = wl.first_stage_matrices(ts)
+    ref = oracle.first_stage(X, *mats)
+    got = _first_stage_gpu(ts, X, mats)
+    err = _rel(got, ref)
+    print("  rel_fro=%.3e" % err, flush=True)
+    assert err <= TOL
+    assert np.abs(got - ref).max() <= 1e-5 * np.abs(ref).max()
+
+
+def test_first_stage_general_csr_and_run_to_run():
+    # a general CSR matrix: unsorted columns, repeated entries, empty rows, arbitrary values
+    rng = np.random.default_rng(5)
+    I, J, K = 200, 90, 12
+
+    def rand_csr(rows, cols, density):
+        rowptr, ci, v = [0], [], []
+        for r in range(rows):
+            n = 0 if r % 5 == 3 else int(rng.integers(1, max(2, int(cols * density))))
+            c = rng.integers(0, cols, n)
+            ci.extend(c.tolist()); v.extend(rng.standard_normal(n).tolist())
+            rowptr.append(len(ci))
+        return np.array(rowptr, dtype=np.int64), np.array(ci, dtype=np.int32), np.array(v, dtype=np.float32)
+    mats = (rand_csr(37, I, 0.2), rand_csr(70, J, 0.3), rand_csr(9, K, 0.9))
+    X = _x(6, I, J, K)
+    ref = oracle.first_stage(X, *mats)
+    st = exat.Stage1(I, J, K, *mats)
+    Xd = gu.to_dev_x(X)
+    a = st.apply(Xd).clone()
+    b = st.apply(Xd)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)                                     # fixed summation order
+    got = a.cpu().numpy().astype(np.float64).reshape(st.dims, order="F")
+    assert _rel(got, ref) <= TOL
+    assert (got[3] == 0).all() and (got[:, 3] == 0).all()        # empty rows give exact zeros
+    st.close()
+
+
+def test_two_stage_chain_matches_oracle():
+    ts = _ts(I=200, J=136, K=90, L=12, M=10, N=8, P=3, alpha=2, beta=3, gamma=2, s=4, index=301)
+    b = ts.base
+    X = _x(7, b.I, b.J, b.K)
+    mats = wl.first_stage_matrices(ts)
+    U2, V2, W2 = wl.second_stage_matrices(ts)
+    ref = oracle.two_stage(X, *mats, U2, V2, W2, b.P)
+    st = exat.Stage1(b.I, b.J, b.K, *mats)
+    plan = gu.plan_with_factors(ts.second, U2, V2, W2)
+    Y = plan.compress(st.apply(gu.to_dev_x(X)))
+    torch.cuda.synchronize()
+    err = oracle.rel_fro(gu.y_to_numpy(Y, b), ref)
+    print("two-stage chain rel_fro=%.3e" % err, flush=True)
+    assert err <= TOL
+    plan.close(); st.close()
