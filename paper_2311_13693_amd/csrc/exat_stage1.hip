@@ -18,7 +18,9 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstdint>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -27,30 +29,50 @@ namespace {
 
 constexpr int S1_IT = 128;     // rows i per tile
 constexpr int S1_JT = 64;      // columns j per tile (one per lane)
+constexpr int S1_NW = 8;       // waves per workgroup
+constexpr int S1_NT = 64 * S1_NW;
 constexpr int S1_XS = S1_IT + 1;  // LDS row stride of the X tile (odd: lanes reading one i of 64 columns hit 64 banks)
 constexpr int S1_MAXROWS = 128;   // largest A1 and B1
 constexpr int64_t kMaxExtent1 = 2147483647LL - 64;
 
 struct SEnt { int c; float v; };  // one non-zero: column inside its tile, value
 
+// Mode-1 work of one wave on one row tile: a stream of 64-byte chunks, each holding up to 8 non-zeros of ONE
+// output row as (word, value) pairs.  A word's low 9 bits are the non-zero's byte offset in an LDS tile row
+// (4 * local column); the first word of a chunk also carries the output row (bits 9..16), whether this is
+// the row's last chunk in the tile (bit 17) and whether pairs 4..7 are only padding (bit 18).  Padding pairs
+// are (0, 0.0f).
+constexpr int CH_LAST = 1 << 17, CH_HALF = 1 << 18;
+
 struct S1Params {
     const float *X;
     int64_t I, J, K;
     int A1, B1;
-    const int *Utp;    // [nit][A1+1] offsets into Uent; every (tile,row) range is a multiple of 4 entries
-    const SEnt *Uent;
-    const int *Vtp;    // [njt][B1+1]
+    const int2 *Uoc;   // [nit][S1_NW waves]: (first chunk, number of chunks) of the wave's stream
+    const int *Uch;    // chunks, 16 ints each; two padding chunks at the very end
+    const int *Vtp;    // [njt][B1+1] offsets into Vent; every (tile,row) range is a multiple of 4 entries
     const SEnt *Vent;
     float *Q;          // [K][B1][A1]
+    int abl;
 };
 
-// AR = output rows a per wave in mode 1 (A1 <= 4*AR), AT = 64-lane tiles of a in mode 2 (A1 <= 64*AT),
-// BR = output rows b per wave in mode 2 (B1 <= 4*BR)
-template <int AR, int AT, int BR>
-__global__ __launch_bounds__(256) void k_stage1_mode12(const S1Params p)
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+
+// The operator's tables are never written while a kernel runs.  Reading them through the constant address
+// space tells the compiler so: wave-uniform reads then go through the scalar cache into SGPRs even in loops
+// that contain LDS atomics (which it otherwise takes for possible writers).
+#define S1_CONST __attribute__((address_space(4)))
+template <typename T>
+__device__ inline const S1_CONST T *as_const(const T *p) { return (const S1_CONST T *)(uintptr_t)p; }
+
+// AT = 64-lane tiles of a (A1 <= 64*AT), BR = output rows b per wave in mode 2 (B1 <= S1_NW*BR)
+template <int AT, int BR>
+__global__ __launch_bounds__(S1_NT) void k_stage1_mode12(const S1Params p)
 {
     extern __shared__ float smem[];
     constexpr int ZS = 64 * AT + 1;
+    constexpr int CG = S1_NT / S1_IT;    // column groups: a thread holds row li of columns lj + CG*jj
+    constexpr int NPRE = S1_JT / CG;
     float *xs = smem;                    // [64 j][S1_XS]
     float *zs = smem + S1_JT * S1_XS;    // [64 j][ZS]: mode-1 result of the current column tile
     const int tid = threadIdx.x, lane = tid & 63;
@@ -58,7 +80,8 @@ __global__ __launch_bounds__(256) void k_stage1_mode12(const S1Params p)
     const int64_t k = blockIdx.x;
     const float *Xk = p.X + k * p.I * p.J;
     const int nit = (int)((p.I + S1_IT - 1) / S1_IT), njt = (int)((p.J + S1_JT - 1) / S1_JT);
-    const int li = tid & 127, lj = tid >> 7;   // this thread's element of the tile: row li, columns lj + 2*jj
+    const int li = tid & (S1_IT - 1);
+    const int lj = w / (S1_IT / 64);     // the same for the whole wave: tile addresses are wave-uniform + 4*li
 
     float acc2[AT][BR];
 #pragma unroll
@@ -66,75 +89,112 @@ __global__ __launch_bounds__(256) void k_stage1_mode12(const S1Params p)
 #pragma unroll
         for (int x = 0; x < BR; x++) acc2[at][x] = 0.0f;
 
-    float pre[32];
+    float pre[NPRE];
     auto gload = [&](int jt, int it) {
-        const int64_t i = (int64_t)it * S1_IT + li;
-        const float *src = Xk + i + p.I * ((int64_t)jt * S1_JT + lj);
-        const int64_t jleft = p.J - ((int64_t)jt * S1_JT + lj);   // columns lj + 2*jj with 2*jj < jleft exist
+        const int64_t i0 = (int64_t)it * S1_IT, j0 = (int64_t)jt * S1_JT + lj;
+        const float *src = Xk + i0 + p.I * j0;   // wave-uniform
+        const bool iok = i0 + li < p.I && !(p.abl & 2);
 #pragma unroll
-        for (int jj = 0; jj < 32; jj++)
-            pre[jj] = (i < p.I && 2 * jj < jleft) ? src[p.I * 2 * jj] : 0.0f;
+        for (int jj = 0; jj < NPRE; jj++)
+            pre[jj] = (iok && j0 + CG * jj < p.J) ? src[p.I * CG * jj + li] : 0.0f;
     };
     gload(0, 0);
+    const char *xl = (const char *)(xs + lane * S1_XS);
+    float *zl = zs + lane * ZS;
     for (int jt = 0; jt < njt; jt++) {
-        float acc1[AR];
-#pragma unroll
-        for (int x = 0; x < AR; x++) acc1[x] = 0.0f;
+        for (int t = tid; t < S1_JT * ZS; t += S1_NT) zs[t] = 0.0f;
         for (int it = 0; it < nit; it++) {
-            __syncthreads();   // the previous tile's readers are done
+            __syncthreads();   // the previous tile's readers are done (and zs is cleared)
 #pragma unroll
-            for (int jj = 0; jj < 32; jj++) xs[(2 * jj + lj) * S1_XS + li] = pre[jj];
+            for (int jj = 0; jj < NPRE; jj++) xs[(CG * jj + lj) * S1_XS + li] = pre[jj];
             __syncthreads();
             if (it + 1 < nit) gload(jt, it + 1);
             else if (jt + 1 < njt) gload(jt + 1, 0);
-            const int *tp = p.Utp + (int64_t)it * (p.A1 + 1);
-            const float *xl = xs + lane * S1_XS;
-#pragma unroll
-            for (int x = 0; x < AR; x++) {
-                const int a = w + 4 * x;
-                if (a < p.A1) {
-                    const int e1 = tp[a + 1];
-                    float s = acc1[x];
-                    for (int e = tp[a]; e < e1; e += 4) {
-                        const SEnt n0 = p.Uent[e], n1 = p.Uent[e + 1], n2 = p.Uent[e + 2], n3 = p.Uent[e + 3];
-                        s = fmaf(n0.v, xl[n0.c], s);
-                        s = fmaf(n1.v, xl[n1.c], s);
-                        s = fmaf(n2.v, xl[n2.c], s);
-                        s = fmaf(n3.v, xl[n3.c], s);
-                    }
-                    acc1[x] = s;
+            // mode 1: the wave's chunk stream, the next chunk requested before the current one is used
+            const S1_CONST int *ocp = as_const((const int *)p.Uoc) + 2 * (it * S1_NW + w);
+            const int nch = (p.abl & 1) ? 0 : ocp[1];
+            // Lane l holds words 4*(l&3) .. 4*(l&3)+3 of a chunk, so every quad of lanes has the whole chunk and a
+            // quad broadcast (folded into the consuming add / multiply-add as a DPP operand) hands any word to
+            // all lanes.  Chunks are requested two ahead.
+            const i32x4 *cpv = (const i32x4 *)(p.Uch + 16 * (int64_t)ocp[0]) + (lane & 3);
+            float s = 0.0f;
+            // acc += (word of quad lane q) * x in one instruction.  The compiler does not see inside the asm, so the two
+            // wait states a DPP read needs after a VALU write of the same register are put in by hand (S1_FMAC0
+            // opens each group; nothing writes the chunk registers between the members of a group)
+#define S1_BC(v, q) __builtin_amdgcn_update_dpp(0, v, (q) * 0x55, 0xf, 0xf, true)
+#define S1_FMAC(word, x, q) S1_FMAC_(word, x, q, "")
+#define S1_FMAC0(word, x, q) S1_FMAC_(word, x, q, "s_nop 1\n\t")
+#define S1_FMAC_(word, x, q, pre)                                                                                       \
+    asm(pre "v_fmac_f32_dpp %0, %1, %2 quad_perm:[" #q "," #q "," #q "," #q "] row_mask:0xf bank_mask:0xf bound_ctrl:1"    \
+        : "+v"(s) : "v"(word), "v"(x))
+            auto use = [&](const i32x4 &c) {
+                const int h = __builtin_amdgcn_readfirstlane(c.x);
+                // the row's running sum over the row tiles lives in zs; its read is issued with the tile reads so
+                // that its latency is not waited out separately (LDS atomic adds would not return anything either,
+                // but they take a cycle per lane)
+                const bool last = (h & CH_LAST) && !(p.abl & 8);
+                float *za = zl + ((h >> 9) & 0xff);
+                const float zold = last ? *za : 0.0f;
+                const float x0 = *(const float *)(xl + (S1_BC(c.x, 0) & 0x1ff)), x1 = *(const float *)(xl + S1_BC(c.z, 0));
+                const float x2 = *(const float *)(xl + S1_BC(c.x, 1)), x3 = *(const float *)(xl + S1_BC(c.z, 1));
+                if (!(h & CH_HALF)) {
+                    const float x4 = *(const float *)(xl + S1_BC(c.x, 2)), x5 = *(const float *)(xl + S1_BC(c.z, 2));
+                    const float x6 = *(const float *)(xl + S1_BC(c.x, 3)), x7 = *(const float *)(xl + S1_BC(c.z, 3));
+                    S1_FMAC0(c.y, x4, 2);
+                    S1_FMAC(c.w, x5, 2);
+                    S1_FMAC(c.y, x6, 3);
+                    S1_FMAC(c.w, x7, 3);
                 }
+                S1_FMAC0(c.y, x0, 0);
+                S1_FMAC(c.w, x1, 0);
+                S1_FMAC(c.y, x2, 1);
+                S1_FMAC(c.w, x3, 1);
+                if (last) {
+                    *za = s + zold;
+                    s = 0.0f;
+                }
+            };
+            // three chunk registers in rotation (no register copies), requests two chunks ahead
+            i32x4 cA = cpv[0], cB = cpv[4], cC;
+            for (int ch = 0; ch < nch; ch += 3) {
+                cC = cpv[4 * (ch + 2)];
+                use(cA);
+                if (ch + 1 >= nch) break;
+                cA = cpv[4 * (ch + 3)];
+                use(cB);
+                if (ch + 2 >= nch) break;
+                cB = cpv[4 * (ch + 4)];
+                use(cC);
             }
+#undef S1_BC
+#undef S1_FMAC
+#undef S1_FMAC0
+#undef S1_FMAC_
         }
-        // turn the 64 x A1 result: zs[j][a]
-#pragma unroll
-        for (int x = 0; x < AR; x++) {
-            const int a = w + 4 * x;
-            if (a < p.A1) zs[lane * ZS + a] = acc1[x];
-        }
-        __syncthreads();
-        const int *vp = p.Vtp + (int64_t)jt * (p.B1 + 1);
+        __syncthreads();   // zs complete
+        const S1_CONST int *vp = as_const(p.Vtp) + (int64_t)jt * (p.B1 + 1);
+        const S1_CONST int *vent = as_const((const int *)p.Vent);
 #pragma unroll
         for (int x = 0; x < BR; x++) {
-            const int b = w + 4 * x;
-            if (b < p.B1) {
+            const int b = w + S1_NW * x;
+            if (b < p.B1 && !(p.abl & 4)) {
                 const int e1 = vp[b + 1];
                 for (int e = vp[b]; e < e1; e += 4) {
 #pragma unroll
                     for (int u = 0; u < 4; u++) {
-                        const SEnt n = p.Vent[e + u];
+                        const SEnt n{vent[2 * (e + u)], __int_as_float(vent[2 * (e + u) + 1])};
 #pragma unroll
                         for (int at = 0; at < AT; at++) acc2[at][x] = fmaf(n.v, zs[n.c * ZS + 64 * at + lane], acc2[at][x]);
                     }
                 }
             }
         }
-        // the next column tile's first barrier separates these reads of zs from its next writes
+        __syncthreads();   // zs may be cleared again
     }
     float *Qk = p.Q + k * p.B1 * p.A1;
 #pragma unroll
     for (int x = 0; x < BR; x++) {
-        const int b = w + 4 * x;
+        const int b = w + S1_NW * x;
         if (b < p.B1) {
 #pragma unroll
             for (int at = 0; at < AT; at++) {
@@ -191,6 +251,60 @@ bool tile_csr(const exat_csr_t &m, int tile, std::vector<int> &tp, std::vector<S
     return true;
 }
 
+// Builds the mode-1 chunk streams: per row tile the rows are dealt to the waves longest first (each to the
+// wave with the least work so far), and every row's non-zeros inside the tile are cut into chunks of 8.
+bool chunk_csr(const exat_csr_t &m, std::vector<int2> &oc, std::vector<int> &ch)
+{
+    const int nt = (int)((m.cols + S1_IT - 1) / S1_IT);
+    std::vector<std::vector<SEnt>> rows((size_t)nt * m.rows);
+    for (int r = 0; r < m.rows; r++)
+        for (int64_t e = m.rowptr[r]; e < m.rowptr[r + 1]; e++) {
+            const int c = m.colidx[e];
+            rows[(size_t)(c / S1_IT) * m.rows + r].push_back(SEnt{c % S1_IT, m.val[e]});
+        }
+    oc.assign((size_t)nt * S1_NW, int2{0, 0});
+    ch.clear();
+    std::vector<int> order(m.rows);
+    for (int t = 0; t < nt; t++) {
+        const std::vector<SEnt> *tr = &rows[(size_t)t * m.rows];
+        for (int r = 0; r < m.rows; r++) order[r] = r;
+        std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return tr[a].size() > tr[b].size(); });
+        std::vector<int> mine[S1_NW];
+        size_t load[S1_NW] = {};
+        for (int r : order) {
+            if (tr[r].empty()) continue;
+            int best = 0;
+            for (int w = 1; w < S1_NW; w++)
+                if (load[w] < load[best]) best = w;
+            mine[best].push_back(r);
+            load[best] += (tr[r].size() + 7) / 8 * 8 + 2;
+        }
+        for (int w = 0; w < S1_NW; w++) {
+            const size_t first = ch.size() / 16;
+            for (int r : mine[w]) {
+                const auto &v = tr[r];
+                for (size_t e = 0; e < v.size(); e += 8) {
+                    const size_t n = std::min<size_t>(8, v.size() - e);
+                    int word[16];
+                    for (size_t u = 0; u < 8; u++) {
+                        word[2 * u] = u < n ? 4 * v[e + u].c : 0;
+                        const float val = u < n ? v[e + u].v : 0.0f;
+                        memcpy(&word[2 * u + 1], &val, 4);
+                    }
+                    word[0] |= r << 9;
+                    if (e + 8 >= v.size()) word[0] |= CH_LAST;
+                    if (n <= 4) word[0] |= CH_HALF;
+                    ch.insert(ch.end(), word, word + 16);
+                }
+            }
+            if (ch.size() / 16 > 0x7ffffff0u / 16) return false;
+            oc[(size_t)t * S1_NW + w] = int2{(int)first, (int)(ch.size() / 16 - first)};
+        }
+    }
+    ch.insert(ch.end(), 32, 0);   // the two chunks the last prefetches of the last stream read
+    return true;
+}
+
 int check_csr(const exat_csr_t *m, int64_t cols, int maxrows)
 {
     if (!m || !m->rowptr) return EXAT_ERR_NULL;
@@ -215,14 +329,14 @@ int upload(const std::vector<T> &h, T **d)
     return EXAT_OK;
 }
 
-template <int AR, int AT, int BR>
+template <int AT, int BR>
 int launch12(const S1Params &p, dim3 grid, size_t lds, hipStream_t st)
 {
     // more than 64 KiB of dynamic LDS has to be allowed per kernel (once per process is enough: the size is fixed by AT)
-    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_stage1_mode12<AR, AT, BR>),
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_stage1_mode12<AT, BR>),
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (attr != hipSuccess) return EXAT_ERR_HIP;
-    hipLaunchKernelGGL((k_stage1_mode12<AR, AT, BR>), grid, dim3(256), lds, st, p);
+    hipLaunchKernelGGL((k_stage1_mode12<AT, BR>), grid, dim3(S1_NT), lds, st, p);
     return hipGetLastError() == hipSuccess ? EXAT_OK : EXAT_ERR_HIP;
 }
 
@@ -231,8 +345,9 @@ int launch12(const S1Params &p, dim3 grid, size_t lds, hipStream_t st)
 struct exat_stage1_s {
     int64_t I, J, K;
     int A1, B1, C1;
-    int *Utp = nullptr, *Vtp = nullptr, *Wrp = nullptr, *Wci = nullptr;
-    SEnt *Uent = nullptr, *Vent = nullptr;
+    int2 *Uoc = nullptr;
+    int *Uch = nullptr, *Vtp = nullptr, *Wrp = nullptr, *Wci = nullptr;
+    SEnt *Vent = nullptr;
     float *Wval = nullptr, *Q = nullptr;
     bool timing = false, timing_valid = false;
     hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
@@ -243,7 +358,7 @@ extern "C" {
 int exat_stage1_destroy(exat_stage1_t s)
 {
     if (!s) return EXAT_OK;
-    void *bufs[] = {s->Utp, s->Vtp, s->Wrp, s->Wci, s->Uent, s->Vent, s->Wval, s->Q};
+    void *bufs[] = {s->Uoc, s->Uch, s->Vtp, s->Wrp, s->Wci, s->Vent, s->Wval, s->Q};
     for (void *b : bufs)
         if (b) (void)hipFree(b);
     for (auto &e : s->ev)
@@ -269,8 +384,10 @@ int exat_stage1_create(exat_stage1_t *out, int64_t I, int64_t J, int64_t K, cons
     try {
         std::vector<int> tp;
         std::vector<SEnt> ent;
-        if (!tile_csr(*U, S1_IT, tp, ent)) { exat_stage1_destroy(s); return EXAT_ERR_SHAPE; }
-        if ((rc = upload(tp, &s->Utp)) == EXAT_OK) rc = upload(ent, &s->Uent);
+        std::vector<int2> oc;
+        std::vector<int> ch;
+        if (!chunk_csr(*U, oc, ch)) { exat_stage1_destroy(s); return EXAT_ERR_SHAPE; }
+        if ((rc = upload(oc, &s->Uoc)) == EXAT_OK) rc = upload(ch, &s->Uch);
         if (rc == EXAT_OK) {
             if (!tile_csr(*V, S1_JT, tp, ent)) { exat_stage1_destroy(s); return EXAT_ERR_SHAPE; }
             if ((rc = upload(tp, &s->Vtp)) == EXAT_OK) rc = upload(ent, &s->Vent);
@@ -307,16 +424,17 @@ int exat_stage1_apply(exat_stage1_t s, const float *X, float *X1, void *stream)
     hipStream_t st = (hipStream_t)stream;
     S1Params p;
     p.X = X; p.I = s->I; p.J = s->J; p.K = s->K; p.A1 = s->A1; p.B1 = s->B1;
-    p.Utp = s->Utp; p.Uent = s->Uent; p.Vtp = s->Vtp; p.Vent = s->Vent; p.Q = s->Q;
+    p.abl = getenv("EXAT_S1_ABL") ? atoi(getenv("EXAT_S1_ABL")) : 0; p.Uoc = s->Uoc; p.Uch = s->Uch; p.Vtp = s->Vtp; p.Vent = s->Vent; p.Q = s->Q;
     const int AT = s->A1 > 64 ? 2 : 1;
     const size_t lds = (size_t)(S1_JT * S1_XS + S1_JT * (64 * AT + 1)) * sizeof(float);
     const dim3 grid((unsigned)s->K);
     if (s->timing && hipEventRecord(s->ev[0], st) != hipSuccess) return EXAT_ERR_HIP;
     int rc;
-    if (s->A1 <= 64 && s->B1 <= 64) rc = launch12<16, 1, 16>(p, grid, lds, st);
-    else if (s->A1 <= 64) rc = launch12<16, 1, 32>(p, grid, lds, st);
-    else if (s->B1 <= 64) rc = launch12<32, 2, 16>(p, grid, lds, st);
-    else rc = launch12<32, 2, 32>(p, grid, lds, st);
+    constexpr int BR1 = 64 / S1_NW, BR2 = 128 / S1_NW;
+    if (s->A1 <= 64 && s->B1 <= 64) rc = launch12<1, BR1>(p, grid, lds, st);
+    else if (s->A1 <= 64) rc = launch12<1, BR2>(p, grid, lds, st);
+    else if (s->B1 <= 64) rc = launch12<2, BR1>(p, grid, lds, st);
+    else rc = launch12<2, BR2>(p, grid, lds, st);
     if (rc != EXAT_OK) return rc;
     if (s->timing && hipEventRecord(s->ev[1], st) != hipSuccess) return EXAT_ERR_HIP;
     S1Mode3Params m;
