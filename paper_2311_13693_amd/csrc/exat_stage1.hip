@@ -20,7 +20,6 @@
 
 #include <algorithm>
 #include <cstdint>
-#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -29,10 +28,12 @@ namespace {
 
 constexpr int S1_IT = 128;     // rows i per tile
 constexpr int S1_JT = 64;      // columns j per tile (one per lane)
-constexpr int S1_NW = 8;       // waves per workgroup
+constexpr int S1_NW = 8;       // waves per workgroup (each owns a chunk stream per row tile)
 constexpr int S1_NT = 64 * S1_NW;
 constexpr int S1_XS = S1_IT + 1;  // LDS row stride of the X tile (odd: lanes reading one i of 64 columns hit 64 banks)
 constexpr int S1_MAXROWS = 128;   // largest A1 and B1
+constexpr int64_t S1_MAXI = (1 << 23) - 1;   // 64 tile columns of I floats must stay below 2 GiB (buffer offsets)
+constexpr int64_t S1_TARGET_WG = 768;   // three workgroups on each of the 256 compute units
 constexpr int64_t kMaxExtent1 = 2147483647LL - 64;
 
 struct SEnt { int c; float v; };  // one non-zero: column inside its tile, value
@@ -52,8 +53,8 @@ struct S1Params {
     const int *Uch;    // chunks, 16 ints each; two padding chunks at the very end
     const int *Vtp;    // [njt][B1+1] offsets into Vent; every (tile,row) range is a multiple of 4 entries
     const SEnt *Vent;
-    float *Q;          // [K][B1][A1]
-    int abl;
+    float *Q;          // [JS][K][B1][A1]: partial sums over the column range of each workgroup
+    int jt_per;        // column tiles per workgroup (blockIdx.y selects the range)
 };
 
 typedef int i32x4 __attribute__((ext_vector_type(4)));
@@ -67,11 +68,11 @@ __device__ inline const S1_CONST T *as_const(const T *p) { return (const S1_CONS
 
 // AT = 64-lane tiles of a (A1 <= 64*AT), BR = output rows b per wave in mode 2 (B1 <= S1_NW*BR)
 template <int AT, int BR>
-__global__ __launch_bounds__(S1_NT) void k_stage1_mode12(const S1Params p)
+__global__ __launch_bounds__(S1_NT, 6) void k_stage1_mode12(const S1Params p)
 {
     extern __shared__ float smem[];
     constexpr int ZS = 64 * AT + 1;
-    constexpr int CG = S1_NT / S1_IT;    // column groups: a thread holds row li of columns lj + CG*jj
+    constexpr int CG = S1_NT / S1_IT;     // column groups: a thread holds row li of columns lj + CG*jj
     constexpr int NPRE = S1_JT / CG;
     float *xs = smem;                    // [64 j][S1_XS]
     float *zs = smem + S1_JT * S1_XS;    // [64 j][ZS]: mode-1 result of the current column tile
@@ -90,29 +91,35 @@ __global__ __launch_bounds__(S1_NT) void k_stage1_mode12(const S1Params p)
         for (int x = 0; x < BR; x++) acc2[at][x] = 0.0f;
 
     float pre[NPRE];
+    // Tile loads go through a buffer descriptor rebuilt per tile (scalar work only): the address of a load is
+    // descriptor base (the wave's first column of the tile) + a per-load scalar offset (the column) + one
+    // per-lane offset (the row), so no per-load address lives in vector registers, and the descriptor's
+    // range check returns 0 for columns past J; lanes whose row is past I get an offset outside any range.
     auto gload = [&](int jt, int it) {
         const int64_t i0 = (int64_t)it * S1_IT, j0 = (int64_t)jt * S1_JT + lj;
-        const float *src = Xk + i0 + p.I * j0;   // wave-uniform
-        const bool iok = i0 + li < p.I && !(p.abl & 2);
+        const int64_t org = i0 + p.I * j0;
+        int64_t rem = (p.I * p.J - org) * 4;
+        rem = rem < 0 ? 0 : (rem > 0x7fffffff ? 0x7fffffff : rem);
+        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)(Xk + org), 0, (int)rem, 0x00020000);
+        const int voff = (i0 + li < p.I) ? 4 * li : (int)0x80000000;
 #pragma unroll
         for (int jj = 0; jj < NPRE; jj++)
-            pre[jj] = (iok && j0 + CG * jj < p.J) ? src[p.I * CG * jj + li] : 0.0f;
+            pre[jj] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsrc, voff, (int)(p.I * CG * jj * 4), 0));
     };
-    gload(0, 0);
+    gload(blockIdx.y * p.jt_per, 0);
     const char *xl = (const char *)(xs + lane * S1_XS);
     float *zl = zs + lane * ZS;
-    for (int jt = 0; jt < njt; jt++) {
+    const int jt0 = blockIdx.y * p.jt_per, jt1 = (jt0 + p.jt_per < njt) ? jt0 + p.jt_per : njt;
+    for (int jt = jt0; jt < jt1; jt++) {
         for (int t = tid; t < S1_JT * ZS; t += S1_NT) zs[t] = 0.0f;
         for (int it = 0; it < nit; it++) {
             __syncthreads();   // the previous tile's readers are done (and zs is cleared)
 #pragma unroll
             for (int jj = 0; jj < NPRE; jj++) xs[(CG * jj + lj) * S1_XS + li] = pre[jj];
             __syncthreads();
-            if (it + 1 < nit) gload(jt, it + 1);
-            else if (jt + 1 < njt) gload(jt + 1, 0);
             // mode 1: the wave's chunk stream, the next chunk requested before the current one is used
             const S1_CONST int *ocp = as_const((const int *)p.Uoc) + 2 * (it * S1_NW + w);
-            const int nch = (p.abl & 1) ? 0 : ocp[1];
+            const int nch = ocp[1];
             // Lane l holds words 4*(l&3) .. 4*(l&3)+3 of a chunk, so every quad of lanes has the whole chunk and a
             // quad broadcast (folded into the consuming add / multiply-add as a DPP operand) hands any word to
             // all lanes.  Chunks are requested two ahead.
@@ -132,7 +139,7 @@ __global__ __launch_bounds__(S1_NT) void k_stage1_mode12(const S1Params p)
                 // the row's running sum over the row tiles lives in zs; its read is issued with the tile reads so
                 // that its latency is not waited out separately (LDS atomic adds would not return anything either,
                 // but they take a cycle per lane)
-                const bool last = (h & CH_LAST) && !(p.abl & 8);
+                const bool last = (h & CH_LAST) != 0;
                 float *za = zl + ((h >> 9) & 0xff);
                 const float zold = last ? *za : 0.0f;
                 const float x0 = *(const float *)(xl + (S1_BC(c.x, 0) & 0x1ff)), x1 = *(const float *)(xl + S1_BC(c.z, 0));
@@ -170,6 +177,10 @@ __global__ __launch_bounds__(S1_NT) void k_stage1_mode12(const S1Params p)
 #undef S1_FMAC
 #undef S1_FMAC0
 #undef S1_FMAC_
+            // The next tile is requested only now: a wave's loads complete in issue order, so chunk requests queued
+            // behind a tile request would wait out the HBM latency.  Other workgroups on the CU cover this one's wait.
+            if (it + 1 < nit) gload(jt, it + 1);
+            else if (jt + 1 < jt1) gload(jt + 1, 0);
         }
         __syncthreads();   // zs complete
         const S1_CONST int *vp = as_const(p.Vtp) + (int64_t)jt * (p.B1 + 1);
@@ -177,7 +188,7 @@ __global__ __launch_bounds__(S1_NT) void k_stage1_mode12(const S1Params p)
 #pragma unroll
         for (int x = 0; x < BR; x++) {
             const int b = w + S1_NW * x;
-            if (b < p.B1 && !(p.abl & 4)) {
+            if (b < p.B1) {
                 const int e1 = vp[b + 1];
                 for (int e = vp[b]; e < e1; e += 4) {
 #pragma unroll
@@ -191,7 +202,7 @@ __global__ __launch_bounds__(S1_NT) void k_stage1_mode12(const S1Params p)
         }
         __syncthreads();   // zs may be cleared again
     }
-    float *Qk = p.Q + k * p.B1 * p.A1;
+    float *Qk = p.Q + ((int64_t)blockIdx.y * p.K + k) * p.B1 * p.A1;
 #pragma unroll
     for (int x = 0; x < BR; x++) {
         const int b = w + S1_NW * x;
@@ -206,7 +217,9 @@ __global__ __launch_bounds__(S1_NT) void k_stage1_mode12(const S1Params p)
 }
 
 struct S1Mode3Params {
-    const float *Q;   // [K][AB]
+    const float *Q;   // [JS][K][AB]
+    int JS;
+    int64_t K;
     const int *rp;    // [C1+1]
     const int *ci;
     const float *val;
@@ -221,7 +234,12 @@ __global__ __launch_bounds__(256) void k_stage1_mode3(const S1Mode3Params p)
     if (ab >= p.AB) return;
     const int e1 = p.rp[c + 1];
     float s = 0.0f;
-    for (int e = p.rp[c]; e < e1; e++) s = fmaf(p.val[e], p.Q[(int64_t)p.ci[e] * p.AB + ab], s);
+    for (int e = p.rp[c]; e < e1; e++) {
+        const float *q = p.Q + (int64_t)p.ci[e] * p.AB + ab;
+        float t = q[0];
+        for (int js = 1; js < p.JS; js++) t += q[js * p.K * p.AB];   // the column ranges, in order
+        s = fmaf(p.val[e], t, s);
+    }
     p.X1[ab + p.AB * c] = s;
 }
 
@@ -349,6 +367,7 @@ struct exat_stage1_s {
     int *Uch = nullptr, *Vtp = nullptr, *Wrp = nullptr, *Wci = nullptr;
     SEnt *Vent = nullptr;
     float *Wval = nullptr, *Q = nullptr;
+    int JS = 1, jt_per = 1;   // column ranges per slice (more workgroups when K alone would not fill the chip)
     bool timing = false, timing_valid = false;
     hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
 };
@@ -372,7 +391,7 @@ int exat_stage1_create(exat_stage1_t *out, int64_t I, int64_t J, int64_t K, cons
 {
     if (!out) return EXAT_ERR_NULL;
     *out = nullptr;
-    if (I < 1 || J < 1 || K < 1 || I > kMaxExtent1 || J > kMaxExtent1 || K > kMaxExtent1) return EXAT_ERR_SHAPE;
+    if (I < 1 || J < 1 || K < 1 || I > S1_MAXI || J > kMaxExtent1 || K > kMaxExtent1) return EXAT_ERR_SHAPE;
     int rc;
     if ((rc = check_csr(U, I, S1_MAXROWS)) != EXAT_OK) return rc;
     if ((rc = check_csr(V, J, S1_MAXROWS)) != EXAT_OK) return rc;
@@ -402,7 +421,14 @@ int exat_stage1_create(exat_stage1_t *out, int64_t I, int64_t J, int64_t K, cons
     } catch (const std::bad_alloc &) {
         rc = EXAT_ERR_ALLOC;
     }
-    if (rc == EXAT_OK && hipMalloc((void **)&s->Q, (size_t)K * s->A1 * s->B1 * sizeof(float)) != hipSuccess) {
+    {
+        const int64_t njt = (J + S1_JT - 1) / S1_JT;
+        int64_t want = (S1_TARGET_WG + K - 1) / K;
+        want = want < 1 ? 1 : (want > njt ? njt : want);
+        s->jt_per = (int)((njt + want - 1) / want);
+        s->JS = (int)((njt + s->jt_per - 1) / s->jt_per);
+    }
+    if (rc == EXAT_OK && hipMalloc((void **)&s->Q, (size_t)s->JS * K * s->A1 * s->B1 * sizeof(float)) != hipSuccess) {
         s->Q = nullptr;
         rc = EXAT_ERR_ALLOC;
     }
@@ -424,10 +450,10 @@ int exat_stage1_apply(exat_stage1_t s, const float *X, float *X1, void *stream)
     hipStream_t st = (hipStream_t)stream;
     S1Params p;
     p.X = X; p.I = s->I; p.J = s->J; p.K = s->K; p.A1 = s->A1; p.B1 = s->B1;
-    p.abl = getenv("EXAT_S1_ABL") ? atoi(getenv("EXAT_S1_ABL")) : 0; p.Uoc = s->Uoc; p.Uch = s->Uch; p.Vtp = s->Vtp; p.Vent = s->Vent; p.Q = s->Q;
+    p.Uoc = s->Uoc; p.Uch = s->Uch; p.Vtp = s->Vtp; p.Vent = s->Vent; p.Q = s->Q; p.jt_per = s->jt_per;
     const int AT = s->A1 > 64 ? 2 : 1;
     const size_t lds = (size_t)(S1_JT * S1_XS + S1_JT * (64 * AT + 1)) * sizeof(float);
-    const dim3 grid((unsigned)s->K);
+    const dim3 grid((unsigned)s->K, (unsigned)s->JS);
     if (s->timing && hipEventRecord(s->ev[0], st) != hipSuccess) return EXAT_ERR_HIP;
     int rc;
     constexpr int BR1 = 64 / S1_NW, BR2 = 128 / S1_NW;
@@ -438,7 +464,7 @@ int exat_stage1_apply(exat_stage1_t s, const float *X, float *X1, void *stream)
     if (rc != EXAT_OK) return rc;
     if (s->timing && hipEventRecord(s->ev[1], st) != hipSuccess) return EXAT_ERR_HIP;
     S1Mode3Params m;
-    m.Q = s->Q; m.rp = s->Wrp; m.ci = s->Wci; m.val = s->Wval; m.X1 = X1; m.AB = (int64_t)s->A1 * s->B1;
+    m.Q = s->Q; m.JS = s->JS; m.K = s->K; m.rp = s->Wrp; m.ci = s->Wci; m.val = s->Wval; m.X1 = X1; m.AB = (int64_t)s->A1 * s->B1;
     hipLaunchKernelGGL(k_stage1_mode3, dim3((unsigned)((m.AB + 255) / 256), (unsigned)s->C1), dim3(256), 0, st, m);
     if (hipGetLastError() != hipSuccess) return EXAT_ERR_HIP;
     if (s->timing) {
