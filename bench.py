@@ -41,7 +41,91 @@ def parse():
     ap.add_argument("--split", action="store_true",
                     help="fp32 materialised configurations only: run the contractions on the fp16 matrix cores with "
                          "two-piece operands (EXAT_F32_SPLIT) instead of fp32 MFMA; reported against the fp16 MFMA peak")
+    ap.add_argument("--two-stage", action="store_true",
+                    help="fp32 materialised configurations only: the two-stage compression of Sec. 4.4 (sparse first "
+                         "stage to 2L x 2M x 2N with 4 entries per column, then the dense replicas on its output); the "
+                         "roofline object then describes the HBM-bound first-stage kernel")
     return ap.parse_args()
+
+
+def two_stage(args):
+    """One step = sparse first stage over X (resident in HBM) + dense multi-replica second stage on its output."""
+    import torch
+    from paper_2311_13693_amd import exat, workloads as wl
+    cfg = wl.CONFIGS[args.config]
+    assert cfg.materialised and cfg.dtype == "f32", "--two-stage needs a materialised fp32 configuration"
+    ts = wl.TwoStage(cfg)
+    steps = args.steps if args.steps is not None else (5 if cfg.elements > 5e8 else 20)
+    warmup = args.warmup if args.warmup is not None else 3
+    torch.cuda.set_device(0)
+    A, B, C = wl.cp_factors(cfg)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+    gen = exat.make_gen(dev(A.T), dev(B.T), dev(C.T), cfg.seed, cfg.sigma)
+    whole = exat.make_desc(cfg.I, cfg.J, cfg.K, cfg.L, cfg.M, cfg.N, cfg.P, cfg.I, cfg.J, cfg.K, exat.EXAT_F32)
+    X = torch.empty(cfg.elements, dtype=torch.float32, device="cuda")
+    exat.gen_block(whole, gen, 0, 0, 0, X)
+    mats = wl.first_stage_matrices(ts)
+    U2, V2, W2 = wl.second_stage_matrices(ts)
+    st = exat.Stage1(cfg.I, cfg.J, cfg.K, *mats)
+    c2 = ts.second
+    plan = exat.Plan(exat.make_desc(c2.I, c2.J, c2.K, c2.L, c2.M, c2.N, c2.P, c2.dI, c2.dJ, c2.dK, exat.EXAT_F32))
+    plan.set_factors(dev(U2), dev(V2), dev(W2))
+    X1 = torch.empty(ts.A1 * ts.B1 * ts.C1, dtype=torch.float32, device="cuda")
+    Y = plan.new_y()
+
+    def step():
+        st.apply(X, X1)
+        plan.compress(X1, Y)
+    st.set_timing(True)
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    k12, k3 = [], []
+    e0.record()
+    for _ in range(steps):
+        step()
+        a, b = st.last_timing()
+        k12.append(a); k3.append(b)
+    e1.record()
+    torch.cuda.synchronize()
+    ms_step = e0.elapsed_time(e1) / steps
+    ms12, ms3 = float(np.mean(k12)), float(np.mean(k3))
+    achieved = 4.0 * cfg.elements / (ms12 * 1e-3) / 1e9    # algorithmic bytes: every fp32 element of X once
+    out = {
+        "metric": "input tensor elements compressed/sec + TTM TFLOP/s (% MFMA peak), 1 MI355X",
+        "value": cfg.elements / (ms_step * 1e-3), "unit": "elements/s",
+        "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "%s two-stage: %dx%dx%d f32 -> %dx%dx%d (sparse sign matrices, %d entries per column) -> "
+                               "P=%d replicas of %dx%dx%d" % (cfg.name, cfg.I, cfg.J, cfg.K, ts.A1, ts.B1, ts.C1,
+                                                              ts.nnz_per_col, cfg.P, cfg.L, cfg.M, cfg.N),
+                   "sigma": cfg.sigma},
+        "kernel_ms": {"stage1_mode12": ms12, "stage1_mode3": ms3},
+        "roofline": {"bound": "hbm", "kernel": "k_stage1_mode12", "achieved": achieved, "peak": 8000.0, "unit": "GB/s",
+                     "frac": achieved / 8000.0, "traffic": None},
+    }
+    if args.check:
+        import oracle
+        import gpu_util as gu
+        reps = [0, cfg.P - 1]
+        Xh = X.cpu().numpy().reshape((cfg.I, cfg.J, cfg.K), order="F")
+        Yo = oracle.two_stage(Xh, *mats, U2, V2, W2, cfg.P, replicas=reps)
+        out["check"] = {"replicas": reps, "rel_fro_vs_oracle": oracle.rel_fro(gu.y_to_numpy(Y, cfg)[..., reps], Yo)}
+    if not args.no_cpu_baseline:
+        import oracle
+        Xh = X.cpu().numpy().reshape((cfg.I, cfg.J, cfg.K), order="F")
+        nrep = 1 if cfg.elements > 5e8 else 2
+        t0 = time.perf_counter()
+        oracle.two_stage(Xh, *mats, U2, V2, W2, cfg.P, replicas=list(range(nrep)))
+        t = (time.perf_counter() - t0) * cfg.P / nrep
+        from threadpoolctl import threadpool_info
+        cores = max([int(lib.get("num_threads", 1)) for lib in threadpool_info()] + [1])   # numpy's BLAS pool
+        out["cpu_baseline"] = {"value": cfg.elements / t, "unit": "elements/s", "cores": cores, "kind": "oracle",
+                               "sample": "replicas 0..%d of %d over the whole tensor (numpy fp64), scaled to all replicas"
+                                         % (nrep - 1, cfg.P), "seconds_full": t, "extrapolated": nrep < cfg.P}
+    plan.close(); st.close()
+    print(json.dumps(out))
 
 
 def cpu_baseline(cfg, A, B, C, U, V, W, budget_s=15.0):
@@ -85,9 +169,11 @@ def main():
         print("bench.py: this build runs on ONE GPU only (no collectives are part of it); "
               "run with --gpus 1. Throughput at N GPUs is not measured.", file=sys.stderr)
         sys.exit(2)
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    if args.two_stage:
+        return two_stage(args)
     import torch
     from paper_2311_13693_amd import exat, workloads as wl
-    sys.path.insert(0, os.path.join(ROOT, "tests"))
     cfg = wl.CONFIGS[args.config]
     big = cfg.elements > 5e10
     steps = args.steps if args.steps is not None else (2 if big else (5 if cfg.elements > 5e8 else 20))

@@ -105,3 +105,32 @@ def test_two_stage_chain_matches_oracle():
     print("two-stage chain rel_fro=%.3e" % err, flush=True)
     assert err <= TOL
     plan.close(); st.close()
+
+
+@pytest.mark.parametrize("name,reps", [("cfg2", [0, 7, 15]), ("cfg3", [31])])
+def test_two_stage_at_benchmark_sizes(name, reps):
+    """The launch configuration `bench.py --two-stage` times: first stage compared element by element with
+    the oracle, the chain on sampled replicas."""
+    cfg = wl.CONFIGS[name]
+    ts = wl.TwoStage(cfg)
+    print("case", name, flush=True)
+    A, B, C = wl.cp_factors(cfg)
+    gen = gu.gen_of(cfg, A, B, C)
+    whole = exat.make_desc(cfg.I, cfg.J, cfg.K, cfg.L, cfg.M, cfg.N, cfg.P, cfg.I, cfg.J, cfg.K, exat.EXAT_F32)
+    Xd = torch.empty(cfg.elements, dtype=torch.float32, device="cuda")
+    exat.gen_block(whole, gen, 0, 0, 0, Xd)
+    mats = wl.first_stage_matrices(ts)
+    U2, V2, W2 = wl.second_stage_matrices(ts)
+    st = exat.Stage1(cfg.I, cfg.J, cfg.K, *mats)
+    plan = gu.plan_with_factors(ts.second, U2, V2, W2)
+    X1 = st.apply(Xd)
+    Y = plan.compress(X1)
+    torch.cuda.synchronize()
+    X = Xd.cpu().numpy().reshape((cfg.I, cfg.J, cfg.K), order="F")
+    ref1 = oracle.first_stage(X, *mats)
+    e1 = _rel(X1.cpu().numpy().astype(np.float64).reshape(st.dims, order="F"), ref1)
+    ref = oracle.two_stage(X, *mats, U2, V2, W2, cfg.P, replicas=reps)
+    e2 = oracle.rel_fro(gu.y_to_numpy(Y, cfg)[..., reps], ref)
+    print("  first stage rel_fro=%.3e, chain rel_fro=%.3e" % (e1, e2), flush=True)
+    assert e1 <= TOL and e2 <= TOL
+    plan.close(); st.close()
