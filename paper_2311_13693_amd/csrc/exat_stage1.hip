@@ -33,7 +33,6 @@ constexpr int S1_NT = 64 * S1_NW;
 constexpr int S1_XS = S1_IT + 1;  // LDS row stride of the X tile (odd: lanes reading one i of 64 columns hit 64 banks)
 constexpr int S1_MAXROWS = 128;   // largest A1 and B1
 constexpr int64_t S1_MAXI = (1 << 23) - 1;   // 64 tile columns of I floats must stay below 2 GiB (buffer offsets)
-constexpr int64_t S1_TARGET_WG = 768;   // three workgroups on each of the 256 compute units
 constexpr int64_t kMaxExtent1 = 2147483647LL - 64;
 
 struct SEnt { int c; float v; };  // one non-zero: column inside its tile, value
@@ -55,6 +54,7 @@ struct S1Params {
     const SEnt *Vent;
     float *Q;          // [JS][K][B1][A1]: partial sums over the column range of each workgroup
     int jt_per;        // column tiles per workgroup (blockIdx.y selects the range)
+    int64_t qstride;   // floats between the partial results of consecutive column ranges
 };
 
 typedef int i32x4 __attribute__((ext_vector_type(4)));
@@ -202,7 +202,7 @@ __global__ __launch_bounds__(S1_NT, 6) void k_stage1_mode12(const S1Params p)
         }
         __syncthreads();   // zs may be cleared again
     }
-    float *Qk = p.Q + ((int64_t)blockIdx.y * p.K + k) * p.B1 * p.A1;
+    float *Qk = p.Q + blockIdx.y * p.qstride + k * p.B1 * p.A1;
 #pragma unroll
     for (int x = 0; x < BR; x++) {
         const int b = w + S1_NW * x;
@@ -216,10 +216,22 @@ __global__ __launch_bounds__(S1_NT, 6) void k_stage1_mode12(const S1Params p)
     }
 }
 
+// Q[0][..] += Q[1][..] + ... + Q[JS-1][..] (the column ranges in order), four floats per thread; n4 = K*A1*B1/4
+// rounded up, the allocation is padded accordingly.
+__global__ __launch_bounds__(256) void k_stage1_sum_ranges(float *Q, int JS, int64_t stride, int64_t n4)
+{
+    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (t >= n4) return;
+    float4 a = ((const float4 *)Q)[t];
+    for (int js = 1; js < JS; js++) {
+        const float4 b = ((const float4 *)(Q + js * stride))[t];
+        a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
+    }
+    ((float4 *)Q)[t] = a;
+}
+
 struct S1Mode3Params {
-    const float *Q;   // [JS][K][AB]
-    int JS;
-    int64_t K;
+    const float *Q;   // [K][AB]
     const int *rp;    // [C1+1]
     const int *ci;
     const float *val;
@@ -233,13 +245,17 @@ __global__ __launch_bounds__(256) void k_stage1_mode3(const S1Mode3Params p)
     const int c = blockIdx.y;
     if (ab >= p.AB) return;
     const int e1 = p.rp[c + 1];
+    auto qsum = [&](int e) { return p.Q[(int64_t)p.ci[e] * p.AB + ab]; };
     float s = 0.0f;
-    for (int e = p.rp[c]; e < e1; e++) {
-        const float *q = p.Q + (int64_t)p.ci[e] * p.AB + ab;
-        float t = q[0];
-        for (int js = 1; js < p.JS; js++) t += q[js * p.K * p.AB];   // the column ranges, in order
-        s = fmaf(p.val[e], t, s);
+    int e = p.rp[c];
+    for (; e + 4 <= e1; e += 4) {   // four entries' loads in flight together; the sum keeps the stored order
+        const float t0 = qsum(e), t1 = qsum(e + 1), t2 = qsum(e + 2), t3 = qsum(e + 3);
+        s = fmaf(p.val[e], t0, s);
+        s = fmaf(p.val[e + 1], t1, s);
+        s = fmaf(p.val[e + 2], t2, s);
+        s = fmaf(p.val[e + 3], t3, s);
     }
+    for (; e < e1; e++) s = fmaf(p.val[e], qsum(e), s);
     p.X1[ab + p.AB * c] = s;
 }
 
@@ -372,6 +388,10 @@ struct exat_stage1_s {
     hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
 };
 
+namespace {
+inline int64_t qstride_of(const exat_stage1_s *s) { return ((int64_t)s->K * s->A1 * s->B1 + 3) / 4 * 4; }
+}  // namespace
+
 extern "C" {
 
 int exat_stage1_destroy(exat_stage1_t s)
@@ -422,13 +442,21 @@ int exat_stage1_create(exat_stage1_t *out, int64_t I, int64_t J, int64_t K, cons
         rc = EXAT_ERR_ALLOC;
     }
     {
+        // Column ranges per slice: the workgroups all take about the same time, so the kernel runs in
+        // ceil(workgroups / resident workgroups) rounds of ceil(njt / JS) column tiles each; take the smallest JS
+        // that minimises the product.
         const int64_t njt = (J + S1_JT - 1) / S1_JT;
-        int64_t want = (S1_TARGET_WG + K - 1) / K;
-        want = want < 1 ? 1 : (want > njt ? njt : want);
-        s->jt_per = (int)((njt + want - 1) / want);
+        const int64_t slots = 256 * (s->A1 > 64 ? 2 : 3);   // LDS allows 3 (A1 <= 64) or 2 workgroups per CU
+        int64_t best = 1, best_cost = -1;
+        for (int64_t js = 1; js <= njt && js <= 64; js++) {
+            const int64_t per = (njt + js - 1) / js, njs = (njt + per - 1) / per;
+            const int64_t cost = ((K * njs + slots - 1) / slots) * per;
+            if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = njs; }
+        }
+        s->jt_per = (int)((njt + best - 1) / best);
         s->JS = (int)((njt + s->jt_per - 1) / s->jt_per);
     }
-    if (rc == EXAT_OK && hipMalloc((void **)&s->Q, (size_t)s->JS * K * s->A1 * s->B1 * sizeof(float)) != hipSuccess) {
+    if (rc == EXAT_OK && hipMalloc((void **)&s->Q, (size_t)s->JS * qstride_of(s) * sizeof(float)) != hipSuccess) {
         s->Q = nullptr;
         rc = EXAT_ERR_ALLOC;
     }
@@ -450,7 +478,7 @@ int exat_stage1_apply(exat_stage1_t s, const float *X, float *X1, void *stream)
     hipStream_t st = (hipStream_t)stream;
     S1Params p;
     p.X = X; p.I = s->I; p.J = s->J; p.K = s->K; p.A1 = s->A1; p.B1 = s->B1;
-    p.Uoc = s->Uoc; p.Uch = s->Uch; p.Vtp = s->Vtp; p.Vent = s->Vent; p.Q = s->Q; p.jt_per = s->jt_per;
+    p.Uoc = s->Uoc; p.Uch = s->Uch; p.Vtp = s->Vtp; p.Vent = s->Vent; p.Q = s->Q; p.jt_per = s->jt_per; p.qstride = qstride_of(s);
     const int AT = s->A1 > 64 ? 2 : 1;
     const size_t lds = (size_t)(S1_JT * S1_XS + S1_JT * (64 * AT + 1)) * sizeof(float);
     const dim3 grid((unsigned)s->K, (unsigned)s->JS);
@@ -463,8 +491,13 @@ int exat_stage1_apply(exat_stage1_t s, const float *X, float *X1, void *stream)
     else rc = launch12<2, BR2>(p, grid, lds, st);
     if (rc != EXAT_OK) return rc;
     if (s->timing && hipEventRecord(s->ev[1], st) != hipSuccess) return EXAT_ERR_HIP;
+    if (s->JS > 1) {
+        const int64_t n4 = qstride_of(s) / 4;
+        hipLaunchKernelGGL(k_stage1_sum_ranges, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, st, s->Q, s->JS, qstride_of(s), n4);
+        if (hipGetLastError() != hipSuccess) return EXAT_ERR_HIP;
+    }
     S1Mode3Params m;
-    m.Q = s->Q; m.JS = s->JS; m.K = s->K; m.rp = s->Wrp; m.ci = s->Wci; m.val = s->Wval; m.X1 = X1; m.AB = (int64_t)s->A1 * s->B1;
+    m.Q = s->Q; m.rp = s->Wrp; m.ci = s->Wci; m.val = s->Wval; m.X1 = X1; m.AB = (int64_t)s->A1 * s->B1;
     hipLaunchKernelGGL(k_stage1_mode3, dim3((unsigned)((m.AB + 255) / 256), (unsigned)s->C1), dim3(256), 0, st, m);
     if (hipGetLastError() != hipSuccess) return EXAT_ERR_HIP;
     if (s->timing) {
