@@ -1,16 +1,15 @@
 // First stage of the two-stage compression (paper Sec. 4.4): X1 = X x1 U x2 V x3 W with sparse U, V, W
 // shared by all replicas.  Declarations and contracts in include/exat.h.
 //
-// The stage is bound by reading X once from HBM (4 bytes per element against 2*nnz_per_column flops), so the
-// kernels are organised around that stream and use no matrix cores:
-//   k_stage1_mode12  one workgroup per frontal slice k.  It walks the slice in 64-column x 128-row tiles that
-//                    go HBM -> registers -> LDS (each element once, the next tile's loads in flight while the
-//                    current one is used).  Mode 1: a lane owns a column j of the tile and a wave a set of
-//                    output rows a; for every non-zero (a, i) of U inside the tile the wave does one LDS read
-//                    and one FMA, the non-zero itself coming through the scalar cache (it is the same for all
-//                    lanes).  When the column tile's rows are finished the 64 x A1 result is turned through
-//                    LDS and mode 2 runs the same way with lanes along a.  The A1 x B1 slice result goes to
-//                    Q[k][b][a].
+// The stage reads X once from HBM (4 bytes per element against 2*nnz_per_column flops) and uses no matrix cores:
+//   k_stage1_mode12  one workgroup per (frontal slice k, range of column tiles).  It walks its part of the slice
+//                    in 64-column x 128-row tiles that go HBM -> registers -> LDS, each element once.  Mode 1: a
+//                    lane owns a column j of the tile; the non-zeros of U inside the row tile are dealt to the
+//                    waves row by row, as streams of 64-byte chunks (8 non-zeros of one output row a).  For every
+//                    non-zero the wave does one LDS read and one multiply-add; the row's sum over the row tiles
+//                    is kept in LDS.  When the column tile's rows are finished mode 2 runs over the 64 x A1 result
+//                    with lanes along a, and the A1 x B1 partial result of the column range goes to Q.
+//   k_stage1_sum_ranges  adds the partial results of the column ranges (only when a slice was split).
 //   k_stage1_mode3   X1[a,b,c] = sum_k W[c,k] Q[k][b][a], a thread per (a,b,c), the non-zeros of row c in
 //                    stored order.
 // Every sum has a fixed order, so results are bit-identical from run to run.
