@@ -21,7 +21,7 @@ PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}   # MI355X dense MFMA peaks
 # HBM-side bytes of one launch of the fused mode-1/2 kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE passes,
 # scaled by the same counters on a plain device copy (figures and commands: profiles/*_hbm_counters.txt).
 # Counter passes are separate runs, so this is a recorded value, not one measured by this script.
-TRAFFIC_BYTES = {"cfg2": 1.150e9}
+TRAFFIC_BYTES = {"cfg2": 1.150e9, "cfg2_two_stage": 5.633e8}
 
 
 def parse():
@@ -89,6 +89,11 @@ def two_stage(args):
         k12.append(a); k3.append(b)
     e1.record()
     torch.cuda.synchronize()
+    if args.calib_copy:
+        src = torch.ones(64 << 20, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
     ms_step = e0.elapsed_time(e1) / steps
     ms12, ms3 = float(np.mean(k12)), float(np.mean(k3))
     achieved = 4.0 * cfg.elements / (ms12 * 1e-3) / 1e9    # algorithmic bytes: every fp32 element of X once
@@ -103,7 +108,7 @@ def two_stage(args):
                    "sigma": cfg.sigma},
         "kernel_ms": {"stage1_mode12": ms12, "stage1_mode3": ms3},
         "roofline": {"bound": "hbm", "kernel": "k_stage1_mode12", "achieved": achieved, "peak": 8000.0, "unit": "GB/s",
-                     "frac": achieved / 8000.0, "traffic": None},
+                     "frac": achieved / 8000.0, "traffic": TRAFFIC_BYTES.get(cfg.name + "_two_stage")},
     }
     if args.check:
         import oracle
