@@ -134,3 +134,37 @@ def test_two_stage_at_benchmark_sizes(name, reps):
     print("  first stage rel_fro=%.3e, chain rel_fro=%.3e" % (e1, e2), flush=True)
     assert e1 <= TOL and e2 <= TOL
     plan.close(); st.close()
+
+
+def test_first_stage_degenerate_shapes():
+    """Single fibre / slice / row, an all-zero matrix, and a dense (every entry present) matrix whose per-wave
+    chunk streams are longer than anything the sparse ensemble produces."""
+    rng = np.random.default_rng(9)
+
+    def dense_csr(D):
+        rows, cols = D.shape
+        return (np.arange(rows + 1, dtype=np.int64) * cols, np.tile(np.arange(cols, dtype=np.int32), rows),
+                D.reshape(-1).astype(np.float32))
+
+    def zero_csr(rows):
+        return np.zeros(rows + 1, dtype=np.int64), np.zeros(0, dtype=np.int32), np.zeros(0, dtype=np.float32)
+    cases = [
+        (1, 1, 1, dense_csr(np.array([[2.0]])), dense_csr(np.array([[3.0]])), dense_csr(np.array([[5.0]]))),
+        (130, 1, 1, dense_csr(rng.standard_normal((3, 130))), dense_csr(np.array([[1.0], [2.0]])), dense_csr(np.array([[1.0]]))),
+        (40, 70, 3, zero_csr(4), dense_csr(rng.standard_normal((5, 70))), dense_csr(rng.standard_normal((2, 3)))),
+        (300, 90, 5, dense_csr(rng.standard_normal((128, 300))), dense_csr(rng.standard_normal((128, 90))),
+         dense_csr(rng.standard_normal((7, 5)))),
+    ]
+    for I, J, K, U, V, W in cases:
+        print("case", I, J, K, len(U[0]) - 1, len(V[0]) - 1, len(W[0]) - 1, flush=True)
+        X = _x(12, I, J, K)
+        ref = oracle.first_stage(X, U, V, W)
+        st = exat.Stage1(I, J, K, U, V, W)
+        got = st.apply(gu.to_dev_x(X))
+        torch.cuda.synchronize()
+        got = got.cpu().numpy().astype(np.float64).reshape(st.dims, order="F")
+        st.close()
+        if np.abs(ref).max() == 0:
+            assert (got == 0).all()
+        else:
+            assert _rel(got, ref) <= TOL
