@@ -133,6 +133,18 @@ int exat_compress_block(exat_plan_t plan, const void *Xblk, int32_t bi, int32_t 
  * Errors: NULL, STATE (no block submitted), HIP. */
 int exat_finalize(exat_plan_t plan, float *Y, void *stream);
 
+/* Block-streamed compression of a tensor that lives in HOST memory (Sec. 4.3 with the tensor outside the
+ * accelerator's memory): every block T^{bi,bj,bk} is copied into one of three device buffers the plan owns
+ * (allocated on first use, dI*dJ*dK elements each) on an internal copy stream and compressed on `stream` as by
+ * exat_compress_block, copies running ahead of the compute by up to two blocks; exat_finalize ends the pass.
+ * The blocks are taken in the fixed order bi fastest, bk slowest, so Y is bit-identical to the same sequence of
+ * exat_compress_block calls.  Xhost: host, column-major I x J x K in in_dtype; page-locked memory
+ * (hipHostMalloc) is needed for the copies to overlap the compute, pageable memory works but serialises.
+ * Asynchronous: returns when everything is enqueued; Xhost must stay valid until the work on `stream` has
+ * completed.  Must not be interleaved with a block sequence of the caller's on the same plan.
+ * Errors: NULL, STATE (factors not set, block sequence open), ALLOC, HIP. */
+int exat_compress_host(exat_plan_t plan, const void *Xhost, float *Y, void *stream);
+
 /* Compression of the synthetic tensor of exat_gen_t without ever materialising it: the
  * kernels generate each X tile on chip.  box == NULL means the whole tensor; otherwise
  * only the elements of X inside the box contribute (the merge of Fig. 2a over a sub-box).

@@ -42,6 +42,13 @@ struct exat_plan_s {
     int64_t nblocks = 0, ysize = 0;
     std::vector<unsigned char> submitted, slot_used;
     int64_t nsubmitted = 0;
+    // host-streamed compression: ring of device block buffers, a copy stream, and per buffer an event "copy done"
+    // (recorded on the copy stream) and an event "buffer consumed" (recorded on the compute stream)
+    static constexpr int kRing = 3;
+    void *ring[kRing] = {nullptr, nullptr, nullptr};
+    hipStream_t copy_stream = nullptr;
+    hipEvent_t ev_copied[kRing] = {nullptr, nullptr, nullptr}, ev_free[kRing] = {nullptr, nullptr, nullptr};
+    bool ring_used[kRing] = {false, false, false};
     // optional per-kernel timing
     bool timing = false, timing_valid = false;
     hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
@@ -395,6 +402,14 @@ int exat_plan_create(exat_plan_t *plan, const exat_desc_t *desc)
 
 int exat_plan_destroy(exat_plan_t pl)
 {
+    if (pl) {
+        for (int b = 0; b < exat_plan_s::kRing; b++) {
+            if (pl->ring[b]) (void)hipFree(pl->ring[b]);
+            if (pl->ev_copied[b]) (void)hipEventDestroy(pl->ev_copied[b]);
+            if (pl->ev_free[b]) (void)hipEventDestroy(pl->ev_free[b]);
+        }
+        if (pl->copy_stream) (void)hipStreamDestroy(pl->copy_stream);
+    }
     if (!pl) return EXAT_OK;
     (void)hipFree(pl->Upack); (void)hipFree(pl->Ufrag); (void)hipFree(pl->Vfrag);
     (void)hipFree(pl->Ufh); (void)hipFree(pl->Ufl); (void)hipFree(pl->Vfh); (void)hipFree(pl->Vfl); (void)hipFree(pl->Vpack); (void)hipFree(pl->Wpack); (void)hipFree(pl->Q);
@@ -527,6 +542,60 @@ int exat_finalize(exat_plan_t pl, float *Y, void *stream)
     std::fill(pl->slot_used.begin(), pl->slot_used.end(), 0);
     pl->nsubmitted = 0;
     return EXAT_OK;
+}
+
+int exat_compress_host(exat_plan_t pl, const void *Xhost, float *Y, void *stream)
+{
+    if (!pl || !Xhost || !Y) return EXAT_ERR_NULL;
+    if (!pl->factors_set) return EXAT_ERR_STATE;
+    if (pl->nsubmitted != 0) return EXAT_ERR_STATE;   // a block sequence of the caller's is open
+    const exat_desc_t &d = pl->d;
+    const size_t es = esize(d.in_dtype);
+    const size_t blk_bytes = (size_t)d.dI * d.dJ * d.dK * es;
+    hipStream_t st = (hipStream_t)stream;
+    if (!pl->copy_stream) {
+        // default priority: streams of different priorities are never mixed in this library
+        if (hipStreamCreateWithFlags(&pl->copy_stream, hipStreamNonBlocking) != hipSuccess) { pl->copy_stream = nullptr; return EXAT_ERR_HIP; }
+        for (int b = 0; b < exat_plan_s::kRing; b++) {
+            if (hipMalloc(&pl->ring[b], blk_bytes) != hipSuccess) { pl->ring[b] = nullptr; (void)hipGetLastError(); return EXAT_ERR_ALLOC; }
+            if (hipEventCreateWithFlags(&pl->ev_copied[b], hipEventDisableTiming) != hipSuccess ||
+                hipEventCreateWithFlags(&pl->ev_free[b], hipEventDisableTiming) != hipSuccess) return EXAT_ERR_HIP;
+        }
+    }
+    for (int b = 0; b < exat_plan_s::kRing; b++)
+        if (!pl->ring[b] || !pl->ev_copied[b] || !pl->ev_free[b]) return EXAT_ERR_ALLOC;   // an earlier set-up failed half way
+    const int nbi = (int)(d.I / d.dI), nbj = (int)(d.J / d.dJ), nbk = (int)(d.K / d.dK);
+    int64_t n = 0;
+    for (int bk = 0; bk < nbk; bk++)
+        for (int bj = 0; bj < nbj; bj++)
+            for (int bi = 0; bi < nbi; bi++, n++) {
+                const int b = (int)(n % exat_plan_s::kRing);
+                // the copy into buffer b may start once the block that used it last has been consumed
+                if (pl->ring_used[b] && hipStreamWaitEvent(pl->copy_stream, pl->ev_free[b], 0) != hipSuccess) return EXAT_ERR_HIP;
+                hipMemcpy3DParms cp;
+                memset(&cp, 0, sizeof(cp));
+                cp.srcPtr = make_hipPitchedPtr(const_cast<void *>(Xhost), (size_t)d.I * es, (size_t)d.I * es, (size_t)d.J);
+                cp.srcPos = make_hipPos((size_t)bi * d.dI * es, (size_t)bj * d.dJ, (size_t)bk * d.dK);
+                cp.dstPtr = make_hipPitchedPtr(pl->ring[b], (size_t)d.dI * es, (size_t)d.dI * es, (size_t)d.dJ);
+                cp.dstPos = make_hipPos(0, 0, 0);
+                cp.extent = make_hipExtent((size_t)d.dI * es, (size_t)d.dJ, (size_t)d.dK);
+                cp.kind = hipMemcpyHostToDevice;
+                if (hipMemcpy3DAsync(&cp, pl->copy_stream) != hipSuccess) return EXAT_ERR_HIP;
+                if (hipEventRecord(pl->ev_copied[b], pl->copy_stream) != hipSuccess) return EXAT_ERR_HIP;
+                if (hipStreamWaitEvent(st, pl->ev_copied[b], 0) != hipSuccess) return EXAT_ERR_HIP;
+                const int rc = exat_compress_block(pl, pl->ring[b], bi, bj, bk, stream);
+                if (rc != EXAT_OK) {
+                    // leave no half-finished block sequence behind
+                    hipLaunchKernelGGL(k_clear_flags, dim3(grid_for(pl->nslots)), dim3(256), 0, st, pl->used_dev, pl->nslots);
+                    std::fill(pl->submitted.begin(), pl->submitted.end(), 0);
+                    std::fill(pl->slot_used.begin(), pl->slot_used.end(), 0);
+                    pl->nsubmitted = 0;
+                    return rc;
+                }
+                if (hipEventRecord(pl->ev_free[b], st) != hipSuccess) return EXAT_ERR_HIP;
+                pl->ring_used[b] = true;
+            }
+    return exat_finalize(pl, Y, stream);
 }
 
 int exat_gen_block(const exat_desc_t *desc, const exat_gen_t *gen, int32_t bi, int32_t bj, int32_t bk, void *out, void *stream)

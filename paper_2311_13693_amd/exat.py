@@ -14,7 +14,7 @@ EXAT_F32, EXAT_BF16, EXAT_F32_SPLIT = 0, 1, 2
 OK, ERR_NULL, ERR_SHAPE, ERR_DTYPE, ERR_STATE, ERR_ALLOC, ERR_HIP = 0, -1, -2, -3, -4, -5, -6
 
 EXPORTS = ["exat_plan_create", "exat_plan_destroy", "exat_set_factors", "exat_compress",
-           "exat_compress_block", "exat_finalize", "exat_compress_gen", "exat_gen_block",
+           "exat_compress_block", "exat_finalize", "exat_compress_host", "exat_compress_gen", "exat_gen_block",
            "exat_plan_set_timing", "exat_plan_last_timing", "exat_plan_check_status",
            "exat_stage1_create", "exat_stage1_destroy", "exat_stage1_dims", "exat_stage1_apply",
            "exat_stage1_set_timing", "exat_stage1_last_timing", "exat_strerror"]
@@ -71,6 +71,7 @@ def lib():
         L.exat_compress.argtypes = [vp, vp, vp, vp]
         L.exat_compress_block.argtypes = [vp, vp, i32, i32, i32, vp]
         L.exat_finalize.argtypes = [vp, vp, vp]
+        L.exat_compress_host.argtypes = [vp, vp, vp, vp]
         L.exat_compress_gen.argtypes = [vp, ctypes.POINTER(Gen), ctypes.POINTER(Box), vp, vp]
         L.exat_gen_block.argtypes = [ctypes.POINTER(Desc), ctypes.POINTER(Gen), i32, i32, i32, vp, vp]
         L.exat_plan_set_timing.argtypes = [vp, ctypes.c_int]
@@ -193,6 +194,13 @@ class Plan:
     def finalize(self, Y=None, stream=None):
         Y = self.new_y() if Y is None else Y
         _check(lib().exat_finalize(self._h, _ptr(Y), _stream_handle(stream)))
+        return Y
+
+    def compress_host(self, Xhost, Y=None, stream=None):
+        """Xhost: CPU tensor (ideally pinned) holding the column-major I x J x K tensor; streamed block by block."""
+        assert not Xhost.is_cuda and Xhost.is_contiguous()
+        Y = self.new_y() if Y is None else Y
+        _check(lib().exat_compress_host(self._h, _ptr(Xhost), _ptr(Y), _stream_handle(stream)))
         return Y
 
     def compress_gen(self, gen, box=None, Y=None, stream=None):
