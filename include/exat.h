@@ -40,7 +40,7 @@ typedef struct exat_plan_s *exat_plan_t; /* opaque */
 typedef enum {
     EXAT_OK = 0,
     EXAT_ERR_NULL = -1,   /* a required pointer is NULL                                    */
-    EXAT_ERR_SHAPE = -2,  /* non-positive or too large extent, block does not divide the   */
+    EXAT_ERR_SHAPE = -2,  /* non-positive or too large extent, block edge larger than the   */
                           /* tensor, box not inside the tensor, ld too small               */
     EXAT_ERR_DTYPE = -3,  /* unknown in_dtype                                              */
     EXAT_ERR_STATE = -4,  /* factors not set, block submitted twice, finalize with nothing */
@@ -65,7 +65,8 @@ typedef enum { EXAT_F32 = 0, EXAT_BF16 = 1, EXAT_F32_SPLIT = 2 } exat_dtype_t;
 typedef struct {
     int64_t I, J, K;     /* X is I x J x K; each extent in [1, 2^31 - 64]                  */
     int32_t L, M, N, P;  /* each Y_p is L x M x N; P replicas; M <= 64; P*L < 2^24          */
-    int32_t dI, dJ, dK;  /* block edges; must divide I, J, K (Sec. 4.3)                     */
+    int32_t dI, dJ, dK;  /* block edges, 1 <= dI <= I etc. (Sec. 4.3 assumes they divide    */
+                         /* the extents; here the last block of an axis may be shorter)    */
     int32_t in_dtype;    /* exat_dtype_t                                                    */
 } exat_desc_t;
 
@@ -116,8 +117,9 @@ int exat_set_factors(exat_plan_t plan, const float *U, int64_t ldU, const float 
 int exat_compress(exat_plan_t plan, const void *X, float *Y, void *stream);
 
 /* Block-streamed compression (Sec. 4.3, Fig. 2a): compresses the block
- * T^{bi,bj,bk} = X(bi*dI:(bi+1)*dI, bj*dJ:.., bk*dK:..) given as its own column-major
- * dI x dJ x dK device array (in_dtype) with the matching column slices of U, V, W and
+ * T^{bi,bj,bk} = X(bi*dI:(bi+1)*dI, bj*dJ:.., bk*dK:..) (cut off at the tensor's edge when the block
+ * edges do not divide the extents; there are ceil(I/dI) x ceil(J/dJ) x ceil(K/dK) blocks) given as its own
+ * column-major device array of the block's actual extents (in_dtype) with the matching column slices of U, V, W and
  * adds the result to the plan's partial sums.  Xblk may be reused as soon as the work
  * enqueued on `stream` has completed.  Each block is accepted once (a second
  * submission returns STATE); exat_finalize merges the partials in a fixed order, so Y
@@ -153,8 +155,8 @@ int exat_compress_host(exat_plan_t plan, const void *Xhost, float *Y, void *stre
 int exat_compress_gen(exat_plan_t plan, const exat_gen_t *gen, const exat_box_t *box, float *Y,
                       void *stream);
 
-/* Writes block (bi,bj,bk) of the synthetic tensor into `out` (device, column-major
- * dI x dJ x dK, fp32 or bf16 according to desc->in_dtype): the same element function the
+/* Writes block (bi,bj,bk) of the synthetic tensor into `out` (device, column-major in the block's actual
+ * extents, dI x dJ x dK except at a ragged edge, fp32 or bf16 according to desc->in_dtype): the same element function the
  * fused kernels evaluate on chip.
  * Errors: NULL, SHAPE, DTYPE, HIP. */
 int exat_gen_block(const exat_desc_t *desc, const exat_gen_t *gen, int32_t bi, int32_t bj, int32_t bk,

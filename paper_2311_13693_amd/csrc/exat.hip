@@ -60,6 +60,9 @@ struct exat_plan_s {
 namespace {
 
 inline int64_t ceil_to(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
+inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
+// extent of block b along an axis of length n cut into pieces of d (the last piece may be shorter)
+inline int64_t blk_ext(int64_t n, int64_t d, int64_t b) { return (b + 1) * d <= n ? d : n - b * d; }
 inline size_t esize(int dt) { return dt == EXAT_BF16 ? 2 : 4; }
 
 int env_int(const char *name, int dflt)
@@ -90,7 +93,7 @@ int validate_desc(const exat_desc_t *d)
     if (d->L < 1 || d->M < 1 || d->N < 1 || d->P < 1 || d->M > 64) return EXAT_ERR_SHAPE;
     if ((int64_t)d->P * d->L >= (1 << 24) || (int64_t)d->P * d->N >= (1 << 24)) return EXAT_ERR_SHAPE;
     if (d->dI < 1 || d->dJ < 1 || d->dK < 1) return EXAT_ERR_SHAPE;
-    if (d->I % d->dI || d->J % d->dJ || d->K % d->dK) return EXAT_ERR_SHAPE;
+    if (d->dI > d->I || d->dJ > d->J || d->dK > d->K) return EXAT_ERR_SHAPE;
     return EXAT_OK;
 }
 
@@ -394,7 +397,7 @@ int exat_plan_create(exat_plan_t *plan, const exat_desc_t *desc)
         exat_plan_destroy(pl);
         return EXAT_ERR_ALLOC;
     }
-    pl->nblocks = (desc->I / desc->dI) * (desc->J / desc->dJ) * (desc->K / desc->dK);
+    pl->nblocks = cdiv(desc->I, desc->dI) * cdiv(desc->J, desc->dJ) * cdiv(desc->K, desc->dK);
     pl->ysize = (int64_t)desc->P * desc->L * desc->M * desc->N;
     *plan = pl;
     return EXAT_OK;
@@ -488,7 +491,7 @@ int exat_compress_block(exat_plan_t pl, const void *Xblk, int32_t bi, int32_t bj
     if (!pl || !Xblk) return EXAT_ERR_NULL;
     if (!pl->factors_set) return EXAT_ERR_STATE;
     const exat_desc_t &d = pl->d;
-    const int64_t nbi = d.I / d.dI, nbj = d.J / d.dJ, nbk = d.K / d.dK;
+    const int64_t nbi = cdiv(d.I, d.dI), nbj = cdiv(d.J, d.dJ), nbk = cdiv(d.K, d.dK);
     if (bi < 0 || bj < 0 || bk < 0 || bi >= nbi || bj >= nbj || bk >= nbk) return EXAT_ERR_SHAPE;
     hipStream_t st = (hipStream_t)stream;
     if (!pl->slots) {
@@ -513,11 +516,12 @@ int exat_compress_block(exat_plan_t pl, const void *Xblk, int32_t bi, int32_t bj
     const int slot = (int)(blk % pl->nslots);
     Mode12Params mp;
     memset(&mp, 0, sizeof(mp));
-    mp.X = Xblk; mp.x_sj = d.dI; mp.x_sk = (int64_t)d.dI * d.dJ;
+    const int64_t di = blk_ext(d.I, d.dI, bi), dj = blk_ext(d.J, d.dJ, bj), dk = blk_ext(d.K, d.dK, bk);
+    mp.X = Xblk; mp.x_sj = di; mp.x_sk = di * dj;
     mp.xo_i = (int64_t)bi * d.dI; mp.xo_j = (int64_t)bj * d.dJ; mp.xo_k = (int64_t)bk * d.dK;
     const int e16 = 16 / (int)esize(d.in_dtype);
-    mp.x_vec = (d.dI % e16 == 0) && (mp.xo_i % e16 == 0) && (((uintptr_t)Xblk & 15) == 0);
-    mp.i0 = mp.xo_i; mp.i1 = mp.xo_i + d.dI; mp.j0 = mp.xo_j; mp.j1 = mp.xo_j + d.dJ; mp.k0 = mp.xo_k; mp.k1 = mp.xo_k + d.dK;
+    mp.x_vec = (di % e16 == 0) && (mp.xo_i % e16 == 0) && (((uintptr_t)Xblk & 15) == 0);
+    mp.i0 = mp.xo_i; mp.i1 = mp.xo_i + di; mp.j0 = mp.xo_j; mp.j1 = mp.xo_j + dj; mp.k0 = mp.xo_k; mp.k1 = mp.xo_k + dk;
     int rc = run_chain(pl, mp, false, pl->slots + (int64_t)slot * pl->ysize, pl->slot_used[(size_t)slot] ? 1 : 0, st);
     if (rc != EXAT_OK) return rc;
     if (!pl->slot_used[(size_t)slot]) {
@@ -564,7 +568,7 @@ int exat_compress_host(exat_plan_t pl, const void *Xhost, float *Y, void *stream
     }
     for (int b = 0; b < exat_plan_s::kRing; b++)
         if (!pl->ring[b] || !pl->ev_copied[b] || !pl->ev_free[b]) return EXAT_ERR_ALLOC;   // an earlier set-up failed half way
-    const int nbi = (int)(d.I / d.dI), nbj = (int)(d.J / d.dJ), nbk = (int)(d.K / d.dK);
+    const int nbi = (int)cdiv(d.I, d.dI), nbj = (int)cdiv(d.J, d.dJ), nbk = (int)cdiv(d.K, d.dK);
     int64_t n = 0;
     for (int bk = 0; bk < nbk; bk++)
         for (int bj = 0; bj < nbj; bj++)
@@ -576,9 +580,10 @@ int exat_compress_host(exat_plan_t pl, const void *Xhost, float *Y, void *stream
                 memset(&cp, 0, sizeof(cp));
                 cp.srcPtr = make_hipPitchedPtr(const_cast<void *>(Xhost), (size_t)d.I * es, (size_t)d.I * es, (size_t)d.J);
                 cp.srcPos = make_hipPos((size_t)bi * d.dI * es, (size_t)bj * d.dJ, (size_t)bk * d.dK);
-                cp.dstPtr = make_hipPitchedPtr(pl->ring[b], (size_t)d.dI * es, (size_t)d.dI * es, (size_t)d.dJ);
+                const size_t di = (size_t)blk_ext(d.I, d.dI, bi), dj = (size_t)blk_ext(d.J, d.dJ, bj), dk = (size_t)blk_ext(d.K, d.dK, bk);
+                cp.dstPtr = make_hipPitchedPtr(pl->ring[b], di * es, di * es, dj);
                 cp.dstPos = make_hipPos(0, 0, 0);
-                cp.extent = make_hipExtent((size_t)d.dI * es, (size_t)d.dJ, (size_t)d.dK);
+                cp.extent = make_hipExtent(di * es, dj, dk);
                 cp.kind = hipMemcpyHostToDevice;
                 if (hipMemcpy3DAsync(&cp, pl->copy_stream) != hipSuccess) return EXAT_ERR_HIP;
                 if (hipEventRecord(pl->ev_copied[b], pl->copy_stream) != hipSuccess) return EXAT_ERR_HIP;
@@ -606,16 +611,16 @@ int exat_gen_block(const exat_desc_t *desc, const exat_gen_t *gen, int32_t bi, i
     if (rc != EXAT_OK) return rc;
     if (!out) return EXAT_ERR_NULL;
     const exat_desc_t &d = *desc;
-    if (bi < 0 || bj < 0 || bk < 0 || bi >= d.I / d.dI || bj >= d.J / d.dJ || bk >= d.K / d.dK) return EXAT_ERR_SHAPE;
+    if (bi < 0 || bj < 0 || bk < 0 || bi >= cdiv(d.I, d.dI) || bj >= cdiv(d.J, d.dJ) || bk >= cdiv(d.K, d.dK)) return EXAT_ERR_SHAPE;
     GenParams gp;
     gp.A = gen->A; gp.B = gen->B; gp.C = gen->C; gp.ldA = d.I; gp.ldB = d.J; gp.ldC = d.K; gp.R = gen->R;
     gp.skey = seed_key(gen->seed);
     gp.amp2_ln2 = amp2_ln2_of(gen->sigma);
-    gp.i0 = (int64_t)bi * d.dI; gp.i1 = gp.i0 + d.dI;
-    gp.j0 = (int64_t)bj * d.dJ; gp.j1 = gp.j0 + d.dJ;
-    gp.k0 = (int64_t)bk * d.dK; gp.k1 = gp.k0 + d.dK;
+    gp.i0 = (int64_t)bi * d.dI; gp.i1 = gp.i0 + blk_ext(d.I, d.dI, bi);
+    gp.j0 = (int64_t)bj * d.dJ; gp.j1 = gp.j0 + blk_ext(d.J, d.dJ, bj);
+    gp.k0 = (int64_t)bk * d.dK; gp.k1 = gp.k0 + blk_ext(d.K, d.dK, bk);
     const int64_t nq = ((gp.i1 - 1) >> 2) - (gp.i0 >> 2) + 1;
-    const int64_t n = nq * d.dJ * d.dK;
+    const int64_t n = nq * (gp.j1 - gp.j0) * (gp.k1 - gp.k0);
     hipStream_t st = (hipStream_t)stream;
     if (d.in_dtype == EXAT_BF16)
         hipLaunchKernelGGL(k_gen_box<__bf16>, dim3(grid_for(n)), dim3(256), 0, st, gp, (__bf16 *)out);

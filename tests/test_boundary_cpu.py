@@ -42,7 +42,7 @@ def _desc(**kw):
 @pytest.mark.parametrize("kw,code", [
     (dict(I=0), exat.ERR_SHAPE), (dict(J=-3), exat.ERR_SHAPE), (dict(K=2 ** 31), exat.ERR_SHAPE),
     (dict(L=0), exat.ERR_SHAPE), (dict(M=65), exat.ERR_SHAPE), (dict(P=0), exat.ERR_SHAPE),
-    (dict(dI=3), exat.ERR_SHAPE), (dict(dJ=0), exat.ERR_SHAPE), (dict(dK=5), exat.ERR_SHAPE),
+    (dict(dI=9), exat.ERR_SHAPE), (dict(dJ=0), exat.ERR_SHAPE), (dict(dK=16), exat.ERR_SHAPE),
     (dict(in_dtype=7), exat.ERR_DTYPE), (dict(P=2 ** 20, L=64), exat.ERR_SHAPE),
 ])
 def test_plan_create_rejects_bad_descriptors(kw, code):

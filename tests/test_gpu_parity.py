@@ -1,6 +1,7 @@
 """GPU parity: the HIP path through the C ABI against the CPU oracle, element by element / per
 replica on the same seeded inputs.  Tolerances (relative Frobenius error per replica, the
 benchmark contract): 1e-5 on fp32 paths, 2e-2 on bf16-input/fp32-accumulate paths."""
+import ctypes
 import os
 import sys
 
@@ -446,4 +447,43 @@ def test_host_streamed_matches_block_sequence_and_oracle(case):
     err = oracle.rel_fro(gu.y_to_numpy(Y1, cfg), oracle.comp_multi(np.asfortranarray(Xo), U, V, W, cfg.P))
     print("  rel_fro=%.3e" % err, flush=True)
     assert err <= (2e-2 if bf else 1e-5)      # bf16: U, V, W are rounded inside the plan as well
+    plan.close()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_ragged_blocks(dtype):
+    """Block edges that do not divide the extents: the last block of an axis is shorter.  Blocks through
+    exat_gen_block / exat_compress_block, the same tensor through exat_compress_host and in one shot."""
+    cfg = wl.small(I=24, J=20, K=28, dI=10, dJ=8, dK=9, dtype=dtype)     # blocks 10,10,4 x 8,8,4 x 9,9,9,1
+    print("case ragged", dtype, flush=True)
+    A, B, C = wl.cp_factors(cfg)
+    U, V, W = wl.compression_matrices(cfg)
+    bf = dtype == "bf16"
+    tdt = torch.bfloat16 if bf else torch.float32
+    plan = gu.plan_with_factors(cfg, U, V, W)
+    desc, gen = gu.desc_of(cfg), gu.gen_of(cfg, A, B, C)
+    cuts = lambda n, d: [(o, min(n, o + d)) for o in range(0, n, d)]
+    for bk, (k0, k1) in enumerate(cuts(cfg.K, cfg.dK)):
+        for bj, (j0, j1) in enumerate(cuts(cfg.J, cfg.dJ)):
+            for bi, (i0, i1) in enumerate(cuts(cfg.I, cfg.dI)):
+                blk = torch.empty((i1 - i0) * (j1 - j0) * (k1 - k0), dtype=tdt, device="cuda")
+                exat.gen_block(desc, gen, bi, bj, bk, blk)
+                ref = oracle.gen_box(A, B, C, cfg.seed, cfg.sigma, (i0, i1, j0, j1, k0, k1), to_bf16=bf)
+                got = blk.float().cpu().numpy().reshape(ref.shape, order="F")
+                assert np.abs(got - ref).max() <= (0.05 if bf else 2e-6 * (1 + np.abs(ref).max()))
+                plan.compress_block(blk, bi, bj, bk)
+    Yb = plan.finalize().clone()
+    X = oracle.gen_box(A, B, C, cfg.seed, cfg.sigma, to_bf16=bf)
+    Xflat = torch.from_numpy(np.ascontiguousarray(X.reshape(-1, order="F"))).to(tdt)
+    Yh = plan.compress_host(Xflat.pin_memory()).clone()
+    Y1 = plan.compress(Xflat.cuda()).clone()
+    torch.cuda.synchronize()
+    Yo = oracle.comp_multi(X, U, V, W, cfg.P)
+    tol = 2e-2 if bf else 1e-5
+    for name, Y in (("blocks", Yb), ("host", Yh), ("one shot", Y1)):
+        err = oracle.rel_fro(gu.y_to_numpy(Y, cfg), Yo)
+        print("  %s rel_fro=%.3e" % (name, err), flush=True)
+        assert err <= tol
+    L = exat.lib()
+    assert L.exat_compress_block(plan._h, ctypes.c_void_p(Xflat.cuda().data_ptr()), 3, 0, 0, None) == exat.ERR_SHAPE   # 3 blocks along i
     plan.close()
