@@ -334,10 +334,14 @@ int run_chain(exat_plan_s *pl, Mode12Params mp, bool generated, float *Yout, int
     m3.K = pl->d.K; m3.k0 = mp.k0; m3.k1 = mp.k1; m3.accumulate = accumulate;
     const int64_t ntile = ((int64_t)pl->PL * pl->Mpad + 31) / 32;
     dim3 grid((unsigned)ntile, (unsigned)((pl->Npad + 63) / 64));
-    if (pl->Npad % 64 == 0) hipLaunchKernelGGL(k_mode3<2>, grid, dim3(64 * M3_WAVES), 0, st, m3);
-    else {  // 32-column tiles, so that no launch carries an idle second tile
+    const bool longk = (m3.k1 - m3.k0) > 512LL * M3_WAVES - 8;   // a wave's slab (rounded up to even) may exceed 512
+    if (pl->Npad % 64 == 0) {
+        if (longk) hipLaunchKernelGGL((k_mode3<2, true>), grid, dim3(64 * M3_WAVES), 0, st, m3);
+        else hipLaunchKernelGGL((k_mode3<2, false>), grid, dim3(64 * M3_WAVES), 0, st, m3);
+    } else {  // 32-column tiles, so that no launch carries an idle second tile
         grid.y = (unsigned)(pl->Npad / 32);
-        hipLaunchKernelGGL(k_mode3<1>, grid, dim3(64 * M3_WAVES), 0, st, m3);
+        if (longk) hipLaunchKernelGGL((k_mode3<1, true>), grid, dim3(64 * M3_WAVES), 0, st, m3);
+        else hipLaunchKernelGGL((k_mode3<1, false>), grid, dim3(64 * M3_WAVES), 0, st, m3);
     }
     if (hipGetLastError() != hipSuccess) return EXAT_ERR_HIP;
     if (pl->timing) {

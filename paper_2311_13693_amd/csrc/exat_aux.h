@@ -66,8 +66,11 @@ struct Mode3Params {
 // sums in wave order, which keeps the result independent of timing.
 constexpr int M3_WAVES = 4;
 
-template <int NT>  // NT = 32-column tiles of n per workgroup (1 or 2)
-__global__ __launch_bounds__(64 * M3_WAVES) void k_mode3(const Mode3Params p)
+// NT = 32-column tiles of n per workgroup (1 or 2).  LONGK: a wave's slab of k may exceed KFLUSH values, so the
+// fp32 MFMA accumulators are flushed into fp64 sums every KFLUSH values; without it the accumulators themselves
+// are the slab's result and no fp64 registers are alive during the loop.
+template <int NT, bool LONGK>
+__global__ __launch_bounds__(64 * M3_WAVES, LONGK ? 1 : 2) void k_mode3(const Mode3Params p)
 {
     constexpr int KFLUSH = 512;
     __shared__ float part[M3_WAVES - 1][NT][16][64];
@@ -84,18 +87,17 @@ __global__ __launch_bounds__(64 * M3_WAVES) void k_mode3(const Mode3Params p)
     const int64_t nk = (kbeg >= nkall) ? 0 : ((kbeg + slab < nkall) ? slab : nkall - kbeg);
     const float *qp = p.Q + kbeg * qs + pos0 + l32;                                    // + kk*qs
     const float *wp = p.W + ((int64_t)pr * p.K + p.k0 + kbeg) * p.Npad + n0 + l32;     // + kk*Npad (+32 for tile 1)
-    double tot[NT][16];
+    double totl[LONGK ? NT : 1][16];   // LONGK only
+    f32x16 acc[NT];
 #pragma unroll
     for (int t = 0; t < NT; t++)
 #pragma unroll
-        for (int e = 0; e < 16; e++) tot[t][e] = 0.0;
-    for (int64_t kc = 0; kc < nk; kc += KFLUSH) {
-        f32x16 acc[NT];
-#pragma unroll
-        for (int t = 0; t < NT; t++)
-#pragma unroll
-            for (int e = 0; e < 16; e++) acc[t][e] = 0.0f;
-        const int64_t kend = (kc + KFLUSH < nk) ? kc + KFLUSH : nk;
+        for (int e = 0; e < 16; e++) {
+            acc[t][e] = 0.0f;
+            if (LONGK) totl[t][e] = 0.0;
+        }
+    for (int64_t kc = 0; kc < nk; kc += LONGK ? KFLUSH : nk) {
+        const int64_t kend = (LONGK && kc + KFLUSH < nk) ? kc + KFLUSH : nk;
         // 16 values of k per batch, two register sets: the loads of the next batch are issued before the MFMAs
         // of the current one (the kernel runs at well under one wave per SIMD, so nothing else hides the latency)
         constexpr int KB = 16, NS = KB / 2;
@@ -126,11 +128,21 @@ __global__ __launch_bounds__(64 * M3_WAVES) void k_mode3(const Mode3Params p)
             __builtin_amdgcn_sched_barrier(0);
             mma_batch(a1, b01, b11);
         }
+        if (LONGK) {
 #pragma unroll
-        for (int t = 0; t < NT; t++)
+            for (int t = 0; t < NT; t++)
 #pragma unroll
-            for (int e = 0; e < 16; e++) tot[t][e] += (double)acc[t][e];
+                for (int e = 0; e < 16; e++) {
+                    totl[t][e] += (double)acc[t][e];
+                    acc[t][e] = 0.0f;
+                }
+        }
     }
+    double tot[NT][16];
+#pragma unroll
+    for (int t = 0; t < NT; t++)
+#pragma unroll
+        for (int e = 0; e < 16; e++) tot[t][e] = LONGK ? totl[t][e] : (double)acc[t][e];
     if (wave > 0) {
 #pragma unroll
         for (int t = 0; t < NT; t++)
