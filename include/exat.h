@@ -219,6 +219,13 @@ int exat_stage1_dims(exat_stage1_t s, int32_t *A1, int32_t *B1, int32_t *C1);
  * (they share its intermediate).  Errors: NULL, HIP. */
 int exat_stage1_apply(exat_stage1_t s, const float *X, float *X1, void *stream);
 
+/* The same for a tensor in HOST memory: slabs of frontal slices (contiguous in a column-major tensor, about
+ * 128 MiB each) are copied into three device buffers the operator owns (allocated on first use) on an internal
+ * copy stream, up to two slabs ahead of the kernels on `stream`.  Same result as exat_stage1_apply, bit for
+ * bit.  Page-locked memory is needed for the copies to overlap the kernels.  Asynchronous; Xhost must stay
+ * valid until the work on `stream` has completed.  Errors: NULL, ALLOC, HIP. */
+int exat_stage1_apply_host(exat_stage1_t s, const float *Xhost, float *X1, void *stream);
+
 /* Measurement aid, as exat_plan_set_timing / exat_plan_last_timing: durations of the fused mode-1/2
  * kernel and of the mode-3 kernel of the most recent exat_stage1_apply. */
 int exat_stage1_set_timing(exat_stage1_t s, int enable);

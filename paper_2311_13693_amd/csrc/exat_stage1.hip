@@ -19,6 +19,7 @@
 
 #include <algorithm>
 #include <cstdint>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -53,6 +54,7 @@ struct S1Params {
     const SEnt *Vent;
     float *Q;          // [JS][K][B1][A1]: partial sums over the column range of each workgroup
     int jt_per;        // column tiles per workgroup (blockIdx.y selects the range)
+    int64_t k0;        // slice index of X[0] (X may be a slab of slices of the tensor): Q is indexed by k0 + blockIdx.x
     int64_t qstride;   // floats between the partial results of consecutive column ranges
 };
 
@@ -201,7 +203,7 @@ __global__ __launch_bounds__(S1_NT, 6) void k_stage1_mode12(const S1Params p)
         }
         __syncthreads();   // zs may be cleared again
     }
-    float *Qk = p.Q + blockIdx.y * p.qstride + k * p.B1 * p.A1;
+    float *Qk = p.Q + blockIdx.y * p.qstride + (p.k0 + k) * p.B1 * p.A1;
 #pragma unroll
     for (int x = 0; x < BR; x++) {
         const int b = w + S1_NW * x;
@@ -385,6 +387,14 @@ struct exat_stage1_s {
     int JS = 1, jt_per = 1;   // column ranges per slice (more workgroups when K alone would not fill the chip)
     bool timing = false, timing_valid = false;
     hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
+    // host-streamed application: ring of device buffers holding slabs of frontal slices, a copy stream, and per
+    // buffer the events "copied" (copy stream) and "consumed" (compute stream)
+    static constexpr int kRing = 3;
+    float *ring[kRing] = {nullptr, nullptr, nullptr};
+    int64_t slab = 0;   // slices per slab
+    hipStream_t copy_stream = nullptr;
+    hipEvent_t ev_copied[kRing] = {nullptr, nullptr, nullptr}, ev_free[kRing] = {nullptr, nullptr, nullptr};
+    bool ring_used[kRing] = {false, false, false};
 };
 
 namespace {
@@ -401,6 +411,12 @@ int exat_stage1_destroy(exat_stage1_t s)
         if (b) (void)hipFree(b);
     for (auto &e : s->ev)
         if (e) (void)hipEventDestroy(e);
+    for (int b = 0; b < exat_stage1_s::kRing; b++) {
+        if (s->ring[b]) (void)hipFree(s->ring[b]);
+        if (s->ev_copied[b]) (void)hipEventDestroy(s->ev_copied[b]);
+        if (s->ev_free[b]) (void)hipEventDestroy(s->ev_free[b]);
+    }
+    if (s->copy_stream) (void)hipStreamDestroy(s->copy_stream);
     delete s;
     return EXAT_OK;
 }
@@ -471,25 +487,27 @@ int exat_stage1_dims(exat_stage1_t s, int32_t *A1, int32_t *B1, int32_t *C1)
     return EXAT_OK;
 }
 
-int exat_stage1_apply(exat_stage1_t s, const float *X, float *X1, void *stream)
+namespace {
+
+// modes 1 and 2 over the nk frontal slices starting at X (slices k0 .. k0+nk-1 of the tensor)
+int run_mode12(exat_stage1_s *s, const float *X, int64_t k0, int64_t nk, hipStream_t st)
 {
-    if (!s || !X || !X1) return EXAT_ERR_NULL;
-    hipStream_t st = (hipStream_t)stream;
     S1Params p;
-    p.X = X; p.I = s->I; p.J = s->J; p.K = s->K; p.A1 = s->A1; p.B1 = s->B1;
+    p.X = X; p.I = s->I; p.J = s->J; p.K = s->K; p.A1 = s->A1; p.B1 = s->B1; p.k0 = k0;
     p.Uoc = s->Uoc; p.Uch = s->Uch; p.Vtp = s->Vtp; p.Vent = s->Vent; p.Q = s->Q; p.jt_per = s->jt_per; p.qstride = qstride_of(s);
     const int AT = s->A1 > 64 ? 2 : 1;
     const size_t lds = (size_t)(S1_JT * S1_XS + S1_JT * (64 * AT + 1)) * sizeof(float);
-    const dim3 grid((unsigned)s->K, (unsigned)s->JS);
-    if (s->timing && hipEventRecord(s->ev[0], st) != hipSuccess) return EXAT_ERR_HIP;
-    int rc;
+    const dim3 grid((unsigned)nk, (unsigned)s->JS);
     constexpr int BR1 = 64 / S1_NW, BR2 = 128 / S1_NW;
-    if (s->A1 <= 64 && s->B1 <= 64) rc = launch12<1, BR1>(p, grid, lds, st);
-    else if (s->A1 <= 64) rc = launch12<1, BR2>(p, grid, lds, st);
-    else if (s->B1 <= 64) rc = launch12<2, BR1>(p, grid, lds, st);
-    else rc = launch12<2, BR2>(p, grid, lds, st);
-    if (rc != EXAT_OK) return rc;
-    if (s->timing && hipEventRecord(s->ev[1], st) != hipSuccess) return EXAT_ERR_HIP;
+    if (s->A1 <= 64 && s->B1 <= 64) return launch12<1, BR1>(p, grid, lds, st);
+    if (s->A1 <= 64) return launch12<1, BR2>(p, grid, lds, st);
+    if (s->B1 <= 64) return launch12<2, BR1>(p, grid, lds, st);
+    return launch12<2, BR2>(p, grid, lds, st);
+}
+
+// sum of the column ranges, then mode 3
+int run_mode3(exat_stage1_s *s, float *X1, hipStream_t st)
+{
     if (s->JS > 1) {
         const int64_t n4 = qstride_of(s) / 4;
         hipLaunchKernelGGL(k_stage1_sum_ranges, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, st, s->Q, s->JS, qstride_of(s), n4);
@@ -498,12 +516,63 @@ int exat_stage1_apply(exat_stage1_t s, const float *X, float *X1, void *stream)
     S1Mode3Params m;
     m.Q = s->Q; m.rp = s->Wrp; m.ci = s->Wci; m.val = s->Wval; m.X1 = X1; m.AB = (int64_t)s->A1 * s->B1;
     hipLaunchKernelGGL(k_stage1_mode3, dim3((unsigned)((m.AB + 255) / 256), (unsigned)s->C1), dim3(256), 0, st, m);
-    if (hipGetLastError() != hipSuccess) return EXAT_ERR_HIP;
+    return hipGetLastError() == hipSuccess ? EXAT_OK : EXAT_ERR_HIP;
+}
+
+}  // namespace
+
+int exat_stage1_apply(exat_stage1_t s, const float *X, float *X1, void *stream)
+{
+    if (!s || !X || !X1) return EXAT_ERR_NULL;
+    hipStream_t st = (hipStream_t)stream;
+    if (s->timing && hipEventRecord(s->ev[0], st) != hipSuccess) return EXAT_ERR_HIP;
+    int rc = run_mode12(s, X, 0, s->K, st);
+    if (rc != EXAT_OK) return rc;
+    if (s->timing && hipEventRecord(s->ev[1], st) != hipSuccess) return EXAT_ERR_HIP;
+    if ((rc = run_mode3(s, X1, st)) != EXAT_OK) return rc;
     if (s->timing) {
         if (hipEventRecord(s->ev[2], st) != hipSuccess) return EXAT_ERR_HIP;
         s->timing_valid = true;
     }
     return EXAT_OK;
+}
+
+int exat_stage1_apply_host(exat_stage1_t s, const float *Xhost, float *X1, void *stream)
+{
+    if (!s || !Xhost || !X1) return EXAT_ERR_NULL;
+    hipStream_t st = (hipStream_t)stream;
+    const int64_t slice = s->I * s->J;   // elements per frontal slice; slices are contiguous in a column-major tensor
+    if (!s->copy_stream) {
+        // about 128 MiB per slab; EXAT_STAGE1_SLAB_BYTES overrides the size (testing aid: several slabs on small tensors)
+        const char *env = getenv("EXAT_STAGE1_SLAB_BYTES");
+        const int64_t target = env && atoll(env) > 0 ? atoll(env) : (int64_t)(128u << 20);
+        int64_t slab = target / (slice * 4);
+        slab = slab < 1 ? 1 : (slab > s->K ? s->K : slab);
+        // default priority: streams of different priorities are never mixed in this library
+        if (hipStreamCreateWithFlags(&s->copy_stream, hipStreamNonBlocking) != hipSuccess) { s->copy_stream = nullptr; return EXAT_ERR_HIP; }
+        s->slab = slab;
+        for (int b = 0; b < exat_stage1_s::kRing; b++) {
+            if (hipMalloc((void **)&s->ring[b], (size_t)slab * slice * 4) != hipSuccess) { s->ring[b] = nullptr; (void)hipGetLastError(); return EXAT_ERR_ALLOC; }
+            if (hipEventCreateWithFlags(&s->ev_copied[b], hipEventDisableTiming) != hipSuccess ||
+                hipEventCreateWithFlags(&s->ev_free[b], hipEventDisableTiming) != hipSuccess) return EXAT_ERR_HIP;
+        }
+    }
+    for (int b = 0; b < exat_stage1_s::kRing; b++)
+        if (!s->ring[b] || !s->ev_copied[b] || !s->ev_free[b]) return EXAT_ERR_ALLOC;   // an earlier set-up failed half way
+    int64_t n = 0;
+    for (int64_t k0 = 0; k0 < s->K; k0 += s->slab, n++) {
+        const int b = (int)(n % exat_stage1_s::kRing);
+        const int64_t nk = k0 + s->slab <= s->K ? s->slab : s->K - k0;
+        if (s->ring_used[b] && hipStreamWaitEvent(s->copy_stream, s->ev_free[b], 0) != hipSuccess) return EXAT_ERR_HIP;
+        if (hipMemcpyAsync(s->ring[b], Xhost + k0 * slice, (size_t)nk * slice * 4, hipMemcpyHostToDevice, s->copy_stream) != hipSuccess) return EXAT_ERR_HIP;
+        if (hipEventRecord(s->ev_copied[b], s->copy_stream) != hipSuccess) return EXAT_ERR_HIP;
+        if (hipStreamWaitEvent(st, s->ev_copied[b], 0) != hipSuccess) return EXAT_ERR_HIP;
+        const int rc = run_mode12(s, s->ring[b], k0, nk, st);
+        if (rc != EXAT_OK) return rc;
+        if (hipEventRecord(s->ev_free[b], st) != hipSuccess) return EXAT_ERR_HIP;
+        s->ring_used[b] = true;
+    }
+    return run_mode3(s, X1, st);
 }
 
 int exat_stage1_set_timing(exat_stage1_t s, int enable)

@@ -16,7 +16,7 @@ OK, ERR_NULL, ERR_SHAPE, ERR_DTYPE, ERR_STATE, ERR_ALLOC, ERR_HIP = 0, -1, -2, -
 EXPORTS = ["exat_plan_create", "exat_plan_destroy", "exat_set_factors", "exat_compress",
            "exat_compress_block", "exat_finalize", "exat_compress_host", "exat_compress_gen", "exat_gen_block",
            "exat_plan_set_timing", "exat_plan_last_timing", "exat_plan_check_status",
-           "exat_stage1_create", "exat_stage1_destroy", "exat_stage1_dims", "exat_stage1_apply",
+           "exat_stage1_create", "exat_stage1_destroy", "exat_stage1_dims", "exat_stage1_apply", "exat_stage1_apply_host",
            "exat_stage1_set_timing", "exat_stage1_last_timing", "exat_strerror"]
 
 
@@ -82,6 +82,7 @@ def lib():
         L.exat_stage1_destroy.argtypes = [vp]
         L.exat_stage1_dims.argtypes = [vp, ctypes.POINTER(i32), ctypes.POINTER(i32), ctypes.POINTER(i32)]
         L.exat_stage1_apply.argtypes = [vp, vp, vp, vp]
+        L.exat_stage1_apply_host.argtypes = [vp, vp, vp, vp]
         L.exat_stage1_set_timing.argtypes = [vp, ctypes.c_int]
         L.exat_stage1_last_timing.argtypes = [vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_float)]
         L.exat_strerror.argtypes = [ctypes.c_int]
@@ -263,4 +264,13 @@ class Stage1:
         if X1 is None:
             X1 = torch.empty(self.dims[0] * self.dims[1] * self.dims[2], dtype=torch.float32, device="cuda")
         _check(lib().exat_stage1_apply(self._h, _ptr(X), _ptr(X1), _stream_handle(stream)))
+        return X1
+
+    def apply_host(self, Xhost, X1=None, stream=None):
+        """Xhost: float32 CPU tensor (ideally pinned) holding the column-major tensor; streamed slab by slab."""
+        import torch
+        assert (not Xhost.is_cuda) and Xhost.dtype == torch.float32 and Xhost.is_contiguous()
+        if X1 is None:
+            X1 = torch.empty(self.dims[0] * self.dims[1] * self.dims[2], dtype=torch.float32, device="cuda")
+        _check(lib().exat_stage1_apply_host(self._h, _ptr(Xhost), _ptr(X1), _stream_handle(stream)))
         return X1

@@ -168,3 +168,23 @@ def test_first_stage_degenerate_shapes():
             assert (got == 0).all()
         else:
             assert _rel(got, ref) <= TOL
+
+
+def test_first_stage_from_host_memory(monkeypatch):
+    """exat_stage1_apply_host: slabs of slices copied from host memory ahead of the kernels; bit-identical to the
+    device-resident call.  The slab size is forced down so that the 23 slices take 8 slabs (ring of 3 reused)."""
+    ts = _ts(I=150, J=100, K=23, L=10, M=9, N=5, index=302)
+    b = ts.base
+    monkeypatch.setenv("EXAT_STAGE1_SLAB_BYTES", str(3 * b.I * b.J * 4))
+    X = _x(13, b.I, b.J, b.K)
+    mats = wl.first_stage_matrices(ts)
+    st = exat.Stage1(b.I, b.J, b.K, *mats)
+    Xflat = torch.from_numpy(np.ascontiguousarray(X.reshape(-1, order="F")))
+    ref = st.apply(Xflat.cuda()).clone()
+    a = st.apply_host(Xflat.pin_memory()).clone()
+    c = st.apply_host(Xflat.clone()).clone()      # pageable, second pass over the ring
+    torch.cuda.synchronize()
+    assert torch.equal(a, ref) and torch.equal(c, ref)
+    got = a.cpu().numpy().astype(np.float64).reshape(st.dims, order="F")
+    assert _rel(got, oracle.first_stage(X, *mats)) <= TOL
+    st.close()
