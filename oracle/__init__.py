@@ -5,8 +5,8 @@ cpu_baseline leg may import this package; the product (the HIP library and its
 Python binding) never does, and this package never imports the product.
 
 Every function is a numpy-facing wrapper over oracle/exat_oracle.c (plain C,
-fp64 accumulation), except the two-stage functions at the end (Sec. 4.4), which are
-plain numpy in fp64.
+fp64 accumulation), except the two-stage functions (Sec. 4.4) and the CP-ALS of the
+proxy tensors (Alg. 1) at the end, which are plain numpy in fp64.
 
 Conventions (paper Sec. 3, Eq. 3 and Sec. 4.1):
   X   float32 array of shape (I, J, K), Fortran (column-major) order
@@ -231,3 +231,45 @@ def two_stage(X, Ucsr, Vcsr, Wcsr, U2, V2, W2, P, replicas=None):
         Wp = W2[p * N:(p + 1) * N].astype(np.float64) @ Wd
         Y[:, :, :, t] = ttm_chain64(X64, Up, Vp, Wp)
     return Y
+
+
+# ---- CP-ALS on the proxy tensors (Alg. 1), the consumer of Y ---------------------------------------
+# Plain numpy in fp64.  One sweep = the three updates of the algorithm's loop body in its order (A, B, C),
+# each the least-squares solution with the two other matrices fixed:
+#   A <- Y_(1) (C kr B) [(C^T C) * (B^T B)]^{-1}      (kr = Khatri-Rao product, * = Hadamard product)
+# The listing prints the Gram term without the inverse and as C C^T; read as the standard normal equations.
+
+def khatri_rao(C, B):
+    """Column-wise Kronecker product: row (m + M*n) of the result is C[n,:] * B[m,:]."""
+    N, R = C.shape
+    M = B.shape[0]
+    return (C[:, None, :] * B[None, :, :]).reshape(N * M, R)
+
+
+def unfold(Y, mode):
+    """Mode-n matricisation of a 3-way array in the column-major convention of Sec. 2:
+    Y_(1)[l, m + M*n], Y_(2)[m, l + L*n], Y_(3)[n, l + L*m]."""
+    Y = np.asarray(Y, dtype=np.float64)
+    L, M, N = Y.shape
+    if mode == 0:
+        return Y.reshape(L, M * N, order="F")
+    if mode == 1:
+        return Y.transpose(1, 0, 2).reshape(M, L * N, order="F")
+    return Y.transpose(2, 0, 1).reshape(N, L * M, order="F")
+
+
+def cp_als(Y, A0, B0, C0, sweeps):
+    """`sweeps` sweeps of Alg. 1 from the given start; returns float64 (A, B, C)."""
+    A, B, C = (np.array(F, dtype=np.float64) for F in (A0, B0, C0))
+    Y1, Y2, Y3 = unfold(Y, 0), unfold(Y, 1), unfold(Y, 2)
+    for _ in range(sweeps):
+        A = np.linalg.solve(((C.T @ C) * (B.T @ B)).T, (Y1 @ khatri_rao(C, B)).T).T
+        B = np.linalg.solve(((C.T @ C) * (A.T @ A)).T, (Y2 @ khatri_rao(C, A)).T).T
+        C = np.linalg.solve(((B.T @ B) * (A.T @ A)).T, (Y3 @ khatri_rao(B, A)).T).T
+    return A, B, C
+
+
+def cp_reconstruct(A, B, C):
+    """sum_r a_r o b_r o c_r (Eq. 1) as a float64 (L, M, N) array."""
+    return np.einsum("lr,mr,nr->lmn", np.asarray(A, dtype=np.float64), np.asarray(B, dtype=np.float64),
+                     np.asarray(C, dtype=np.float64))
