@@ -231,6 +231,23 @@ int exat_stage1_apply_host(exat_stage1_t s, const float *Xhost, float *X1, void 
 int exat_stage1_set_timing(exat_stage1_t s, int enable);
 int exat_stage1_last_timing(exat_stage1_t s, float *ms_mode12, float *ms_mode3);
 
+/* ---- CP-ALS on the proxy tensors (Alg. 1) ----------------------------------------------------------
+ * The decomposition stage applies the alternating-least-squares algorithm to each of the P small tensors
+ * Y_p (L x M x N) that the compression produced.  exat_cpals runs `sweeps` sweeps of the loop body of Alg. 1
+ * (update A, then B, then C; each the least-squares solution with the other two fixed,
+ * A <- Y_(1) (C kr B) [(C^T C) * (B^T B)]^{-1}, solved by Cholesky factorisation of the R x R normal matrix)
+ * for all P replicas at once, one workgroup per replica, in fp32.  There is no convergence test: the caller
+ * chooses the number of sweeps.
+ *   Y      device, P*L*M*N floats in the layout exat_compress writes: Y[l + L*(m + M*(n + N*p))]; not modified
+ *   A,B,C  device, in: start values, out: result; per replica column-major L x R, M x R, N x R:
+ *          A[l + L*(r + R*p)] etc.
+ *   work   device scratch of exat_cpals_workspace_floats(L,M,N,P) floats (two permuted copies of Y), caller-owned
+ * Limits: L, M, N, R <= 64.  The normal matrices must be positive definite (they are for generic data); nothing
+ * checks it.  Asynchronous on `stream`.  Errors: NULL, SHAPE, HIP. */
+int64_t exat_cpals_workspace_floats(int32_t L, int32_t M, int32_t N, int32_t P);
+int exat_cpals(const float *Y, int32_t L, int32_t M, int32_t N, int32_t P, int32_t R, int32_t sweeps,
+               float *A, float *B, float *C, float *work, void *stream);
+
 /* Static description of a status code (never NULL). */
 const char *exat_strerror(int status);
 

@@ -13,6 +13,7 @@ UNITS = {
     "exat.hip": ["exat_device.h", "exat_common.h", "exat_mode12.h", "exat_mode2.h", "exat_mode12_v2.h",
                  "exat_mode12_v3.h", "exat_mode12_split.h", "exat_aux.h"],
     "exat_stage1.hip": [],
+    "exat_cpals.hip": [],
 }
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-w",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

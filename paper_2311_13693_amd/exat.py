@@ -17,7 +17,8 @@ EXPORTS = ["exat_plan_create", "exat_plan_destroy", "exat_set_factors", "exat_co
            "exat_compress_block", "exat_finalize", "exat_compress_host", "exat_compress_gen", "exat_gen_block",
            "exat_plan_set_timing", "exat_plan_last_timing", "exat_plan_check_status",
            "exat_stage1_create", "exat_stage1_destroy", "exat_stage1_dims", "exat_stage1_apply", "exat_stage1_apply_host",
-           "exat_stage1_set_timing", "exat_stage1_last_timing", "exat_strerror"]
+           "exat_stage1_set_timing", "exat_stage1_last_timing", "exat_cpals_workspace_floats", "exat_cpals",
+           "exat_strerror"]
 
 
 class Desc(ctypes.Structure):
@@ -85,10 +86,13 @@ def lib():
         L.exat_stage1_apply_host.argtypes = [vp, vp, vp, vp]
         L.exat_stage1_set_timing.argtypes = [vp, ctypes.c_int]
         L.exat_stage1_last_timing.argtypes = [vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_float)]
+        L.exat_cpals_workspace_floats.argtypes = [i32, i32, i32, i32]
+        L.exat_cpals.argtypes = [vp, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp]
         L.exat_strerror.argtypes = [ctypes.c_int]
         L.exat_strerror.restype = ctypes.c_char_p
         for name in EXPORTS[:-1]:
             getattr(L, name).restype = ctypes.c_int
+        L.exat_cpals_workspace_floats.restype = ctypes.c_int64
         _lib = L
     return _lib
 
@@ -274,3 +278,15 @@ class Stage1:
             X1 = torch.empty(self.dims[0] * self.dims[1] * self.dims[2], dtype=torch.float32, device="cuda")
         _check(lib().exat_stage1_apply_host(self._h, _ptr(Xhost), _ptr(X1), _stream_handle(stream)))
         return X1
+
+
+def cpals(Y, L, M, N, P, R, sweeps, A, B, C, work=None, stream=None):
+    """Batched CP-ALS (Alg. 1) on the P proxy tensors in Y (the flat output of Plan.compress).  A, B, C: float32 CUDA
+    tensors of P*L*R, P*M*R, P*N*R elements (per replica column-major), start values in, results out (in place)."""
+    import torch
+    for t in (Y, A, B, C):
+        assert t.is_cuda and t.dtype == torch.float32 and t.is_contiguous()
+    if work is None:
+        work = torch.empty(lib().exat_cpals_workspace_floats(L, M, N, P), dtype=torch.float32, device="cuda")
+    _check(lib().exat_cpals(_ptr(Y), L, M, N, P, R, sweeps, _ptr(A), _ptr(B), _ptr(C), _ptr(work), _stream_handle(stream)))
+    return A, B, C

@@ -88,3 +88,16 @@ def test_stage1_argument_errors():
     assert L.exat_stage1_create(ctypes.byref(h), 0, 4, 4, ctypes.byref(good), ctypes.byref(good), ctypes.byref(good)) == exat.ERR_SHAPE
     assert L.exat_stage1_apply(None, None, None, None) == exat.ERR_NULL
     assert L.exat_stage1_destroy(None) == exat.OK
+
+
+def test_cpals_argument_errors():
+    # validation happens before the first HIP call; the non-null pointers are never dereferenced
+    L = exat.lib()
+    p = ctypes.c_void_p(256)
+    assert L.exat_cpals(None, 2, 2, 2, 1, 1, 1, p, p, p, p, None) == exat.ERR_NULL
+    assert L.exat_cpals(p, 2, 2, 2, 1, 1, 1, p, p, p, None, None) == exat.ERR_NULL
+    assert L.exat_cpals(p, 65, 2, 2, 1, 1, 1, p, p, p, p, None) == exat.ERR_SHAPE
+    assert L.exat_cpals(p, 2, 2, 2, 1, 65, 1, p, p, p, p, None) == exat.ERR_SHAPE
+    assert L.exat_cpals(p, 2, 2, 2, 0, 1, 1, p, p, p, p, None) == exat.ERR_SHAPE
+    assert L.exat_cpals(p, 2, 2, 2, 1, 1, -1, p, p, p, p, None) == exat.ERR_SHAPE
+    assert L.exat_cpals_workspace_floats(3, 4, 5, 6) == 2 * 3 * 4 * 5 * 6
