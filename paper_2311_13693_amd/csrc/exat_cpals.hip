@@ -111,36 +111,49 @@ __global__ __launch_bounds__(256) void k_cpals(const CpParams p)
             G[r * GS + c] = g1 * g2;
         }
         __syncthreads();
-        // Cholesky factor in the lower triangle of G, column by column
+        // Cholesky factor in the lower triangle of G, right-looking: per column, scale it, then every thread
+        // updates its share of the trailing triangle (two barriers per column, no serial sums)
         for (int j = 0; j < R; j++) {
-            if (tid == 0) {
-                float d = G[j * GS + j];
-                for (int k = 0; k < j; k++) d = fmaf(-G[j * GS + k], G[j * GS + k], d);
-                G[j * GS + j] = sqrtf(d);
-            }
+            const float inv = 1.0f / sqrtf(G[j * GS + j]);
+            __syncthreads();   // everyone has read the pivot
+            for (int t = j + tid; t < R; t += 256) G[t * GS + j] *= inv;   // t = j: the pivot becomes its square root
             __syncthreads();
-            const float inv = 1.0f / G[j * GS + j];
-            for (int t = j + 1 + tid; t < R; t += 256) {
-                float v = G[t * GS + j];
-                for (int k = 0; k < j; k++) v = fmaf(-G[t * GS + k], G[j * GS + k], v);
-                G[t * GS + j] = v * inv;
+            const int n = R - 1 - j;   // trailing triangle: rows t > j, columns j < c <= t
+            for (int e = tid; e < n * n; e += 256) {
+                const int t = j + 1 + e / n, c = j + 1 + e % n;
+                if (c <= t) G[t * GS + c] = fmaf(-G[t * GS + j], G[c * GS + j], G[t * GS + c]);
             }
             __syncthreads();
         }
-        // one row of Mx per thread: L z = m, then L^T o = z, in place
+        // one row of Mx per thread, held in registers: L z = m, then L^T o = z.  The loops are unrolled to the
+        // instantiation's largest rank, so the row is indexed statically and the reads of the factor (the same
+        // address for every thread) do not depend on the data.
         if (tid < D0) {
-            float *m = Mx + tid * GS;
-            for (int i = 0; i < R; i++) {
-                float v = m[i];
-                for (int k = 0; k < i; k++) v = fmaf(-G[i * GS + k], m[k], v);
-                m[i] = v / G[i * GS + i];
+            float m[RS];
+#pragma unroll
+            for (int i = 0; i < RS; i++) m[i] = i < R ? Mx[tid * GS + i] : 0.0f;
+#pragma unroll
+            for (int i = 0; i < RS; i++) {
+                if (i < R) {
+                    float v = m[i];
+#pragma unroll
+                    for (int k = 0; k < i; k++) v = fmaf(-G[i * GS + k], m[k], v);
+                    m[i] = v / G[i * GS + i];
+                }
             }
-            for (int i = R - 1; i >= 0; i--) {
-                float v = m[i];
-                for (int k = i + 1; k < R; k++) v = fmaf(-G[k * GS + i], m[k], v);
-                m[i] = v / G[i * GS + i];
+#pragma unroll
+            for (int i = RS - 1; i >= 0; i--) {
+                if (i < R) {
+                    float v = m[i];
+#pragma unroll
+                    for (int k = i + 1; k < RS; k++)
+                        if (k < R) v = fmaf(-G[k * GS + i], m[k], v);
+                    m[i] = v / G[i * GS + i];
+                }
             }
-            for (int r = 0; r < R; r++) F0[tid * RS + r] = m[r];
+#pragma unroll
+            for (int r = 0; r < RS; r++)
+                if (r < R) F0[tid * RS + r] = m[r];
         }
         __syncthreads();
     };
