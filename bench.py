@@ -45,7 +45,101 @@ def parse():
                     help="fp32 materialised configurations only: the two-stage compression of Sec. 4.4 (sparse first "
                          "stage to 2L x 2M x 2N with 4 entries per column, then the dense replicas on its output); the "
                          "roofline object then describes the HBM-bound first-stage kernel")
+    ap.add_argument("--cpals", action="store_true",
+                    help="the decomposition stage on the configuration's proxy tensors: 10 sweeps of batched CP-ALS (Alg. 1) "
+                         "over the P tensors of L x M x N that the compression of the same synthetic tensor produced (fp32 "
+                         "materialised configurations); value then counts proxy-tensor elements swept per second")
     return ap.parse_args()
+
+
+def cpals(args):
+    """One step = `SWEEPS` sweeps of Alg. 1 over all P proxy tensors (the output of one compression pass)."""
+    import torch
+    from paper_2311_13693_amd import exat, workloads as wl
+    SWEEPS = 10
+    cfg = wl.CONFIGS[args.config]
+    assert cfg.materialised and cfg.dtype == "f32", "--cpals needs a materialised fp32 configuration"
+    steps = args.steps if args.steps is not None else 10
+    warmup = args.warmup if args.warmup is not None else 2
+    torch.cuda.set_device(0)
+    A, B, C = wl.cp_factors(cfg)
+    U, V, W = wl.compression_matrices(cfg)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+    gen = exat.make_gen(dev(A.T), dev(B.T), dev(C.T), cfg.seed, cfg.sigma)
+    plan = exat.Plan(exat.make_desc(cfg.I, cfg.J, cfg.K, cfg.L, cfg.M, cfg.N, cfg.P, cfg.dI, cfg.dJ, cfg.dK, exat.EXAT_F32))
+    plan.set_factors(dev(U), dev(V), dev(W))
+    whole = exat.make_desc(cfg.I, cfg.J, cfg.K, cfg.L, cfg.M, cfg.N, cfg.P, cfg.I, cfg.J, cfg.K, exat.EXAT_F32)
+    X = torch.empty(cfg.elements, dtype=torch.float32, device="cuda")
+    exat.gen_block(whole, gen, 0, 0, 0, X)
+    Y = plan.compress(X)                      # the proxy tensors: input of the timed region, resident in HBM
+    torch.cuda.synchronize()
+    del X
+    L, M, N, P, R = cfg.L, cfg.M, cfg.N, cfg.P, cfg.R
+    rng = np.random.default_rng(cfg.seed & 0xFFFFFFFF)
+    start = [rng.standard_normal((P, R, d)).astype(np.float32) for d in (L, M, N)]   # [p][r][d] = column-major d x R
+    S = [torch.from_numpy(s).cuda() for s in start]
+    F = [s.clone() for s in S]
+    work = torch.empty(exat.lib().exat_cpals_workspace_floats(L, M, N, P), dtype=torch.float32, device="cuda")
+
+    def step():
+        for f, s in zip(F, S):
+            f.copy_(s)
+        exat.cpals(Y, L, M, N, P, R, SWEEPS, F[0], F[1], F[2], work)
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ks, ke = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    kms = []
+    e0.record()
+    for _ in range(steps):
+        for f, s in zip(F, S):
+            f.copy_(s)
+        ks.record()                           # the library's kernels run on torch's current stream
+        exat.cpals(Y, L, M, N, P, R, SWEEPS, F[0], F[1], F[2], work)
+        ke.record()
+        ke.synchronize()
+        kms.append(ks.elapsed_time(ke))
+    e1.record()
+    torch.cuda.synchronize()
+    ms_step, ms_k = e0.elapsed_time(e1) / steps, float(np.mean(kms))
+    flops = 3 * 2.0 * L * M * N * R * P * SWEEPS          # the three MTTKRPs of a sweep, factored form
+    achieved = flops / (ms_k * 1e-3) / 1e12
+    out = {
+        "metric": "input tensor elements compressed/sec + TTM TFLOP/s (% MFMA peak), 1 MI355X",
+        "value": P * L * M * N * SWEEPS / (ms_step * 1e-3), "unit": "elements/s",
+        "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "%s decomposition stage: %d sweeps of CP-ALS (rank %d) over the %d proxy tensors of %dx%dx%d; "
+                               "elements = proxy-tensor elements x sweeps" % (cfg.name, SWEEPS, R, P, L, M, N)},
+        "kernel_ms": {"all_launches": ms_k, "per_sweep": ms_k / SWEEPS},
+        "roofline": {"bound": "alu", "kernel": "k_cpals_mttkrp + k_cpals_solve", "achieved": achieved, "peak": 157.3, "unit": "TFLOP/s",
+                     "frac": achieved / 157.3, "traffic": None},
+    }
+    Yh = Y.cpu().numpy().reshape((L, M, N, P), order="F")
+    if args.check:
+        import oracle
+        errs = []
+        for p in (0, P - 1):
+            ref = oracle.cp_als(Yh[..., p], start[0][p].T, start[1][p].T, start[2][p].T, SWEEPS)
+            for f, d, r in zip(F, (L, M, N), ref):
+                got = f[p].cpu().numpy().T.astype(np.float64)
+                errs.append(float(np.linalg.norm(got - r) / np.linalg.norm(r)))
+        out["check"] = {"replicas": [0, P - 1], "worst_factor_rel_fro_vs_oracle": max(errs)}
+    if not args.no_cpu_baseline:
+        import oracle
+        from threadpoolctl import threadpool_info
+        nrep = min(P, 4)
+        t0 = time.perf_counter()
+        for p in range(nrep):
+            oracle.cp_als(Yh[..., p], start[0][p].T, start[1][p].T, start[2][p].T, SWEEPS)
+        t = (time.perf_counter() - t0) * P / nrep
+        cores = max([int(lib.get("num_threads", 1)) for lib in threadpool_info()] + [1])
+        out["cpu_baseline"] = {"value": P * L * M * N * SWEEPS / t, "unit": "elements/s", "cores": cores, "kind": "oracle",
+                               "sample": "replicas 0..%d of %d, %d sweeps each (numpy fp64), scaled to all replicas" % (nrep - 1, P, SWEEPS),
+                               "seconds_full": t, "extrapolated": nrep < P}
+    plan.close()
+    print(json.dumps(out))
 
 
 def two_stage(args):
@@ -190,6 +284,8 @@ def main():
     sys.path.insert(0, os.path.join(ROOT, "tests"))
     if args.two_stage:
         return two_stage(args)
+    if args.cpals:
+        return cpals(args)
     import torch
     from paper_2311_13693_amd import exat, workloads as wl
     cfg = wl.CONFIGS[args.config]
