@@ -116,8 +116,17 @@ __global__ __launch_bounds__(256) void k_cpals_solve(const CpUpdate p)
     // MTTKRP result: the slabs' partial results in slab order
     for (int e = tid; e < D0 * R; e += 256) {
         const float *src = p.part + rep * p.NS * D0 * R + e;
-        float v = src[0];
-        for (int sl = 1; sl < p.NS; sl++) v += src[(int64_t)sl * D0 * R];
+        const int64_t st = (int64_t)D0 * R;
+        float v = 0.0f;
+        int sl = 0;
+        for (; sl + 8 <= p.NS; sl += 8) {   // eight loads in flight, added in slab order
+            float t[8];
+#pragma unroll
+            for (int u = 0; u < 8; u++) t[u] = src[(sl + u) * st];
+#pragma unroll
+            for (int u = 0; u < 8; u++) v += t[u];
+        }
+        for (; sl < p.NS; sl++) v += src[sl * st];
         Mx[(e / R) * GS + e % R] = v;
     }
     __syncthreads();
