@@ -31,7 +31,8 @@ struct exat_plan_s {
     int64_t Ipad, Jpad;
     void *Upack = nullptr;
     void *Ufrag = nullptr;  // U in MFMA fragment order (k_pack_u_frag), same size as Upack
-    void *Vfrag = nullptr;  // bf16 plans: V in bf16 MFMA fragment order (k_pack_v_frag)
+    void *Vfrag = nullptr;  // bf16 plans: V in bf16 MFMA fragment order (k_pack_v_frag); fp32 plans: V in the order
+                            // mode2_direct consumes (k_pack_v_direct)
     _Float16 *Ufh = nullptr, *Ufl = nullptr, *Vfh = nullptr, *Vfl = nullptr;  // split plans: fp16 pieces in fragment order
     float *Vpack = nullptr, *Wpack = nullptr, *Q = nullptr;
     bool factors_set = false;
@@ -167,11 +168,11 @@ int launch_v2_gen_f32(const Mode12Params &mp, const GenSplitParams &gs, const Ch
     return boxed ? launch_v2_inst<float, NW, RT, SRC_GENERATED, 2, true>(mp, gs, ck, nk, st) : launch_v2_inst<float, NW, RT, SRC_GENERATED, 2, false>(mp, gs, ck, nk, st);
 }
 
-template <typename T, int NW, int RT, int SRC, int KS, bool BOXED, int DU, int DX, int WPS = (NW + 3) / 4, bool CHECKED = false>
+template <typename T, int NW, int RT, int SRC, int KS, bool BOXED, int DU, int DX, int WPS = (NW + 3) / 4, bool CHECKED = false, bool ZT = false>
 int launch_v3_inst(const Mode12Params &mp, const GenSplitParams &gs, const UFragParams &uf, const CheckParams &ck, int nk, hipStream_t st)
 {
     typedef Mode12V3Cfg<NW, RT> cfg;
-    auto kern = k_mode12_v3<T, NW, RT, SRC, KS, BOXED, CHECKED, DU, DX, WPS>;
+    auto kern = k_mode12_v3<T, NW, RT, SRC, KS, BOXED, CHECKED, DU, DX, WPS, ZT>;
     static bool attr_done = false;
     if (!attr_done) {
         if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, cfg::LDS_BYTES) != hipSuccess) return EXAT_ERR_HIP;
@@ -190,6 +191,13 @@ int launch_v3_mat(const Mode12Params &mp, const GenSplitParams &gs, const UFragP
 {
     constexpr int D = sizeof(T) == 2 ? 3 : 2, DXV = sizeof(T) == 2 ? 3 : 1;
     return launch_v3_inst<T, NW, RT, SRC_MATERIALISED, 1, false, D, DXV>(mp, gs, uf, ck, nk, st);
+}
+
+// fp32 materialised source with mode 2 straight from the (transposed) accumulators; needs L % 32 == 0
+template <int NW, int RT>
+int launch_v3_mat_zt(const Mode12Params &mp, const GenSplitParams &gs, const UFragParams &uf, const CheckParams &ck, int nk, hipStream_t st)
+{
+    return launch_v3_inst<float, NW, RT, SRC_MATERIALISED, 1, false, 2, 1, (NW + 3) / 4, false, true>(mp, gs, uf, ck, nk, st);
 }
 
 // bf16 generated source, 4 waves
@@ -300,6 +308,8 @@ int run_chain(exat_plan_s *pl, Mode12Params mp, bool generated, float *Yout, int
         uf.Uf = pl->Ufrag; uf.nig = pl->Ipad / (bf ? 16 : 8); uf.Vf = pl->Vfrag;
         if (!generated) {
             if (bf) rc = rt == 4 ? launch_v3_mat<__bf16, 8, 2>(mp, gs, uf, ck, nk, st) : launch_v3_mat<__bf16, 4, 2>(mp, gs, uf, ck, nk, st);
+            else if (pl->d.L % 32 == 0 && env_int("EXAT_ZT", 1))
+                rc = rt == 4 ? launch_v3_mat_zt<8, 2>(mp, gs, uf, ck, nk, st) : launch_v3_mat_zt<4, 2>(mp, gs, uf, ck, nk, st);
             else rc = rt == 4 ? launch_v3_mat<float, 8, 2>(mp, gs, uf, ck, nk, st) : launch_v3_mat<float, 4, 2>(mp, gs, uf, ck, nk, st);
         } else if (bf) {
             if (rt == 4) rc = launch_v3_gen_bf16_8w_checked(mp, gs, uf, ck, ks, boxed, nk, st);
@@ -393,6 +403,7 @@ int exat_plan_create(exat_plan_t *plan, const exat_desc_t *desc)
         hipMalloc((void **)&pl->Asplit, pl->ab) != hipSuccess ||
         hipMalloc(&pl->Upack, ub) != hipSuccess || hipMalloc(&pl->Ufrag, ub) != hipSuccess ||
         (desc->in_dtype == EXAT_BF16 && hipMalloc(&pl->Vfrag, (size_t)desc->P * pl->Jpad * 64 * 2) != hipSuccess) ||
+        (desc->in_dtype != EXAT_BF16 && hipMalloc(&pl->Vfrag, (size_t)desc->P * pl->Mpad * pl->Jpad * 4) != hipSuccess) ||
         (desc->in_dtype == EXAT_F32_SPLIT &&
          (hipMalloc((void **)&pl->Ufh, (size_t)pl->PLpad * pl->Ipad * 2) != hipSuccess || hipMalloc((void **)&pl->Ufl, (size_t)pl->PLpad * pl->Ipad * 2) != hipSuccess ||
           hipMalloc((void **)&pl->Vfh, (size_t)desc->P * pl->Jpad * 64 * 2) != hipSuccess || hipMalloc((void **)&pl->Vfl, (size_t)desc->P * pl->Jpad * 64 * 2) != hipSuccess)) || hipMalloc((void **)&pl->Vpack, vb) != hipSuccess ||
@@ -448,6 +459,7 @@ int exat_set_factors(exat_plan_t pl, const float *U, int64_t ldU, const float *V
         hipLaunchKernelGGL(k_pack_u<float>, dim3(grid_for(nu)), dim3(256), 0, st, U, ldU, pl->PL, d.I, (float *)pl->Upack, pl->PLpad, pl->Ipad);
         hipLaunchKernelGGL(k_pack_u_frag<float>, dim3(grid_for(nu)), dim3(256), 0, st, U, ldU, pl->PL, d.I, (float *)pl->Ufrag, pl->PLpad / 32, pl->Ipad / 8);
         hipLaunchKernelGGL(k_pack_v<float>, dim3(grid_for(nv)), dim3(256), 0, st, V, ldV, d.P, d.M, d.J, pl->Vpack, pl->Mpad, pl->Jpad);
+        hipLaunchKernelGGL(k_pack_v_direct, dim3(grid_for(nv)), dim3(256), 0, st, V, ldV, d.P, d.M, d.J, (float *)pl->Vfrag, pl->Mpad, pl->Jpad);
         hipLaunchKernelGGL(k_pack_w<float>, dim3(grid_for(nw)), dim3(256), 0, st, W, ldW, d.P, d.N, d.K, pl->Wpack, pl->Npad);
     }
     if (hipGetLastError() != hipSuccess) return EXAT_ERR_HIP;

@@ -30,7 +30,7 @@ struct UFragParams {
                      // i = ig*GI + (l/32)*E16 .. +E16-1   (GI = 2*E16: 16 for bf16, 8 for fp32)
     int64_t nig;     // Ipad / GI
     const void *Vf;  // bf16 plans: [P][Jpad/16][2][64][8 bf16]: lane l of fragment (p, j16, mt) holds
-                     // V_p[m = 32*mt + l%32, j = 16*j16 + 8*(l/32) .. +7]
+                     // V_p[m = 32*mt + l%32, j = 16*j16 + 8*(l/32) .. +7]; fp32 plans: the order of k_pack_v_direct
 };
 
 template <int NW, int RT>
@@ -83,7 +83,9 @@ constexpr int lcm_i(int a, int b) { return a / gcd_i(a, b) * b; }
 // every set is addressed statically.
 // WPS: waves per SIMD the register allocation must allow (2 with NW = 4 lets two workgroups share a compute unit,
 // so that one's chunk set-up and mode-2 phases run under the other's MFMA phase).
-template <typename T, int NW, int RT, int SRC, int KS, bool BOXED, bool CHECKED, int DU = 2, int DX = 1, int WPS = (NW + 3) / 4>
+// ZT: mode 1 with the MFMA operands swapped (accumulators hold Z^T) and mode 2 straight from the accumulators
+// (mode2_direct; fp32 materialised source, L % 32 == 0).
+template <typename T, int NW, int RT, int SRC, int KS, bool BOXED, bool CHECKED, int DU = 2, int DX = 1, int WPS = (NW + 3) / 4, bool ZT = false>
 __global__ __launch_bounds__(64 * NW, WPS) void k_mode12_v3(const Mode12Params p, const GenSplitParams gs, const UFragParams uf, const CheckParams ck)
 {
     typedef Mode12V3Cfg<NW, RT> cfg;
@@ -326,7 +328,8 @@ __global__ __launch_bounds__(64 * NW, WPS) void k_mode12_v3(const Mode12Params p
             }
             static_for<NMAIN>([&](auto mc) {
                 constexpr int m = decltype(mc)::value, g2 = m / (RT * CT), rt = (m / CT) % RT, ct = m % CT;
-                mma_frag<T>::mma(acc[rt][ct], ufr[US][rt][g2], bx[g2][ct]);
+                if constexpr (ZT) mma_frag<T>::mma(acc[rt][ct], bx[g2][ct], ufr[US][rt][g2]);
+                else mma_frag<T>::mma(acc[rt][ct], ufr[US][rt][g2], bx[g2][ct]);
                 if constexpr (ct == CT - 1) ufr[US][rt][g2] = load_uf(rt, ig2 + g2);  // last use this stage: refill for stage s+DU
                 __builtin_amdgcn_sched_barrier(0);
                 if constexpr (SRC == SRC_GENERATED) {
@@ -394,7 +397,11 @@ __global__ __launch_bounds__(64 * NW, WPS) void k_mode12_v3(const Mode12Params p
         // ---- mode 2 on the finished Z chunk ----
         float *Zs = (float *)smem + wave * (32 * ZST);
         const bool first_chunk = (jc == ja0);
-        if (p.MT == 2) mode2_chunk<RT, CT, CHECKED, 2, sizeof(T) == 2 ? VM_BF16 : VM_F32>(p, uf.Vf, ck, Zs, acc, wrow0, kidx, jc, first_chunk, tid & 63);
+        if constexpr (ZT) {
+            static_assert(!ZT || (sizeof(T) == 4 && SRC == SRC_MATERIALISED && !CHECKED), "ZT: fp32 materialised source only");
+            if (p.MT == 2) mode2_direct<RT, CT, 2>(p, (const float *)uf.Vf, acc, wrow0, kidx, jc, first_chunk, tid & 63);
+            else mode2_direct<RT, CT, 1>(p, (const float *)uf.Vf, acc, wrow0, kidx, jc, first_chunk, tid & 63);
+        } else if (p.MT == 2) mode2_chunk<RT, CT, CHECKED, 2, sizeof(T) == 2 ? VM_BF16 : VM_F32>(p, uf.Vf, ck, Zs, acc, wrow0, kidx, jc, first_chunk, tid & 63);
         else mode2_chunk<RT, CT, CHECKED, 1, sizeof(T) == 2 ? VM_BF16 : VM_F32>(p, uf.Vf, ck, Zs, acc, wrow0, kidx, jc, first_chunk, tid & 63);
     }
 }
@@ -428,6 +435,22 @@ __global__ void k_pack_v_frag(const float *src, int64_t ld, int P, int M, int64_
         const int64_t j = 16 * j16 + 8 * (l >> 5) + e;
         const float v = (m < M && j < J) ? src[(pr * M + m) * ld + j] : 0.0f;
         dst[idx] = (__bf16)v;
+    }
+}
+
+// Stacked fp32 V (P*M x J) in the order mode2_direct consumes: [P][Mpad/32][Jpad/32][4 b][64 lanes][4 r] holds
+// V_p[m = 32*mt + l%32][j = 32*jt + 8*b + 4*(l/32) + r], zero padded.
+__global__ void k_pack_v_direct(const float *src, int64_t ld, int P, int M, int64_t J, float *dst, int Mpad, int64_t Jpad)
+{
+    const int64_t n = (int64_t)P * Mpad * Jpad;
+    const int64_t nj32 = Jpad / 32;
+    const int mtc = Mpad / 32;
+    for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < n; idx += (int64_t)gridDim.x * blockDim.x) {
+        const int r = (int)(idx & 3), l = (int)((idx >> 2) & 63), b = (int)((idx >> 8) & 3);
+        const int64_t f = idx >> 10, jt = f % nj32, mt = (f / nj32) % mtc, pr = f / (nj32 * mtc);
+        const int m = 32 * (int)mt + (l & 31);
+        const int64_t j = 32 * jt + 8 * b + 4 * (l >> 5) + r;
+        dst[idx] = (m < M && j < J) ? src[(pr * M + m) * ld + j] : 0.0f;
     }
 }
 

@@ -204,4 +204,60 @@ __device__ __forceinline__ void mode2_chunk(const Mode12Params &p, const void *V
     }
 }
 
+// Mode 2 straight from the accumulators, for kernels that ran mode 1 with the MFMA operands swapped, so that a
+// tile's accumulator holds Z^T (rows: 32 fibres j, columns: 32 stacked rows q).  Register 4b+r of lane l is then
+// Z^T[j = 8b + 4(l/32) + r][q = l%32], which is exactly what the 32x32x2 MFMA wants as its second operand for
+// the pair of contraction indices (8b + r, 8b + 4 + r): Q^T[m, q] += sum_j V_p[m, j] Z^T[j, q] takes 16 MFMAs per
+// tile with no trip through LDS.  V comes in the matching order (k_pack_v_direct): [p][mt][j/32][b][lane][r] holds
+// V_p[32 mt + l%32][32 (j/32) + 8b + 4(l/32) + r].  Requires L % 32 == 0 (a tile of 32 rows q lies in one
+// replica) and fp32 data.  Q keeps its layout [k][q][m]: a lane owns one row q and writes 16-byte pieces of it.
+template <int RT, int CT, int MTC>
+__device__ __forceinline__ void mode2_direct(const Mode12Params &p, const float *Vd, const f32x16 (&acc)[RT][CT], int wrow0, int kidx,
+                                             int64_t jc, bool first_chunk, int lane)
+{
+    constexpr int MP = 32 * MTC;   // = p.Mpad
+    const int l32 = lane & 31, hi = lane >> 5;
+    const int64_t nj32 = p.Jpad / 32;
+#pragma unroll
+    for (int rt = 0; rt < RT; rt++) {
+        const int q0 = wrow0 + rt * 32;   // wave-uniform
+        if (q0 < p.PL) {
+            const int pr = q0 / p.L;
+#pragma unroll
+            for (int mt = 0; mt < MTC; mt++) {
+                // this lane's 16 values of row q of Q (4 pieces of 4 consecutive m), requested before the MFMAs
+                float *Qt = p.Q + ((int64_t)kidx * p.PLpad + q0 + l32) * MP + 32 * mt + 4 * hi;   // + 8*b
+                f32x4 qold[4];
+#pragma unroll
+                for (int b = 0; b < 4; b++) qold[b] = first_chunk ? f32x4{0.0f, 0.0f, 0.0f, 0.0f} : *(const f32x4 *)(Qt + 8 * b);
+                const f32x4 *vf = (const f32x4 *)Vd + (((int64_t)pr * MTC + mt) * nj32 + jc / 32) * (4 * 64) + lane;   // + (ct*4 + b)*64
+                f32x4 v[CT][4];
+#pragma unroll
+                for (int ct = 0; ct < CT; ct++)
+#pragma unroll
+                    for (int b = 0; b < 4; b++) v[ct][b] = vf[(ct * 4 + b) * 64];
+                __builtin_amdgcn_sched_barrier(0);   // all requests before the first MFMA
+                f32x16 d;
+#pragma unroll
+                for (int e = 0; e < 16; e++) d[e] = 0.0f;
+#pragma unroll
+                for (int ct = 0; ct < CT; ct++)
+#pragma unroll
+                    for (int b = 0; b < 4; b++)
+#pragma unroll
+                        for (int r = 0; r < 4; r++)
+                            d = __builtin_amdgcn_mfma_f32_32x32x2f32(v[ct][b][r], acc[rt][ct][4 * b + r], d, 0, 0, 0);
+                // d: register 4b+r of lane l is Q^T[m = 32 mt + 8b + 4(l/32) + r][q = q0 + l%32]
+#pragma unroll
+                for (int b = 0; b < 4; b++) {
+                    f32x4 o;
+#pragma unroll
+                    for (int r = 0; r < 4; r++) o[r] = d[4 * b + r] + qold[b][r];
+                    *(f32x4 *)(Qt + 8 * b) = o;
+                }
+            }
+        }
+    }
+}
+
 }  // namespace exat
