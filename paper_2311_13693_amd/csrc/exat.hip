@@ -262,6 +262,7 @@ int run_chain(exat_plan_s *pl, Mode12Params mp, bool generated, float *Yout, int
     const bool split = pl->d.in_dtype == EXAT_F32_SPLIT && !generated && mp.x_vec && (mp.i0 % 32 == 0) && ((mp.i1 - mp.i0) % 32 == 0);
     const int rows = 128 * rt;
     mp.U = pl->Upack; mp.V = pl->Vpack; mp.Q = pl->Q;
+    mp.Vd = pl->d.in_dtype == EXAT_BF16 ? nullptr : (const float *)pl->Vfrag;
     mp.I = pl->d.I; mp.Ipad = pl->Ipad; mp.Jpad = pl->Jpad;
     mp.L = pl->d.L; mp.PL = pl->PL; mp.PLpad = pl->PLpad; mp.Mpad = pl->Mpad; mp.MT = pl->MT;
     mp.G = (pl->PL + rows - 1) / rows;

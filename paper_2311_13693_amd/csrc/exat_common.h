@@ -7,6 +7,7 @@ namespace exat {
 struct Mode12Params {
     const void *U;   // packed [PLpad][Ipad] of T, zero padded
     const float *V;  // packed [P][Mpad][Jpad] fp32, zero padded (bf16-rounded values for bf16 plans)
+    const float *Vd; // fp32 plans: V in the order mode2_direct consumes (k_pack_v_direct), else unused
     float *Q;        // [k1-k0][PLpad][Mpad] fp32
     // materialised source: element (i,j,k) at X[(i-xo_i) + (j-xo_j)*x_sj + (k-xo_k)*x_sk]
     const void *X;

@@ -30,7 +30,7 @@ struct UFragParams {
                      // i = ig*GI + (l/32)*E16 .. +E16-1   (GI = 2*E16: 16 for bf16, 8 for fp32)
     int64_t nig;     // Ipad / GI
     const void *Vf;  // bf16 plans: [P][Jpad/16][2][64][8 bf16]: lane l of fragment (p, j16, mt) holds
-                     // V_p[m = 32*mt + l%32, j = 16*j16 + 8*(l/32) .. +7]; fp32 plans: the order of k_pack_v_direct
+                     // V_p[m = 32*mt + l%32, j = 16*j16 + 8*(l/32) .. +7]
 };
 
 template <int NW, int RT>
@@ -399,8 +399,8 @@ __global__ __launch_bounds__(64 * NW, WPS) void k_mode12_v3(const Mode12Params p
         const bool first_chunk = (jc == ja0);
         if constexpr (ZT) {
             static_assert(!ZT || (sizeof(T) == 4 && SRC == SRC_MATERIALISED && !CHECKED), "ZT: fp32 materialised source only");
-            if (p.MT == 2) mode2_direct<RT, CT, 2>(p, (const float *)uf.Vf, acc, wrow0, kidx, jc, first_chunk, tid & 63);
-            else mode2_direct<RT, CT, 1>(p, (const float *)uf.Vf, acc, wrow0, kidx, jc, first_chunk, tid & 63);
+            if (p.MT == 2) mode2_direct<RT, CT, 2>(p, p.Vd, acc, wrow0, kidx, jc, first_chunk, tid & 63);
+            else mode2_direct<RT, CT, 1>(p, p.Vd, acc, wrow0, kidx, jc, first_chunk, tid & 63);
         } else if (p.MT == 2) mode2_chunk<RT, CT, CHECKED, 2, sizeof(T) == 2 ? VM_BF16 : VM_F32>(p, uf.Vf, ck, Zs, acc, wrow0, kidx, jc, first_chunk, tid & 63);
         else mode2_chunk<RT, CT, CHECKED, 1, sizeof(T) == 2 ? VM_BF16 : VM_F32>(p, uf.Vf, ck, Zs, acc, wrow0, kidx, jc, first_chunk, tid & 63);
     }
