@@ -53,7 +53,7 @@ struct exat_plan_s {
     // optional per-kernel timing
     bool timing = false, timing_valid = false;
     hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
-    __bf16 *Asplit = nullptr;  // bf16 pieces of the generator's A factor, [3][Ipad][64]
+    __bf16 *Asplit = nullptr;  // the two 16-bit pieces of the generator's A factor (bf16 or fp16 bit patterns), [2][Ipad][64]
     unsigned *dbg = nullptr;   // 8 counters written by bounds-checked kernel variants
     size_t ub = 0, vb = 0, qb = 0, ab = 0;  // byte sizes of Upack, Vpack, Q, Asplit
 };
@@ -272,7 +272,8 @@ int run_chain(exat_plan_s *pl, Mode12Params mp, bool generated, float *Yout, int
     gs.Asp = pl->Asplit; gs.Irows = pl->Ipad; gs.Rpad = 32 * ((mp.R + 31) / 32);
     if (pipelined && generated) {
         const int64_t n = gs.Irows * gs.Rpad;
-        hipLaunchKernelGGL(k_split_a, dim3(grid_for(n)), dim3(256), 0, st, mp.A, pl->d.I, mp.R, pl->Asplit, gs.Irows, gs.Rpad, bf ? 2 : 3);
+        if (bf) hipLaunchKernelGGL(k_split_a<__bf16>, dim3(grid_for(n)), dim3(256), 0, st, mp.A, pl->d.I, mp.R, pl->Asplit, gs.Irows, gs.Rpad);
+        else hipLaunchKernelGGL(k_split_a<float>, dim3(grid_for(n)), dim3(256), 0, st, mp.A, pl->d.I, mp.R, pl->Asplit, gs.Irows, gs.Rpad);
         if (hipGetLastError() != hipSuccess) return EXAT_ERR_HIP;
     }
     if (pl->timing && hipEventRecord(pl->ev[0], st) != hipSuccess) return EXAT_ERR_HIP;
@@ -330,6 +331,14 @@ int run_chain(exat_plan_s *pl, Mode12Params mp, bool generated, float *Yout, int
                 } else
                     rc = launch_v3_gen_bf16<3>(mp, gs, uf, ck, ks, boxed, nk, st);
             } else rc = launch_v3_gen_bf16<2>(mp, gs, uf, ck, ks, boxed, nk, st);
+        } else if (rt == 4 && pl->d.L % 32 == 0 && env_int("EXAT_F32_GEN_V3", 1)) {
+            // fp32 generator, 8 waves x 2 row tiles, U fragments straight into registers and mode 2 straight from the
+            // accumulators (the register-hungry LDS transposition of mode 2 was what made this build spill in its stage
+            // loop); EXAT_F32_GEN_V3=0 selects the LDS-staged kernel below
+            if (ks == 1) rc = boxed ? launch_v3_inst<float, 8, 2, SRC_GENERATED, 1, true, 2, 1, 2, false, true>(mp, gs, uf, ck, nk, st)
+                                    : launch_v3_inst<float, 8, 2, SRC_GENERATED, 1, false, 2, 1, 2, false, true>(mp, gs, uf, ck, nk, st);
+            else rc = boxed ? launch_v3_inst<float, 8, 2, SRC_GENERATED, 2, true, 2, 1, 2, false, true>(mp, gs, uf, ck, nk, st)
+                            : launch_v3_inst<float, 8, 2, SRC_GENERATED, 2, false, 2, 1, 2, false, true>(mp, gs, uf, ck, nk, st);
         } else
             rc = rt == 4 ? launch_v2_gen_f32<8, 2>(mp, gs, ck, ks, boxed, nk, st) : launch_v2_gen_f32<4, 2>(mp, gs, ck, ks, boxed, nk, st);
     } else if (pl->d.in_dtype == EXAT_BF16)

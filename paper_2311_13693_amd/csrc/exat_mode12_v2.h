@@ -10,7 +10,7 @@
 //   * for the generated source, the low-rank part of the X tile produced by MFMA instead of
 //     vector FMAs: X[i, j] = sum_r A[i,r] (B[j,r] C[k,r]) is a (32 x R)(R x 128) product per
 //     stage.  To keep fp32 accuracy on the bf16 matrix cores both operands are split into
-//     bf16 pieces (a = a_h + a_m + a_l) and the significant cross terms are accumulated in
+//     16-bit pieces (a = a_h + a_m; see gen_piece) and the three significant cross terms are accumulated in
 //     fp32: 6 terms (error ~2^-23) on the fp32 path, 3 terms (error ~2^-16, below the bf16
 //     rounding of the tile) on the bf16 path.  The noise term is added to the accumulator
 //     layout directly: each lane holds aligned quads of 4 consecutive i, the unit of the
@@ -36,7 +36,7 @@ typedef float f32x4v __attribute__((ext_vector_type(4)));
 #endif
 
 template <typename T> struct v2geom;
-template <> struct v2geom<float> { static constexpr int EI = 16, NV = 3, NTERM = 6, SUBI = 1; };
+template <> struct v2geom<float> { static constexpr int EI = 16, NV = 2, NTERM = 3, SUBI = 1; };
 template <> struct v2geom<__bf16> { static constexpr int EI = 32, NV = 2, NTERM = 3, SUBI = 2; };
 
 template <int NW, int RT>
@@ -48,14 +48,39 @@ struct Mode12V2Cfg {
     static constexpr int LDS_BYTES = 2 * BUF_BYTES > EPI_BYTES ? 2 * BUF_BYTES : EPI_BYTES;
 };
 
-// split an fp32 value into bf16 pieces: v = h + m + l up to 2^-24 relative
-__device__ __forceinline__ void split3(float v, __bf16 &h, __bf16 &m, __bf16 &l)
-{
-    h = (__bf16)v;
-    const float r1 = v - (float)h;
-    m = (__bf16)r1;
-    l = (__bf16)(r1 - (float)m);
-}
+// The generator's low-rank product runs on the 16x16x32 matrix instruction with every operand value taken as
+// the sum of two 16-bit pieces, v = h + m, and the three significant cross terms accumulated in fp32.
+// bf16 plans: bf16 pieces (16 significand bits together, below the bf16 rounding of the tile).
+// fp32 plans: fp16 pieces (22 significand bits together; the dropped term is 2^-22 of a product; the factors and
+// their products are O(1..100), far inside the fp16 range).  Pieces travel as raw 16-bit patterns in bf16x8
+// registers whatever their format.
+template <typename T> struct gen_piece;
+template <> struct gen_piece<__bf16> {
+    static constexpr int FMT = 0;
+    __device__ static __forceinline__ void split(float v, __bf16 &h, __bf16 &m)
+    {
+        h = (__bf16)v;
+        m = (__bf16)(v - (float)h);
+    }
+    __device__ static __forceinline__ f32x4v mfma(const bf16x8 &a, const bf16x8 &b, const f32x4v &c)
+    {
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+    }
+};
+template <> struct gen_piece<float> {
+    static constexpr int FMT = 1;
+    __device__ static __forceinline__ void split(float v, __bf16 &h, __bf16 &m)
+    {
+        const _Float16 fh = (_Float16)v;
+        const _Float16 fm = (_Float16)(v - (float)fh);
+        h = __builtin_bit_cast(__bf16, fh);
+        m = __builtin_bit_cast(__bf16, fm);
+    }
+    __device__ static __forceinline__ f32x4v mfma(const bf16x8 &a, const bf16x8 &b, const f32x4v &c)
+    {
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+    }
+};
 
 // BOXED: the box is a proper sub-range in i, so elements outside [i0,i1) must be forced to zero
 // (for the full extent the zero padding of U already removes them).
@@ -139,20 +164,19 @@ __global__ __launch_bounds__(64 * NW) void k_mode12_v2(const Mode12Params p, con
                 amp[sj] = colok ? p.amp2_ln2 : 0.0f;
 #pragma unroll
                 for (int ks = 0; ks < KS; ks++) {
-                    bf16x8 bh, bm, bl;
+                    bf16x8 bh, bm;
 #pragma unroll
                     for (int e = 0; e < 8; e++) {
                         // clamped, unconditional loads (no branch per element), masked afterwards
                         const int r = 32 * ks + 8 * q16 + e, rr = r < p.R ? r : p.R - 1;
                         float bc = ld_chk<CHECKED>(p.B + jj + p.ldB * rr, ck, CHK_B) * ld_chk<CHECKED>(p.C + k + p.ldC * rr, ck, CHK_C);
                         bc = (colok && r < p.R) ? bc : 0.0f;
-                        __bf16 h, m, l;
-                        split3(bc, h, m, l);
-                        bh[e] = h; bm[e] = m; bl[e] = l;
+                        __bf16 h, m;
+                        gen_piece<T>::split(bc, h, m);
+                        bh[e] = h; bm[e] = m;
                     }
                     bfrag[(0 * KS + ks) * NSJ + sj] = bh;
                     bfrag[(1 * KS + ks) * NSJ + sj] = bm;
-                    if (NV == 3) bfrag[((NV - 1) * KS + ks) * NSJ + sj] = bl;
                 }
             }
         }
@@ -198,16 +222,10 @@ __global__ __launch_bounds__(64 * NW) void k_mode12_v2(const Mode12Params p, con
                         for (int ks = 0; ks < KS; ks++) {
                             const bf16x8 ah = afrag[(0 * KS + ks) * SUBI + si], am = afrag[(1 * KS + ks) * SUBI + si];
                             const bf16x8 bh = bfrag[(0 * KS + ks) * NSJ + sj], bm = bfrag[(1 * KS + ks) * NSJ + sj];
-                            if (NV == 3) {
-                                const bf16x8 al = afrag[((NV - 1) * KS + ks) * SUBI + si], bl = bfrag[((NV - 1) * KS + ks) * NSJ + sj];
-                                // smallest terms first
-                                c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al, bh, c, 0, 0, 0);
-                                c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah, bl, c, 0, 0, 0);
-                                c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(am, bm, c, 0, 0, 0);
-                            }
-                            c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(am, bh, c, 0, 0, 0);
-                            c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah, bm, c, 0, 0, 0);
-                            c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah, bh, c, 0, 0, 0);
+                            // smallest terms first
+                            c = gen_piece<T>::mfma(am, bh, c);
+                            c = gen_piece<T>::mfma(ah, bm, c);
+                            c = gen_piece<T>::mfma(ah, bh, c);
                         }
                         accx[si * NSJ + sj] = c;
                     }
@@ -301,19 +319,20 @@ __global__ __launch_bounds__(64 * NW) void k_mode12_v2(const Mode12Params p, con
     }
 }
 
-// A (I x R, column-major, fp32) -> bf16 pieces [NV][Irows][Rpad], zero padded
-__global__ void k_split_a(const float *A, int64_t I, int R, __bf16 *out, int64_t Irows, int Rpad, int NV)
+// A (I x R, column-major, fp32) -> the generator's two 16-bit pieces [2][Irows][Rpad] (bf16 pieces for bf16 plans,
+// fp16 pieces for fp32 plans), zero padded
+template <typename T>
+__global__ void k_split_a(const float *A, int64_t I, int R, __bf16 *out, int64_t Irows, int Rpad)
 {
     const int64_t n = Irows * Rpad;
     for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < n; idx += (int64_t)gridDim.x * blockDim.x) {
         const int64_t i = idx / Rpad;
         const int r = (int)(idx % Rpad);
         const float v = (i < I && r < R) ? A[i + I * r] : 0.0f;
-        __bf16 h, m, l;
-        split3(v, h, m, l);
+        __bf16 h, m;
+        gen_piece<T>::split(v, h, m);
         out[idx] = h;
         out[n + idx] = m;
-        if (NV == 3) out[2 * n + idx] = l;
     }
 }
 

@@ -43,16 +43,16 @@ struct Mode12V3Cfg {
 };
 
 template <typename T> struct gen_terms;
-// a = a_h + a_m (+ a_l): index 0 = h, 1 = m, 2 = l.  Smallest products first.
+// a = a_h + a_m: index 0 = h, 1 = m (bf16 pieces for bf16 plans, fp16 pieces for fp32 plans: gen_piece).  Smallest products first.
 template <> struct gen_terms<__bf16> {
     static constexpr int N = 3;
     static constexpr int A[3] = {1, 0, 0};
     static constexpr int B[3] = {0, 1, 0};
 };
 template <> struct gen_terms<float> {
-    static constexpr int N = 6;
-    static constexpr int A[6] = {2, 0, 1, 1, 0, 0};
-    static constexpr int B[6] = {0, 2, 1, 0, 1, 0};
+    static constexpr int N = 3;
+    static constexpr int A[3] = {1, 0, 0};
+    static constexpr int B[3] = {0, 1, 0};
 };
 
 template <int... Ms, typename F>
@@ -177,20 +177,19 @@ __global__ __launch_bounds__(64 * NW, WPS) void k_mode12_v3(const Mode12Params p
                 amp[sj] = colok ? p.amp2_ln2 : 0.0f;
 #pragma unroll
                 for (int ks = 0; ks < KS; ks++) {
-                    bf16x8 bh, bm, bl;
+                    bf16x8 bh, bm;
 #pragma unroll
                     for (int e = 0; e < 8; e++) {
                         // clamped, unconditional loads (no branch per element), masked afterwards
                         const int r = 32 * ks + 8 * q16 + e, rr = r < p.R ? r : p.R - 1;
                         float bc = ld_chk<CHECKED>(p.B + jj + p.ldB * rr, ck, CHK_B) * ld_chk<CHECKED>(p.C + k + p.ldC * rr, ck, CHK_C);
                         bc = (colok && r < p.R) ? bc : 0.0f;
-                        __bf16 h, m, l;
-                        split3(bc, h, m, l);
-                        bh[e] = h; bm[e] = m; bl[e] = l;
+                        __bf16 h, m;
+                        gen_piece<T>::split(bc, h, m);
+                        bh[e] = h; bm[e] = m;
                     }
                     bfrag[(0 * KS + ks) * NSJ + sj] = bh;
                     bfrag[(1 * KS + ks) * NSJ + sj] = bm;
-                    if (NV == 3) bfrag[((NV - 1) * KS + ks) * NSJ + sj] = bl;
                 }
             }
         }
@@ -229,7 +228,7 @@ __global__ __launch_bounds__(64 * NW, WPS) void k_mode12_v3(const Mode12Params p
             const bf16x8 bv = bfrag[(gen_terms<T>::B[term] * KS + ks) * NSJ + sj];
             const f32x4v zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
             const f32x4v c = (term == 0 && ks == 0) ? zero4 : dst[sub];
-            dst[sub] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, bv, c, 0, 0, 0);
+            dst[sub] = gen_piece<T>::mfma(av, bv, c);
         };
         // quad q of stage s: X = low rank (in xin) + noise, masked, converted and written to LDS buffer `base`
         auto store_quad = [&](unsigned char *base, int q, int64_t ib, const float *z, const f32x4v &lr) {
@@ -398,7 +397,7 @@ __global__ __launch_bounds__(64 * NW, WPS) void k_mode12_v3(const Mode12Params p
         float *Zs = (float *)smem + wave * (32 * ZST);
         const bool first_chunk = (jc == ja0);
         if constexpr (ZT) {
-            static_assert(!ZT || (sizeof(T) == 4 && SRC == SRC_MATERIALISED && !CHECKED), "ZT: fp32 materialised source only");
+            static_assert(!ZT || (sizeof(T) == 4 && !CHECKED), "ZT: fp32, unchecked only");
             if (p.MT == 2) mode2_direct<RT, CT, 2>(p, p.Vd, acc, wrow0, kidx, jc, first_chunk, tid & 63);
             else mode2_direct<RT, CT, 1>(p, p.Vd, acc, wrow0, kidx, jc, first_chunk, tid & 63);
         } else if (p.MT == 2) mode2_chunk<RT, CT, CHECKED, 2, sizeof(T) == 2 ? VM_BF16 : VM_F32>(p, uf.Vf, ck, Zs, acc, wrow0, kidx, jc, first_chunk, tid & 63);
