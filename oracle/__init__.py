@@ -273,3 +273,20 @@ def cp_reconstruct(A, B, C):
     """sum_r a_r o b_r o c_r (Eq. 1) as a float64 (L, M, N) array."""
     return np.einsum("lr,mr,nr->lmn", np.asarray(A, dtype=np.float64), np.asarray(B, dtype=np.float64),
                      np.asarray(C, dtype=np.float64))
+
+
+# ---- joining the replicas: the stacked least-squares problem of Eq. 4 ------------------------------
+# After the P decompositions (and the alignment of their columns) the factor of the full tensor solves
+#   [A_1; ...; A_P] = [U_1; ...; U_P] X        (PL x R) = (PL x I)(I x R),   X = A Pi Sigma,
+# in the least-squares sense.  The definition written out: the minimiser of the Frobenius norm of the
+# residual, by numpy's SVD-based routine in fp64.
+
+def stacked_ls(Us, Astack):
+    """Us: (P, L, I) compression matrices of one mode; Astack: (P*L, R), the replica factors stacked in
+    replica order.  Returns the float64 (I, R) minimiser of ||[U_1;...;U_P] X - Astack||_F."""
+    Us = np.asarray(Us, dtype=np.float64)
+    P, L, I = Us.shape
+    Astack = np.asarray(Astack, dtype=np.float64)
+    if Astack.shape[0] != P * L:
+        raise ValueError("Astack must have P*L rows")
+    return np.linalg.lstsq(Us.reshape(P * L, I), Astack, rcond=None)[0]
