@@ -248,6 +248,30 @@ int64_t exat_cpals_workspace_floats(int32_t L, int32_t M, int32_t N, int32_t P);
 int exat_cpals(const float *Y, int32_t L, int32_t M, int32_t N, int32_t P, int32_t R, int32_t sweeps,
                float *A, float *B, float *C, float *work, void *stream);
 
+/* ---- joining the replicas: the stacked least-squares problem (Eq. 4) -------------------------------------
+ * After the P decompositions and the alignment of their columns, the factor of the full tensor (up to one common
+ * permutation and scaling, A Pi Sigma in the paper's notation) is the least-squares solution X (I x R) of
+ *   [A_1; ...; A_P] = [U_1; ...; U_P] X
+ * with the stacked P*L x I compression matrix of that mode.  exat_ls runs `iters` iterations of the conjugate
+ * gradient method on the normal equations (CGLS) from X = 0, in fp32, all columns at once, reading the stacked
+ * matrix in place.  A column is left as it is once its normal-equation residual ||U^T (A - U X)|| has fallen to
+ * `tol` times its start value ||U^T A|| (in fp32 the iteration drifts away again if it runs on past convergence;
+ * 1e-6 is a good value, below about 3e-7 the test never triggers; 0 switches it off).  The host never waits: all
+ * `iters` iterations are launched, the caller may read back `relres`.
+ *   U       device, the stacked matrix as exat_set_factors takes it: row p*L + l is row l of U_p; row-major,
+ *           leading dimension ldU >= I in elements; not modified
+ *   Astack  device, P*L x R in the layout exat_cpals writes: A[l + L*(r + R*p)]; not modified
+ *   X       device, out: I x R column-major, X[i + I*r]
+ *   relres  device, out, R floats, or NULL: per column ||U^T (A - U X)|| / ||U^T A|| after the last iteration
+ *   work    device scratch of exat_ls_workspace_floats(P, L, I, R) floats, caller-owned
+ * The system must have full column rank (P*L >= I); the iteration count for a given accuracy grows with the
+ * condition number of the stacked matrix (about 30 iterations to tol = 1e-6 at P*L = 2 I with Gaussian
+ * matrices; a square system, P*L = I, is out of reach of fp32).  Limits: R <= 64, P*L and I <= 2^24.
+ * Asynchronous on `stream`.  Errors: NULL, SHAPE, HIP. */
+int64_t exat_ls_workspace_floats(int32_t P, int32_t L, int32_t I, int32_t R);
+int exat_ls(const float *U, int64_t ldU, int32_t P, int32_t L, int32_t I, const float *Astack, int32_t R,
+            int32_t iters, float tol, float *X, float *relres, float *work, void *stream);
+
 /* Static description of a status code (never NULL). */
 const char *exat_strerror(int status);
 

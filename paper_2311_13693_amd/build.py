@@ -14,6 +14,7 @@ UNITS = {
                  "exat_mode12_v3.h", "exat_mode12_split.h", "exat_aux.h"],
     "exat_stage1.hip": [],
     "exat_cpals.hip": [],
+    "exat_ls.hip": [],
 }
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-w",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -18,7 +18,7 @@ EXPORTS = ["exat_plan_create", "exat_plan_destroy", "exat_set_factors", "exat_co
            "exat_plan_set_timing", "exat_plan_last_timing", "exat_plan_check_status",
            "exat_stage1_create", "exat_stage1_destroy", "exat_stage1_dims", "exat_stage1_apply", "exat_stage1_apply_host",
            "exat_stage1_set_timing", "exat_stage1_last_timing", "exat_cpals_workspace_floats", "exat_cpals",
-           "exat_strerror"]
+           "exat_ls_workspace_floats", "exat_ls", "exat_strerror"]
 
 
 class Desc(ctypes.Structure):
@@ -93,6 +93,7 @@ def lib():
         for name in EXPORTS[:-1]:
             getattr(L, name).restype = ctypes.c_int
         L.exat_cpals_workspace_floats.restype = ctypes.c_int64
+        L.exat_ls_workspace_floats.restype = ctypes.c_int64
         _lib = L
     return _lib
 
@@ -290,3 +291,22 @@ def cpals(Y, L, M, N, P, R, sweeps, A, B, C, work=None, stream=None):
         work = torch.empty(lib().exat_cpals_workspace_floats(L, M, N, P), dtype=torch.float32, device="cuda")
     _check(lib().exat_cpals(_ptr(Y), L, M, N, P, R, sweeps, _ptr(A), _ptr(B), _ptr(C), _ptr(work), _stream_handle(stream)))
     return A, B, C
+
+
+def ls(U, P, L, I, Astack, R, iters, tol=1e-6, X=None, relres=None, work=None, stream=None):
+    """Stacked least squares of Eq. 4 (CGLS, at most `iters` iterations from zero, columns frozen at relative
+    normal-equation residual `tol`).  U: float32 CUDA tensor holding the
+    stacked (P*L, I) matrix row-major (its stride(0) is the leading dimension); Astack: P*L*R floats in the layout
+    cpals writes.  Returns (X, relres): X as I*R floats column-major, relres R floats."""
+    import torch
+    assert U.is_cuda and U.dtype == torch.float32 and U.dim() == 2 and U.stride(1) == 1 and tuple(U.shape) == (P * L, I)
+    assert Astack.is_cuda and Astack.dtype == torch.float32 and Astack.is_contiguous() and Astack.numel() == P * L * R
+    if X is None:
+        X = torch.empty(I * R, dtype=torch.float32, device="cuda")
+    if relres is None:
+        relres = torch.empty(R, dtype=torch.float32, device="cuda")
+    if work is None:
+        work = torch.empty(lib().exat_ls_workspace_floats(P, L, I, R), dtype=torch.float32, device="cuda")
+    _check(lib().exat_ls(_ptr(U), ctypes.c_int64(U.stride(0)), P, L, I, _ptr(Astack), R, iters, ctypes.c_float(tol), _ptr(X), _ptr(relres),
+                         _ptr(work), _stream_handle(stream)))
+    return X, relres

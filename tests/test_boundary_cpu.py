@@ -102,3 +102,20 @@ def test_cpals_argument_errors():
     assert L.exat_cpals(p, 2, 2, 2, 1, 1, -1, p, p, p, p, None) == exat.ERR_SHAPE
     assert L.exat_cpals_workspace_floats(3, 4, 5, 6) >= 2 * 3 * 4 * 5 * 6      # two copies of Y plus partial results
     assert L.exat_cpals_workspace_floats(0, 4, 5, 6) == 0
+
+
+def test_ls_argument_errors():
+    # validation happens before the first HIP call; the non-null pointers are never dereferenced
+    L = exat.lib()
+    p = ctypes.c_void_p(256)
+    ld = ctypes.c_int64(8)
+    tol = ctypes.c_float(1e-6)
+    assert L.exat_ls(None, ld, 2, 4, 8, p, 2, 1, tol, p, p, p, None) == exat.ERR_NULL
+    assert L.exat_ls(p, ld, 2, 4, 8, p, 2, 1, tol, p, None, None, None) == exat.ERR_NULL     # relres may be NULL, work not
+    assert L.exat_ls(p, ctypes.c_int64(7), 2, 4, 8, p, 2, 1, tol, p, p, p, None) == exat.ERR_SHAPE   # ldU < I
+    assert L.exat_ls(p, ld, 2, 4, 8, p, 65, 1, tol, p, p, p, None) == exat.ERR_SHAPE
+    assert L.exat_ls(p, ld, 0, 4, 8, p, 2, 1, tol, p, p, p, None) == exat.ERR_SHAPE
+    assert L.exat_ls(p, ld, 2, 4, 8, p, 2, -1, tol, p, p, p, None) == exat.ERR_SHAPE
+    assert L.exat_ls(p, ld, 2, 4, 8, p, 2, 1, ctypes.c_float(-1.0), p, p, p, None) == exat.ERR_SHAPE
+    assert L.exat_ls_workspace_floats(2, 4, 8, 2) >= 4 * 8 * 2 + 3 * 8 * 2
+    assert L.exat_ls_workspace_floats(2, 4, 8, 65) == 0
