@@ -49,6 +49,10 @@ def parse():
                     help="the decomposition stage on the configuration's proxy tensors: 10 sweeps of batched CP-ALS (Alg. 1) "
                          "over the P tensors of L x M x N that the compression of the same synthetic tensor produced (fp32 "
                          "materialised configurations); value then counts proxy-tensor elements swept per second")
+    ap.add_argument("--ls", action="store_true",
+                    help="the join of the replicas: the stacked least-squares solves of Eq. 4 for the three modes, on the "
+                         "configuration's own stacked compression matrices (needs P*L >= 1.5 I: cfg3); value then counts "
+                         "matrix elements streamed per second (two passes over the stacked matrix per iteration)")
     return ap.parse_args()
 
 
@@ -139,6 +143,82 @@ def cpals(args):
                                "sample": "replicas 0..%d of %d, %d sweeps each (numpy fp64), scaled to all replicas" % (nrep - 1, P, SWEEPS),
                                "seconds_full": t, "extrapolated": nrep < P}
     plan.close()
+    print(json.dumps(out))
+
+
+def ls(args):
+    """One step = the three stacked least-squares solves (Eq. 4) that join the replicas' factors, one per mode."""
+    import torch
+    from paper_2311_13693_amd import exat, workloads as wl
+    ITERS, TOL = 40, 1e-6
+    cfg = wl.CONFIGS[args.config]
+    if 2 * cfg.P * cfg.L < 3 * cfg.I:
+        print("bench.py --ls: %s stacks %d rows for %d unknowns; the fp32 iteration needs P*L >= 1.5 I (use cfg3)"
+              % (cfg.name, cfg.P * cfg.L, cfg.I), file=sys.stderr)
+        sys.exit(2)
+    steps = args.steps if args.steps is not None else 20
+    warmup = args.warmup if args.warmup is not None else 3
+    torch.cuda.set_device(0)
+    P, R = cfg.P, cfg.R
+    dims = ((cfg.L, cfg.I), (cfg.M, cfg.J), (cfg.N, cfg.K))
+    rng = np.random.default_rng(cfg.seed & 0xFFFFFFFF)
+    mats, stacks, hosts = [], [], []
+    for Uh, Fh, (Ld, Id) in zip(wl.compression_matrices(cfg), wl.cp_factors(cfg), dims):
+        # replica factors U_p A (the Kronecker property) plus estimation noise, in the layout the CP-ALS writes
+        Ah = Uh.astype(np.float64) @ Fh.astype(np.float64)
+        Ah = (Ah + 0.05 * np.abs(Ah).mean() * rng.standard_normal(Ah.shape)).astype(np.float32)
+        flat = np.concatenate([Ah[p * Ld:(p + 1) * Ld].reshape(-1, order="F") for p in range(P)])
+        mats.append(torch.from_numpy(np.ascontiguousarray(Uh, dtype=np.float32)).cuda())
+        stacks.append(torch.from_numpy(flat).cuda())
+        hosts.append((Uh, Ah))
+    Xs = [torch.empty(Id * R, dtype=torch.float32, device="cuda") for _, Id in dims]
+    rel = [torch.empty(R, dtype=torch.float32, device="cuda") for _ in dims]
+    works = [torch.empty(exat.lib().exat_ls_workspace_floats(P, Ld, Id, R), dtype=torch.float32, device="cuda") for Ld, Id in dims]
+
+    def step():
+        for (Ld, Id), Ud, Ad, Xd, rd, wk in zip(dims, mats, stacks, Xs, rel, works):
+            exat.ls(Ud, P, Ld, Id, Ad, R, ITERS, TOL, Xd, rd, wk)
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()                                   # the library's kernels run on torch's current stream
+    for _ in range(steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    ms_step = e0.elapsed_time(e1) / steps
+    passes = 2 * ITERS + 1
+    elements = sum(P * Ld * Id for Ld, Id in dims) * passes
+    achieved = 4.0 * elements / (ms_step * 1e-3) / 1e9
+    out = {
+        "metric": "input tensor elements compressed/sec + TTM TFLOP/s (% MFMA peak), 1 MI355X",
+        "value": elements / (ms_step * 1e-3), "unit": "elements/s",
+        "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "%s join of the replicas: stacked least squares (Eq. 4) for the three modes, %d x %d matrices, "
+                               "%d right-hand sides, %d CGLS iterations each; elements = matrix elements x passes over the matrix"
+                               % (cfg.name, P * cfg.L, cfg.I, R, ITERS)},
+        "kernel_ms": {"all_launches": ms_step, "per_iteration": ms_step / (3 * ITERS)},
+        "relres_max": max(float(r.max()) for r in rel),
+        "roofline": {"bound": "hbm", "kernel": "k_ls_up + k_ls_down", "achieved": achieved, "peak": 8000.0, "unit": "GB/s",
+                     "frac": achieved / 8000.0, "traffic": None},
+    }
+    if args.check or not args.no_cpu_baseline:
+        import oracle
+        from threadpoolctl import threadpool_info
+        errs, t = [], 0.0
+        for (Uh, Ah), (Ld, Id), Xd in zip(hosts, dims, Xs):
+            t0 = time.perf_counter()
+            ref = oracle.stacked_ls(Uh.reshape(P, Ld, Id), Ah)
+            t += time.perf_counter() - t0
+            got = Xd.cpu().numpy().astype(np.float64).reshape((Id, R), order="F")
+            errs.append(float(np.linalg.norm(got - ref) / np.linalg.norm(ref)))
+        out["check"] = {"worst_rel_fro_vs_oracle": max(errs)}
+        cores = max([int(lib.get("num_threads", 1)) for lib in threadpool_info()] + [1])
+        out["cpu_baseline"] = {"value": elements / t, "unit": "elements/s", "cores": cores, "kind": "oracle",
+                               "sample": "the same three solves (numpy lstsq, fp64), counted with the GPU's element figure",
+                               "seconds_full": t, "extrapolated": False}
     print(json.dumps(out))
 
 
@@ -286,6 +366,8 @@ def main():
         return two_stage(args)
     if args.cpals:
         return cpals(args)
+    if args.ls:
+        return ls(args)
     import torch
     from paper_2311_13693_amd import exat, workloads as wl
     cfg = wl.CONFIGS[args.config]

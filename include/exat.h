@@ -266,7 +266,7 @@ int exat_cpals(const float *Y, int32_t L, int32_t M, int32_t N, int32_t P, int32
  *   work    device scratch of exat_ls_workspace_floats(P, L, I, R) floats, caller-owned
  * The system must have full column rank (P*L >= I); the iteration count for a given accuracy grows with the
  * condition number of the stacked matrix (about 30 iterations to tol = 1e-6 at P*L = 2 I with Gaussian
- * matrices; a square system, P*L = I, is out of reach of fp32).  Limits: R <= 64, P*L and I <= 2^24.
+ * matrices; a square system, P*L = I, is out of reach of fp32).  Limits: R <= 64, P*L and I <= 2^22, P*L*ldU <= 2^30.
  * Asynchronous on `stream`.  Errors: NULL, SHAPE, HIP. */
 int64_t exat_ls_workspace_floats(int32_t P, int32_t L, int32_t I, int32_t R);
 int exat_ls(const float *U, int64_t ldU, int32_t P, int32_t L, int32_t I, const float *Astack, int32_t R,
