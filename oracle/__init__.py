@@ -5,8 +5,9 @@ cpu_baseline leg may import this package; the product (the HIP library and its
 Python binding) never does, and this package never imports the product.
 
 Every function is a numpy-facing wrapper over oracle/exat_oracle.c (plain C,
-fp64 accumulation), except the two-stage functions (Sec. 4.4) and the CP-ALS of the
-proxy tensors (Alg. 1) at the end, which are plain numpy in fp64.
+fp64 accumulation), except the two-stage functions (Sec. 4.4), the CP-ALS of the
+proxy tensors (Alg. 1) and the stacked least squares (Eq. 4) at the end, which are
+plain numpy in fp64.
 
 Conventions (paper Sec. 3, Eq. 3 and Sec. 4.1):
   X   float32 array of shape (I, J, K), Fortran (column-major) order
