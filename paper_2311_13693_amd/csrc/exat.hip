@@ -292,9 +292,9 @@ int run_chain(exat_plan_s *pl, Mode12Params mp, bool generated, float *Yout, int
     } else if (pipelined) {
         const bool boxed = generated && (mp.i0 != 0 || mp.i1 != pl->d.I);
         const int ks = gs.Rpad / 32;
-        // Fragment-ordered U (k_mode12_v3): every materialised source and the bf16 generator.  The fp32
-        // generator keeps the LDS-staged kernel (k_mode12_v2): its 8-wave build of the other one spills in
-        // the stage loop.
+        // Fragment-ordered U (k_mode12_v3): every materialised source, the bf16 generator and the 8-wave fp32
+        // generator.  `frag` only selects which buffers the bounds-checked variants validate against; those are
+        // bf16 generator kernels or the LDS-staged fp32 one (k_mode12_v2).
         const bool frag = !generated || bf;
         CheckParams ck;
         memset(&ck, 0, sizeof(ck));
