@@ -63,8 +63,8 @@ def cpals(args):
     SWEEPS = 10
     cfg = wl.CONFIGS[args.config]
     assert cfg.materialised and cfg.dtype == "f32", "--cpals needs a materialised fp32 configuration"
-    steps = args.steps if args.steps is not None else 10
-    warmup = args.warmup if args.warmup is not None else 2
+    steps = args.steps if args.steps is not None else 50
+    warmup = args.warmup if args.warmup is not None else 50      # warm up for ~50 ms of load: the chip's clock settles under load
     torch.cuda.set_device(0)
     A, B, C = wl.cp_factors(cfg)
     U, V, W = wl.compression_matrices(cfg)
@@ -156,8 +156,8 @@ def ls(args):
         print("bench.py --ls: %s stacks %d rows for %d unknowns; the fp32 iteration needs P*L >= 1.5 I (use cfg3)"
               % (cfg.name, cfg.P * cfg.L, cfg.I), file=sys.stderr)
         sys.exit(2)
-    steps = args.steps if args.steps is not None else 20
-    warmup = args.warmup if args.warmup is not None else 3
+    steps = args.steps if args.steps is not None else 30
+    warmup = args.warmup if args.warmup is not None else 30
     torch.cuda.set_device(0)
     P, R = cfg.P, cfg.R
     dims = ((cfg.L, cfg.I), (cfg.M, cfg.J), (cfg.N, cfg.K))
@@ -229,8 +229,8 @@ def two_stage(args):
     cfg = wl.CONFIGS[args.config]
     assert cfg.materialised and cfg.dtype == "f32", "--two-stage needs a materialised fp32 configuration"
     ts = wl.TwoStage(cfg)
-    steps = args.steps if args.steps is not None else (5 if cfg.elements > 5e8 else 20)
-    warmup = args.warmup if args.warmup is not None else 3
+    steps = args.steps if args.steps is not None else (20 if cfg.elements > 5e8 else 200)
+    warmup = args.warmup if args.warmup is not None else (20 if cfg.elements > 5e8 else 200)
     torch.cuda.set_device(0)
     A, B, C = wl.cp_factors(cfg)
     dev = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
@@ -372,8 +372,11 @@ def main():
     from paper_2311_13693_amd import exat, workloads as wl
     cfg = wl.CONFIGS[args.config]
     big = cfg.elements > 5e10
-    steps = args.steps if args.steps is not None else (2 if big else (5 if cfg.elements > 5e8 else 20))
-    warmup = args.warmup if args.warmup is not None else (1 if big else 3)
+    # A pass over the small configurations takes about a millisecond, and the chip needs some 50 ms of load before
+    # its clock has settled (cfg2: 1.18 ms per pass after 3 warm-up passes, 1.105 ms after 50 or more), so their
+    # defaults warm up for ~100 ms and time as long again.
+    steps = args.steps if args.steps is not None else (2 if big else (5 if cfg.elements > 5e8 else 100))
+    warmup = args.warmup if args.warmup is not None else (1 if big else (3 if cfg.elements > 5e8 else 100))
 
     torch.cuda.set_device(0)
     A, B, C = wl.cp_factors(cfg)

@@ -135,6 +135,11 @@ __global__ __launch_bounds__(64 * NW, WPS) void k_mode12_v3(const Mode12Params p
     uint32_t ckey[NSJ];
     float amp[NSJ];
 
+    // materialised source: the X tile of the next chunk's first stage, requested before the mode-2 phase of this
+    // chunk so that the memory latency of the chunk start lies behind it (the second tile of the prologue as well
+    // measured no faster and cost registers)
+    u32x4 xnext[SRC == SRC_MATERIALISED ? XPT : 1];
+    bool have_next = false;
     for (int64_t jc = ja0; jc < p.j1; jc += COLS) {
         // Per-lane offsets and pointers of the stage loop are derived again in every chunk from a copy of the
         // thread id the compiler cannot see through.  Kept live across chunks they would sit in registers during
@@ -361,7 +366,13 @@ __global__ __launch_bounds__(64 * NW, WPS) void k_mode12_v3(const Mode12Params p
         }
         if constexpr (SRC == SRC_MATERIALISED) {
 #pragma unroll
-            for (int d = 0; d < DX; d++) load_x(d, xpre[d]);
+            for (int d = 0; d < DX; d++) {
+                if (d == 0 && have_next) {
+#pragma unroll
+                    for (int u = 0; u < XPT; u++) xpre[0][u] = xnext[u];
+                } else
+                    load_x(d, xpre[d]);
+            }
         }
         load_a(0, afrag[0]);
         if constexpr (NAB == 2) load_a(1, afrag[1]);
@@ -393,6 +404,19 @@ __global__ __launch_bounds__(64 * NW, WPS) void k_mode12_v3(const Mode12Params p
             }
         });
 
+        if constexpr (SRC == SRC_MATERIALISED) {
+            have_next = jc + COLS < p.j1;
+            if (have_next) {
+                const T *xb = (const T *)p.X + stage_i(0);
+#pragma unroll
+                for (int u = 0; u < XPT; u++) {
+                    const int64_t j = jc + COLS + pr0 + PSTEP * u;
+                    u32x4 v = {0u, 0u, 0u, 0u};
+                    if (j >= p.j0 && j < p.j1) v = *(const u32x4 *)(xb + (pf * E16 - p.xo_i) + (j - p.xo_j) * p.x_sj + (k - p.xo_k) * p.x_sk);
+                    xnext[u] = v;
+                }
+            }
+        }
         // ---- mode 2 on the finished Z chunk ----
         float *Zs = (float *)smem + wave * (32 * ZST);
         const bool first_chunk = (jc == ja0);

@@ -211,42 +211,54 @@ __device__ __forceinline__ void mode2_chunk(const Mode12Params &p, const void *V
 // tile with no trip through LDS.  V comes in the matching order (k_pack_v_direct): [p][mt][j/32][b][lane][r] holds
 // V_p[32 mt + l%32][32 (j/32) + 8b + 4(l/32) + r].  Requires L % 32 == 0 (a tile of 32 rows q lies in one
 // replica) and fp32 data.  Q keeps its layout [k][q][m]: a lane owns one row q and writes 16-byte pieces of it.
+// The RT * MTC output tiles are taken one after the other in steps of one column tile ct (16 MFMAs); the V
+// fragments of a step are requested three steps ahead (a ring of four register sets), so that after the first
+// step the requests are always in flight behind the matrix instructions, also across the stores of a finished tile.
 template <int RT, int CT, int MTC>
 __device__ __forceinline__ void mode2_direct(const Mode12Params &p, const float *Vd, const f32x16 (&acc)[RT][CT], int wrow0, int kidx,
                                              int64_t jc, bool first_chunk, int lane)
 {
     constexpr int MP = 32 * MTC;   // = p.Mpad
+    constexpr int NS = RT * MTC * CT, AHEAD = 3;
     const int l32 = lane & 31, hi = lane >> 5;
     const int64_t nj32 = p.Jpad / 32;
-#pragma unroll
-    for (int rt = 0; rt < RT; rt++) {
-        const int q0 = wrow0 + rt * 32;   // wave-uniform
+    f32x4 v[AHEAD + 1][4];
+    f32x4 qold[4];
+    f32x16 d;
+    // step s = ((rt * MTC + mt) * CT + ct); a row tile beyond the stacked rows is skipped (wave-uniform)
+    auto load_step = [&](int s) {
+        const int rt = s / (MTC * CT), mt = (s / CT) % MTC, ct = s % CT;
+        const int q0 = wrow0 + rt * 32;
         if (q0 < p.PL) {
             const int pr = q0 / p.L;
+            const f32x4 *vf = (const f32x4 *)Vd + (((int64_t)pr * MTC + mt) * nj32 + jc / 32) * (4 * 64) + lane;
 #pragma unroll
-            for (int mt = 0; mt < MTC; mt++) {
-                // this lane's 16 values of row q of Q (4 pieces of 4 consecutive m), requested before the MFMAs
-                float *Qt = p.Q + ((int64_t)kidx * p.PLpad + q0 + l32) * MP + 32 * mt + 4 * hi;   // + 8*b
-                f32x4 qold[4];
+            for (int b = 0; b < 4; b++) v[s % (AHEAD + 1)][b] = vf[(ct * 4 + b) * 64];
+        }
+    };
 #pragma unroll
-                for (int b = 0; b < 4; b++) qold[b] = first_chunk ? f32x4{0.0f, 0.0f, 0.0f, 0.0f} : *(const f32x4 *)(Qt + 8 * b);
-                const f32x4 *vf = (const f32x4 *)Vd + (((int64_t)pr * MTC + mt) * nj32 + jc / 32) * (4 * 64) + lane;   // + (ct*4 + b)*64
-                f32x4 v[CT][4];
+    for (int s = 0; s < AHEAD && s < NS; s++) load_step(s);
 #pragma unroll
-                for (int ct = 0; ct < CT; ct++)
+    for (int s = 0; s < NS; s++) {
+        const int rt = s / (MTC * CT), mt = (s / CT) % MTC, ct = s % CT;
+        const int q0 = wrow0 + rt * 32;
+        // this lane's 16 values of row q of Q (4 pieces of 4 consecutive m)
+        float *Qt = p.Q + ((int64_t)kidx * p.PLpad + q0 + l32) * MP + 32 * mt + 4 * hi;   // + 8*b
+        if (s + AHEAD < NS) load_step(s + AHEAD);
+        if (ct == 0 && q0 < p.PL) {
 #pragma unroll
-                    for (int b = 0; b < 4; b++) v[ct][b] = vf[(ct * 4 + b) * 64];
-                __builtin_amdgcn_sched_barrier(0);   // all requests before the first MFMA
-                f32x16 d;
+            for (int b = 0; b < 4; b++) qold[b] = first_chunk ? f32x4{0.0f, 0.0f, 0.0f, 0.0f} : *(const f32x4 *)(Qt + 8 * b);
 #pragma unroll
-                for (int e = 0; e < 16; e++) d[e] = 0.0f;
+            for (int e = 0; e < 16; e++) d[e] = 0.0f;
+        }
+        __builtin_amdgcn_sched_barrier(0);   // the requests stay ahead of the MFMAs
+        if (q0 < p.PL) {
 #pragma unroll
-                for (int ct = 0; ct < CT; ct++)
+            for (int b = 0; b < 4; b++)
 #pragma unroll
-                    for (int b = 0; b < 4; b++)
-#pragma unroll
-                        for (int r = 0; r < 4; r++)
-                            d = __builtin_amdgcn_mfma_f32_32x32x2f32(v[ct][b][r], acc[rt][ct][4 * b + r], d, 0, 0, 0);
+                for (int r = 0; r < 4; r++)
+                    d = __builtin_amdgcn_mfma_f32_32x32x2f32(v[s % (AHEAD + 1)][b][r], acc[rt][ct][4 * b + r], d, 0, 0, 0);
+            if (ct == CT - 1) {
                 // d: register 4b+r of lane l is Q^T[m = 32 mt + 8b + 4(l/32) + r][q = q0 + l%32]
 #pragma unroll
                 for (int b = 0; b < 4; b++) {
