@@ -308,6 +308,9 @@ __global__ __launch_bounds__(64 * NW, WPS) void k_mode12_v3(const Mode12Params p
         // one stage: MFMAs of stage s (X tile in LDS buffer PH, A fragments in register set PH) interleaved with
         // the production of the X tile of stage s+1 (into the other buffer), the low-rank MFMAs of stage s+2 and
         // the reload of the A fragment registers for stage s+2
+        // fp32 materialised source: the stage barrier sits mid-stage (see stage); the bf16 build of that form spills
+        constexpr bool MIDBAR = SRC == SRC_MATERIALISED && sizeof(T) == 4;
+        frag_t bx0[MIDBAR ? CT : 1];   // first-group X fragments of the stage about to run
         auto stage = [&](auto sic, int s) {
             constexpr int SI = decltype(sic)::value;  // s mod UNR
             constexpr int PH = SI & 1, US = SI % DU, XS = (SI + 1) % DX;
@@ -315,6 +318,35 @@ __global__ __launch_bounds__(64 * NW, WPS) void k_mode12_v3(const Mode12Params p
             unsigned char *oth = smem + (PH ^ 1) * XBUF;
             const int64_t ib1 = stage_i(s + 1);
             const int64_t ig2 = stage_i(s + DU) / GI;
+            if constexpr (MIDBAR) {
+                // Materialised fp32 source: the tile of stage s+1 is complete in LDS as soon as every wave has stored its
+                // part at the start of stage s, so the stage's barrier sits between its two halves (the MFMAs of the
+                // first and of the second i group): the first-group fragments of stage s+1 are read right after it,
+                // behind the second half's MFMAs, and a wave that waits at the barrier leaves the matrix pipe to the
+                // other wave of its SIMD.  bx0 holds the first-group fragments of the current stage on entry.
+                frag_t bx1[CT];
+#pragma unroll
+                for (int ct = 0; ct < CT; ct++) bx1[ct] = *(const frag_t *)(cur + xs_r + ct * 32 * ROWB + 32);
+#pragma unroll
+                for (int u = 0; u < XPT; u++) *(u32x4 *)(oth + xs_w + u * PSTEP * ROWB) = xpre[XS][u];
+                load_x(s + 1 + DX, xpre[XS]);
+                __builtin_amdgcn_sched_barrier(0);
+                static_for<NMAIN>([&](auto mc) {
+                    constexpr int m = decltype(mc)::value, g2 = m / (RT * CT), rt = (m / CT) % RT, ct = m % CT;
+                    if constexpr (m == NMAIN / 2) {
+                        __syncthreads();
+#pragma unroll
+                        for (int c2 = 0; c2 < CT; c2++) bx0[c2] = *(const frag_t *)(oth + xs_r + c2 * 32 * ROWB);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    const frag_t &bxe = g2 == 0 ? bx0[ct] : bx1[ct];
+                    if constexpr (ZT) mma_frag<T>::mma(acc[rt][ct], bxe, ufr[US][rt][g2]);
+                    else mma_frag<T>::mma(acc[rt][ct], ufr[US][rt][g2], bxe);
+                    if constexpr (ct == CT - 1) ufr[US][rt][g2] = load_uf(rt, ig2 + g2);  // last use this stage: refill for stage s+DU
+                    __builtin_amdgcn_sched_barrier(0);
+                });
+                return;
+            }
             frag_t bx[2][CT];
 #pragma unroll
             for (int g2 = 0; g2 < 2; g2++)
@@ -391,18 +423,23 @@ __global__ __launch_bounds__(64 * NW, WPS) void k_mode12_v3(const Mode12Params p
         load_a(NAB == 2 ? 3 : 2, afrag[NAB - 1]);
         __syncthreads();
 
+        if constexpr (MIDBAR) {
+#pragma unroll
+            for (int ct = 0; ct < CT; ct++) bx0[ct] = *(const frag_t *)(smem + xs_r + ct * 32 * ROWB);
+        }
         int s = 0;
         for (; s + UNR <= nstage; s += UNR)
             static_for<UNR>([&](auto c) {
                 stage(c, s + decltype(c)::value);
-                __syncthreads();
+                if constexpr (!MIDBAR) __syncthreads();   // otherwise the stage has its barrier inside
             });
         static_for<UNR - 1>([&](auto c) {
             if (s + decltype(c)::value < nstage) {
                 stage(c, s + decltype(c)::value);
-                __syncthreads();
+                if constexpr (!MIDBAR) __syncthreads();
             }
         });
+        if constexpr (MIDBAR) __syncthreads();   // every wave is done with the X tiles in LDS
 
         if constexpr (SRC == SRC_MATERIALISED) {
             have_next = jc + COLS < p.j1;
