@@ -112,3 +112,19 @@ def test_zero_right_hand_side_column():
     X, relres = _solve(Us, flat, P, L, I, R, 40)
     assert np.all(np.isfinite(X)) and np.all(X[:, 2] == 0.0) and relres[2] == 0.0
     assert _rel(X, oracle.stacked_ls(Us, A)) <= TOL
+
+
+def test_unaligned_matrix_pointer():
+    # a stacked matrix that starts 4 bytes into an allocation: the 16-byte loads are off, every row tile and
+    # k step goes through the scalar path, at a size that spans several tiles
+    P, L, I, R = 4, 40, 72, 8
+    Us, A, flat = _problem(21, P, L, I, R)
+    ld = I + 3
+    buf = torch.full((P * L * ld + 1,), float("nan"), dtype=torch.float32).cuda()
+    view = buf[1:].view(P * L, ld)[:, :I]
+    view.copy_(torch.from_numpy(Us.reshape(P * L, I)))
+    assert view.data_ptr() % 16 != 0
+    X, relres = exat.ls(view, P, L, I, torch.from_numpy(flat).cuda(), R, 80)
+    torch.cuda.synchronize()
+    got = X.cpu().numpy().astype(np.float64).reshape((I, R), order="F")
+    assert _rel(got, oracle.stacked_ls(Us, A)) <= TOL
