@@ -21,7 +21,7 @@ PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}   # MI355X dense MFMA peaks
 # HBM-side bytes of one launch of the fused mode-1/2 kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE passes,
 # scaled by the same counters on a plain device copy (figures and commands: profiles/*_hbm_counters.txt).
 # Counter passes are separate runs, so this is a recorded value, not one measured by this script.
-TRAFFIC_BYTES = {"cfg2": 8.558e8, "cfg2_two_stage": 5.633e8}
+TRAFFIC_BYTES = {"cfg2": 8.598e8, "cfg2_two_stage": 5.633e8}
 
 
 def parse():
