@@ -171,10 +171,13 @@ int exat_plan_check_status(exat_plan_t plan, uint32_t *counters8);
 /* Measurement aid (not part of the paper's method): with timing enabled, every compress
  * call records HIP events on its stream around the fused mode-1/2 kernel and around the
  * mode-3 kernel.  exat_plan_last_timing waits for the most recent call's events and returns
- * the two kernel durations in milliseconds (the one call in this API that blocks).
- * Errors: NULL, STATE (timing off or no call since it was enabled), HIP. */
+ * the two kernel durations in milliseconds (these are the calls in this API that block).  The plan keeps
+ * the events of its last 128 calls: exat_plan_timing_of returns those of the call `age` calls back
+ * (0 = the most recent), so that a caller can enqueue many calls back to back and read their kernel
+ * times afterwards.  Errors: NULL, STATE (timing off, no such call since it was enabled, age >= 128), HIP. */
 int exat_plan_set_timing(exat_plan_t plan, int enable);
 int exat_plan_last_timing(exat_plan_t plan, float *ms_mode12, float *ms_mode3);
+int exat_plan_timing_of(exat_plan_t plan, int32_t age, float *ms_mode12, float *ms_mode3);
 
 /* ---- Two-stage compression (Sec. 4.4) --------------------------------------------------------------
  * The paper builds the compression matrices as U_p = U'_p U, V_p = V'_p V, W_p = W'_p W with sparse

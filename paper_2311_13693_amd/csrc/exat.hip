@@ -51,8 +51,11 @@ struct exat_plan_s {
     hipEvent_t ev_copied[kRing] = {nullptr, nullptr, nullptr}, ev_free[kRing] = {nullptr, nullptr, nullptr};
     bool ring_used[kRing] = {false, false, false};
     // optional per-kernel timing
-    bool timing = false, timing_valid = false;
-    hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
+    // a ring of event triples, one per compress call, so that a caller can time many calls without waiting in between
+    static constexpr int kTimeRing = 128;
+    bool timing = false;
+    int64_t timed_calls = 0;
+    hipEvent_t evr[kTimeRing][3] = {};
     __bf16 *Asplit = nullptr;  // the two 16-bit pieces of the generator's A factor (bf16 or fp16 bit patterns), [2][Ipad][64]
     unsigned *dbg = nullptr;   // 8 counters written by bounds-checked kernel variants
     size_t ub = 0, vb = 0, qb = 0, ab = 0;  // byte sizes of Upack, Vpack, Q, Asplit
@@ -276,7 +279,8 @@ int run_chain(exat_plan_s *pl, Mode12Params mp, bool generated, float *Yout, int
         else hipLaunchKernelGGL(k_split_a<float>, dim3(grid_for(n)), dim3(256), 0, st, mp.A, pl->d.I, mp.R, pl->Asplit, gs.Irows, gs.Rpad);
         if (hipGetLastError() != hipSuccess) return EXAT_ERR_HIP;
     }
-    if (pl->timing && hipEventRecord(pl->ev[0], st) != hipSuccess) return EXAT_ERR_HIP;
+    hipEvent_t *ev = pl->evr[pl->timed_calls % exat_plan_s::kTimeRing];
+    if (pl->timing && hipEventRecord(ev[0], st) != hipSuccess) return EXAT_ERR_HIP;
     if (split) {
         SplitParams sp;
         sp.Ufh = pl->Ufh; sp.Ufl = pl->Ufl; sp.nig = pl->Ipad / 16; sp.Vfh = pl->Vfh; sp.Vfl = pl->Vfl;
@@ -346,7 +350,7 @@ int run_chain(exat_plan_s *pl, Mode12Params mp, bool generated, float *Yout, int
     else
         rc = generated ? launch_mode12_f32<SRC_GENERATED>(rt, mp, nk, st) : launch_mode12_f32<SRC_MATERIALISED>(rt, mp, nk, st);
     if (rc != EXAT_OK) return rc;
-    if (pl->timing && hipEventRecord(pl->ev[1], st) != hipSuccess) return EXAT_ERR_HIP;
+    if (pl->timing && hipEventRecord(ev[1], st) != hipSuccess) return EXAT_ERR_HIP;
     Mode3Params m3;
     m3.Q = pl->Q; m3.W = pl->Wpack; m3.Y = Yout;
     m3.L = pl->d.L; m3.M = pl->d.M; m3.N = pl->d.N; m3.PL = pl->PL; m3.PLpad = pl->PLpad; m3.Mpad = pl->Mpad;
@@ -365,8 +369,8 @@ int run_chain(exat_plan_s *pl, Mode12Params mp, bool generated, float *Yout, int
     }
     if (hipGetLastError() != hipSuccess) return EXAT_ERR_HIP;
     if (pl->timing) {
-        if (hipEventRecord(pl->ev[2], st) != hipSuccess) return EXAT_ERR_HIP;
-        pl->timing_valid = true;
+        if (hipEventRecord(ev[2], st) != hipSuccess) return EXAT_ERR_HIP;
+        pl->timed_calls++;
     }
     return EXAT_OK;
 }
@@ -442,7 +446,8 @@ int exat_plan_destroy(exat_plan_t pl)
     (void)hipFree(pl->Upack); (void)hipFree(pl->Ufrag); (void)hipFree(pl->Vfrag);
     (void)hipFree(pl->Ufh); (void)hipFree(pl->Ufl); (void)hipFree(pl->Vfh); (void)hipFree(pl->Vfl); (void)hipFree(pl->Vpack); (void)hipFree(pl->Wpack); (void)hipFree(pl->Q);
     (void)hipFree(pl->slots); (void)hipFree(pl->used_dev); (void)hipFree(pl->Asplit); (void)hipFree(pl->dbg);
-    for (hipEvent_t e : pl->ev) if (e) (void)hipEventDestroy(e);
+    for (auto &tr : pl->evr)
+        for (hipEvent_t e : tr) if (e) (void)hipEventDestroy(e);
     delete pl;
     return EXAT_OK;
 }
@@ -666,23 +671,30 @@ int exat_plan_check_status(exat_plan_t pl, uint32_t *counters8)
 int exat_plan_set_timing(exat_plan_t pl, int enable)
 {
     if (!pl) return EXAT_ERR_NULL;
-    if (enable && !pl->ev[0]) {
-        for (hipEvent_t &e : pl->ev)
-            if (hipEventCreate(&e) != hipSuccess) return EXAT_ERR_HIP;
+    if (enable && !pl->evr[0][0]) {
+        for (auto &tr : pl->evr)
+            for (hipEvent_t &e : tr)
+                if (hipEventCreate(&e) != hipSuccess) return EXAT_ERR_HIP;
     }
     pl->timing = enable != 0;
-    pl->timing_valid = false;
+    pl->timed_calls = 0;
+    return EXAT_OK;
+}
+
+int exat_plan_timing_of(exat_plan_t pl, int32_t age, float *ms_mode12, float *ms_mode3)
+{
+    if (!pl || !ms_mode12 || !ms_mode3) return EXAT_ERR_NULL;
+    if (!pl->timing || age < 0 || age >= exat_plan_s::kTimeRing || age >= pl->timed_calls) return EXAT_ERR_STATE;
+    hipEvent_t *ev = pl->evr[(pl->timed_calls - 1 - age) % exat_plan_s::kTimeRing];
+    if (hipEventSynchronize(ev[2]) != hipSuccess) return EXAT_ERR_HIP;
+    if (hipEventElapsedTime(ms_mode12, ev[0], ev[1]) != hipSuccess) return EXAT_ERR_HIP;
+    if (hipEventElapsedTime(ms_mode3, ev[1], ev[2]) != hipSuccess) return EXAT_ERR_HIP;
     return EXAT_OK;
 }
 
 int exat_plan_last_timing(exat_plan_t pl, float *ms_mode12, float *ms_mode3)
 {
-    if (!pl || !ms_mode12 || !ms_mode3) return EXAT_ERR_NULL;
-    if (!pl->timing || !pl->timing_valid) return EXAT_ERR_STATE;
-    if (hipEventSynchronize(pl->ev[2]) != hipSuccess) return EXAT_ERR_HIP;
-    if (hipEventElapsedTime(ms_mode12, pl->ev[0], pl->ev[1]) != hipSuccess) return EXAT_ERR_HIP;
-    if (hipEventElapsedTime(ms_mode3, pl->ev[1], pl->ev[2]) != hipSuccess) return EXAT_ERR_HIP;
-    return EXAT_OK;
+    return exat_plan_timing_of(pl, 0, ms_mode12, ms_mode3);
 }
 
 const char *exat_strerror(int status)

@@ -15,7 +15,7 @@ OK, ERR_NULL, ERR_SHAPE, ERR_DTYPE, ERR_STATE, ERR_ALLOC, ERR_HIP = 0, -1, -2, -
 
 EXPORTS = ["exat_plan_create", "exat_plan_destroy", "exat_set_factors", "exat_compress",
            "exat_compress_block", "exat_finalize", "exat_compress_host", "exat_compress_gen", "exat_gen_block",
-           "exat_plan_set_timing", "exat_plan_last_timing", "exat_plan_check_status",
+           "exat_plan_set_timing", "exat_plan_last_timing", "exat_plan_timing_of", "exat_plan_check_status",
            "exat_stage1_create", "exat_stage1_destroy", "exat_stage1_dims", "exat_stage1_apply", "exat_stage1_apply_host",
            "exat_stage1_set_timing", "exat_stage1_last_timing", "exat_cpals_workspace_floats", "exat_cpals",
            "exat_ls_workspace_floats", "exat_ls", "exat_strerror"]
@@ -77,6 +77,7 @@ def lib():
         L.exat_gen_block.argtypes = [ctypes.POINTER(Desc), ctypes.POINTER(Gen), i32, i32, i32, vp, vp]
         L.exat_plan_set_timing.argtypes = [vp, ctypes.c_int]
         L.exat_plan_last_timing.argtypes = [vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_float)]
+        L.exat_plan_timing_of.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_float)]
         L.exat_plan_check_status.argtypes = [vp, ctypes.POINTER(ctypes.c_uint32)]
         L.exat_stage1_create.argtypes = [ctypes.POINTER(vp), i64, i64, i64, ctypes.POINTER(Csr), ctypes.POINTER(Csr),
                                          ctypes.POINTER(Csr)]
@@ -176,6 +177,12 @@ class Plan:
         """(ms of the fused mode-1/2 kernel, ms of the mode-3 kernel) of the most recent compress call."""
         a, b = ctypes.c_float(), ctypes.c_float()
         _check(lib().exat_plan_last_timing(self._h, ctypes.byref(a), ctypes.byref(b)))
+        return a.value, b.value
+
+    def timing_of(self, age):
+        """The same for the compress call `age` calls back (0 = the most recent, at most 127)."""
+        a, b = ctypes.c_float(), ctypes.c_float()
+        _check(lib().exat_plan_timing_of(self._h, int(age), ctypes.byref(a), ctypes.byref(b)))
         return a.value, b.value
 
     def check_status(self):

@@ -119,3 +119,10 @@ def test_ls_argument_errors():
     assert L.exat_ls(p, ld, 2, 4, 8, p, 2, 1, ctypes.c_float(-1.0), p, p, p, None) == exat.ERR_SHAPE
     assert L.exat_ls_workspace_floats(2, 4, 8, 2) >= 4 * 8 * 2 + 3 * 8 * 2
     assert L.exat_ls_workspace_floats(2, 4, 8, 65) == 0
+
+
+def test_timing_argument_errors():
+    L = exat.lib()
+    f = ctypes.c_float()
+    assert L.exat_plan_timing_of(None, 0, ctypes.byref(f), ctypes.byref(f)) == exat.ERR_NULL
+    assert L.exat_plan_last_timing(None, ctypes.byref(f), ctypes.byref(f)) == exat.ERR_NULL
