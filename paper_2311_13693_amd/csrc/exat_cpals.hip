@@ -106,7 +106,8 @@ __global__ __launch_bounds__(256) void k_cpals_solve(const CpUpdate p)
 {
     constexpr int RS = 4 * RW;
     __shared__ float F1[CP_MAX * RS], F2[CP_MAX * RS];
-    __shared__ float G[RS * (RS + 1)];        // normal matrix, then its Cholesky factor (row stride R+1)
+    __shared__ float G[RS * (RS + 1)];        // normal matrix, updated in place by the factorisation (row stride R+1)
+    __shared__ float Lf[RS * (RS + 1)];       // its Cholesky factor
     __shared__ float Mx[CP_MAX * (RS + 1)];   // MTTKRP result (row stride R+1)
     const int tid = threadIdx.x;
     const int64_t rep = blockIdx.x;
@@ -119,7 +120,14 @@ __global__ __launch_bounds__(256) void k_cpals_solve(const CpUpdate p)
         const int64_t st = (int64_t)D0 * R;
         float v = 0.0f;
         int sl = 0;
-        for (; sl + 8 <= p.NS; sl += 8) {   // eight loads in flight, added in slab order
+        for (; sl + 32 <= p.NS; sl += 32) {   // 32 loads in flight (a round trip to memory each), added in slab order
+            float t[32];
+#pragma unroll
+            for (int u = 0; u < 32; u++) t[u] = src[(sl + u) * st];
+#pragma unroll
+            for (int u = 0; u < 32; u++) v += t[u];
+        }
+        for (; sl + 8 <= p.NS; sl += 8) {
             float t[8];
 #pragma unroll
             for (int u = 0; u < 8; u++) t[u] = src[(sl + u) * st];
@@ -139,17 +147,16 @@ __global__ __launch_bounds__(256) void k_cpals_solve(const CpUpdate p)
         G[r * GS + c] = g1 * g2;
     }
     __syncthreads();
-    // Cholesky factor in the lower triangle of G, right-looking: per column, scale it, then every thread
-    // updates its share of the trailing triangle
+    // Cholesky factor, right-looking, one barrier per column: every thread scales the entries of column j that it
+    // needs by the pivot's inverse square root on the fly for its share of the trailing triangle, and the scaled
+    // column goes to a second matrix Lf (nobody reads column j of G again), so reading and scaling do not collide.
     for (int j = 0; j < R; j++) {
         const float inv = 1.0f / sqrtf(G[j * GS + j]);
-        __syncthreads();   // everyone has read the pivot
-        for (int t = j + tid; t < R; t += 256) G[t * GS + j] *= inv;   // t = j: the pivot becomes its square root
-        __syncthreads();
+        for (int t = j + tid; t < R; t += 256) Lf[t * GS + j] = G[t * GS + j] * inv;   // t = j: the pivot's square root
         const int n = R - 1 - j;   // trailing triangle: rows t > j, columns j < c <= t
         for (int e = tid; e < n * n; e += 256) {
             const int t = j + 1 + e / n, c = j + 1 + e % n;
-            if (c <= t) G[t * GS + c] = fmaf(-G[t * GS + j], G[c * GS + j], G[t * GS + c]);
+            if (c <= t) G[t * GS + c] = fmaf(-(G[t * GS + j] * inv), G[c * GS + j] * inv, G[t * GS + c]);
         }
         __syncthreads();
     }
@@ -165,8 +172,8 @@ __global__ __launch_bounds__(256) void k_cpals_solve(const CpUpdate p)
             if (i < R) {
                 float v = m[i];
 #pragma unroll
-                for (int k = 0; k < i; k++) v = fmaf(-G[i * GS + k], m[k], v);
-                m[i] = v / G[i * GS + i];
+                for (int k = 0; k < i; k++) v = fmaf(-Lf[i * GS + k], m[k], v);
+                m[i] = v / Lf[i * GS + i];
             }
         }
 #pragma unroll
@@ -175,8 +182,8 @@ __global__ __launch_bounds__(256) void k_cpals_solve(const CpUpdate p)
                 float v = m[i];
 #pragma unroll
                 for (int k = i + 1; k < RS; k++)
-                    if (k < R) v = fmaf(-G[k * GS + i], m[k], v);
-                m[i] = v / G[i * GS + i];
+                    if (k < R) v = fmaf(-Lf[k * GS + i], m[k], v);
+                m[i] = v / Lf[i * GS + i];
             }
         }
         float *dst = p.F0 + rep * D0 * R + tid;   // column-major D0 x R
