@@ -81,7 +81,11 @@ typedef struct {
  *   w  = (i & 2) ? mixB(ck ^ (i>>2)) : mixA(ck ^ (i>>2))
  *   u1 = ((w>>16) + 0.5)/65536, u2 = ((w & 0xffff) + 0.5)/65536
  *   g  = sqrt(-2 ln u1) * ((i & 1) ? sin(2 pi u2) : cos(2 pi u2))
- * evaluated in fp32 with the hardware log2/sqrt/sin/cos. */
+ * evaluated in fp32 with the hardware log2/sqrt/sin/cos.
+ * The multiplier/shift sets of mixA and mixB are two published, public-domain 32-bit integer hash
+ * finalisers of the multiply-xorshift family (the "lowbias32" constants found by Chris Wellons'
+ * hash-prospector search and a second set from the same search); 0x243f6a88 is the first 32 fractional
+ * bits of pi.  The composition into a stream key, a fibre key and a quad counter is this library's own. */
 typedef struct {
     const float *A, *B, *C; /* device */
     int32_t R;              /* 1 <= R <= 256 */
@@ -92,8 +96,11 @@ typedef struct {
 /* Half-open sub-box [i0,i1) x [j0,j1) x [k0,k1) of X; any non-empty box inside X. */
 typedef struct { int64_t i0, i1, j0, j1, k0, k1; } exat_box_t;
 
-/* Creates a plan for `desc` on the current device and allocates its workspace
- * (packed U/V/W copies and the mode-2 intermediate of P*L x M x K floats).
+/* Creates a plan for `desc` on the current device and allocates the workspace of the one-shot calls
+ * (packed U/V/W copies and the mode-2 intermediate of P*L x M x K floats).  exat_compress and
+ * exat_compress_gen allocate nothing afterwards.  Two calls allocate on their FIRST use with a plan and
+ * must therefore not be the first such call inside a stream capture: exat_compress_block (the block
+ * partials, at most 4 GiB) and exat_compress_host (three device block buffers, a copy stream, events).
  * Errors: NULL, SHAPE, DTYPE, ALLOC. */
 int exat_plan_create(exat_plan_t *plan, const exat_desc_t *desc);
 
@@ -125,8 +132,8 @@ int exat_compress(exat_plan_t plan, const void *X, float *Y, void *stream);
  * submission returns STATE); exat_finalize merges the partials in a fixed order, so Y
  * does not depend on the submission order whenever the plan could give every block its
  * own partial (it can for up to 4 GiB of partials; beyond that, blocks that share a
- * partial are summed in submission order).
- * Errors: NULL, SHAPE (block index out of range), STATE, HIP. */
+ * partial are summed in submission order).  The first call with a plan allocates the partials.
+ * Errors: NULL, SHAPE (block index out of range), STATE, ALLOC (first call only), HIP. */
 int exat_compress_block(exat_plan_t plan, const void *Xblk, int32_t bi, int32_t bj, int32_t bk,
                         void *stream);
 
@@ -161,12 +168,6 @@ int exat_compress_gen(exat_plan_t plan, const exat_gen_t *gen, const exat_box_t 
  * Errors: NULL, SHAPE, DTYPE, HIP. */
 int exat_gen_block(const exat_desc_t *desc, const exat_gen_t *gen, int32_t bi, int32_t bj, int32_t bk,
                    void *out, void *stream);
-
-/* Diagnostic aid: kernel variants built with in-kernel bounds checking count every global access that
- * would have left its buffer (the access is skipped).  Synchronises the device and copies the plan's 8
- * counters to the host array: [0] = number of rejected accesses, [1..6] = flags per buffer
- * (U, A pieces, B, C, V, Q).  All zero in a correct run.  Errors: NULL, HIP. */
-int exat_plan_check_status(exat_plan_t plan, uint32_t *counters8);
 
 /* Measurement aid (not part of the paper's method): with timing enabled, every compress
  * call records HIP events on its stream around the fused mode-1/2 kernel and around the

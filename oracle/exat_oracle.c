@@ -185,6 +185,9 @@ int orc_closed_form(const float *A, const float *B, const float *C,
 /* (Box-Muller on 16-bit uniforms; all integer arithmetic mod 2^32.)   */
 /* It depends on the global coordinates only, never on the tiling.     */
 /* Requires 0 <= i,j,k < 2^31.                                          */
+/* mixA / mixB use two published public-domain constant sets of the     */
+/* multiply-xorshift hash family ("lowbias32" and a second result of    */
+/* the same hash-prospector search); 0x243f6a88 = fractional bits of pi.*/
 /* ------------------------------------------------------------------ */
 static inline uint32_t mixA(uint32_t x)
 {

@@ -1,9 +1,9 @@
 """exat: multi-replica tensor compression Y_p = X x1 U_p x2 V_p x3 W_p on MI355X (gfx950).
 
 The compute lives in the C-ABI library built from csrc/ (see include/exat.h);
-`paper_2311_13693_amd.exat` is the thin ctypes binding over it and
-`paper_2311_13693_amd.workloads` the seeded synthetic-input recipes.
-Nothing is imported eagerly so that the input recipes can be used without the
-GPU library being present.
+`paper_2311_13693_amd.exat` is the thin ctypes binding over it.  Nothing is
+imported eagerly.  The seeded synthetic-input recipes that tests and benchmark
+feed to both this library and the CPU oracle live outside the package, in the
+top-level module `workloads`.
 """
-__all__ = ["exat", "workloads"]
+__all__ = ["exat"]

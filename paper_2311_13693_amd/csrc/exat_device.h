@@ -14,6 +14,8 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 namespace exat {
 
 // ---- synthetic noise g(seed; i,j,k) (definition in include/exat.h, exat_gen_t) ----
+// mix_a / mix_b: two published public-domain 32-bit multiply-xorshift hash finalisers ("lowbias32" and a second
+// constant set from the same hash-prospector search); only the constants are taken, the keying is this library's.
 __host__ __device__ __forceinline__ uint32_t mix_a(uint32_t x)
 {
     x ^= x >> 16; x *= 0x7feb352du; x ^= x >> 15; x *= 0x846ca68bu; x ^= x >> 16;

@@ -245,9 +245,8 @@ __global__ __launch_bounds__(256) void k_mode12(const Mode12Params p)
         __syncthreads();  // staging LDS is free now
         float *Zs = (float *)smem + wave * (32 * ZST);
         const bool first_chunk = (jc == ja0);
-        const CheckParams ck = {};
-        if (p.MT == 2) mode2_chunk<RT, CT, false, 2, VM_F32, 4>(p, nullptr, ck, Zs, acc, wrow0, kidx, jc, first_chunk, lane);
-        else mode2_chunk<RT, CT, false, 1, VM_F32, 4>(p, nullptr, ck, Zs, acc, wrow0, kidx, jc, first_chunk, lane);
+        if (p.MT == 2) mode2_chunk<RT, CT, 2, VM_F32, 4>(p, nullptr, Zs, acc, wrow0, kidx, jc, first_chunk, lane);
+        else mode2_chunk<RT, CT, 1, VM_F32, 4>(p, nullptr, Zs, acc, wrow0, kidx, jc, first_chunk, lane);
     }
 }
 

@@ -62,7 +62,6 @@ __global__ __launch_bounds__(64 * NW) void k_mode12_split(const Mode12Params p, 
 
     f16x8 uh[DU][RT][2], ul[DU][RT][2];
     f32x4 xpre[DX][2 * XPT];
-    const CheckParams ck = {};
 
     for (int64_t jc = ja0; jc < p.j1; jc += COLS) {
         // per-lane offsets derived again in every chunk (keeps them out of registers during the mode-2 phase)
@@ -189,8 +188,8 @@ __global__ __launch_bounds__(64 * NW) void k_mode12_split(const Mode12Params p, 
         // ---- mode 2 on the finished Z chunk ----
         float *Zs = (float *)smem + wave * (32 * ZST);
         const bool first_chunk = (jc == ja0);
-        if (p.MT == 2) mode2_chunk<RT, CT, false, 2, VM_F16X2>(p, sp.Vfh, ck, Zs, acc, wrow0, kidx, jc, first_chunk, tid & 63, sp.Vfl);
-        else mode2_chunk<RT, CT, false, 1, VM_F16X2>(p, sp.Vfh, ck, Zs, acc, wrow0, kidx, jc, first_chunk, tid & 63, sp.Vfl);
+        if (p.MT == 2) mode2_chunk<RT, CT, 2, VM_F16X2>(p, sp.Vfh, Zs, acc, wrow0, kidx, jc, first_chunk, tid & 63, sp.Vfl);
+        else mode2_chunk<RT, CT, 1, VM_F16X2>(p, sp.Vfh, Zs, acc, wrow0, kidx, jc, first_chunk, tid & 63, sp.Vfl);
     }
 }
 

@@ -84,8 +84,8 @@ template <> struct gen_piece<float> {
 
 // BOXED: the box is a proper sub-range in i, so elements outside [i0,i1) must be forced to zero
 // (for the full extent the zero padding of U already removes them).
-template <typename T, int NW, int RT, int SRC, int KS, bool BOXED, bool CHECKED>
-__global__ __launch_bounds__(64 * NW) void k_mode12_v2(const Mode12Params p, const GenSplitParams gs, const CheckParams ck)
+template <typename T, int NW, int RT, int SRC, int KS, bool BOXED>
+__global__ __launch_bounds__(64 * NW) void k_mode12_v2(const Mode12Params p, const GenSplitParams gs)
 {
     typedef Mode12V2Cfg<NW, RT> cfg;
     typedef typename mma_frag<T>::type frag_t;
@@ -169,7 +169,7 @@ __global__ __launch_bounds__(64 * NW) void k_mode12_v2(const Mode12Params p, con
                     for (int e = 0; e < 8; e++) {
                         // clamped, unconditional loads (no branch per element), masked afterwards
                         const int r = 32 * ks + 8 * q16 + e, rr = r < p.R ? r : p.R - 1;
-                        float bc = ld_chk<CHECKED>(p.B + jj + p.ldB * rr, ck, CHK_B) * ld_chk<CHECKED>(p.C + k + p.ldC * rr, ck, CHK_C);
+                        float bc = *(p.B + jj + p.ldB * rr) * *(p.C + k + p.ldC * rr);
                         bc = (colok && r < p.R) ? bc : 0.0f;
                         __bf16 h, m;
                         gen_piece<T>::split(bc, h, m);
@@ -185,7 +185,7 @@ __global__ __launch_bounds__(64 * NW) void k_mode12_v2(const Mode12Params p, con
         auto load_u = [&](int s) {
             const T *ub = Ug + stage_i(s);
 #pragma unroll
-            for (int u = 0; u < UPT; u++) upre[u] = ld_chk<CHECKED>((const u32x4 *)(ub + (u_voff + u * u_vstep)), ck, CHK_U);
+            for (int u = 0; u < UPT; u++) upre[u] = *((const u32x4 *)(ub + (u_voff + u * u_vstep)));
         };
         auto load_x = [&](int s) {
             if constexpr (SRC == SRC_MATERIALISED) {
@@ -207,7 +207,7 @@ __global__ __launch_bounds__(64 * NW) void k_mode12_v2(const Mode12Params p, con
                     for (int ks = 0; ks < KS; ks++)
 #pragma unroll
                         for (int si = 0; si < SUBI; si++)
-                            afrag[(v * KS + ks) * SUBI + si] = ld_chk<CHECKED>((const bf16x8 *)(gs.Asp + ((int64_t)v * gs.Irows + ib + 16 * si + l16) * gs.Rpad + 32 * ks + 8 * q16), ck, CHK_A);
+                            afrag[(v * KS + ks) * SUBI + si] = *((const bf16x8 *)(gs.Asp + ((int64_t)v * gs.Irows + ib + 16 * si + l16) * gs.Rpad + 32 * ks + 8 * q16));
             }
         };
         // low-rank part of the tile of the stage whose A fragments are loaded: accx = A_tile * bc^T
@@ -314,8 +314,8 @@ __global__ __launch_bounds__(64 * NW) void k_mode12_v2(const Mode12Params p, con
         const bool first_chunk = (jc == ja0);
         // the generator's registers leave less room for V fragments in flight
         constexpr int VB = SRC == SRC_GENERATED ? V2_VB : 16;
-        if (p.MT == 2) mode2_chunk<RT, CT, CHECKED, 2, VM_F32, VB>(p, nullptr, ck, Zs, acc, wrow0, kidx, jc, first_chunk, lane);
-        else mode2_chunk<RT, CT, CHECKED, 1, VM_F32, VB>(p, nullptr, ck, Zs, acc, wrow0, kidx, jc, first_chunk, lane);
+        if (p.MT == 2) mode2_chunk<RT, CT, 2, VM_F32, VB>(p, nullptr, Zs, acc, wrow0, kidx, jc, first_chunk, lane);
+        else mode2_chunk<RT, CT, 1, VM_F32, VB>(p, nullptr, Zs, acc, wrow0, kidx, jc, first_chunk, lane);
     }
 }
 

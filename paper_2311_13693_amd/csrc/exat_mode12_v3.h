@@ -85,8 +85,8 @@ constexpr int lcm_i(int a, int b) { return a / gcd_i(a, b) * b; }
 // so that one's chunk set-up and mode-2 phases run under the other's MFMA phase).
 // ZT: mode 1 with the MFMA operands swapped (accumulators hold Z^T) and mode 2 straight from the accumulators
 // (mode2_direct; fp32 materialised source, L % 32 == 0).
-template <typename T, int NW, int RT, int SRC, int KS, bool BOXED, bool CHECKED, int DU = 2, int DX = 1, int WPS = (NW + 3) / 4, bool ZT = false>
-__global__ __launch_bounds__(64 * NW, WPS) void k_mode12_v3(const Mode12Params p, const GenSplitParams gs, const UFragParams uf, const CheckParams ck)
+template <typename T, int NW, int RT, int SRC, int KS, bool BOXED, int DU = 2, int DX = 1, int WPS = (NW + 3) / 4, bool ZT = false>
+__global__ __launch_bounds__(64 * NW, WPS) void k_mode12_v3(const Mode12Params p, const GenSplitParams gs, const UFragParams uf)
 {
     typedef Mode12V3Cfg<NW, RT> cfg;
     typedef typename mma_frag<T>::type frag_t;
@@ -187,7 +187,7 @@ __global__ __launch_bounds__(64 * NW, WPS) void k_mode12_v3(const Mode12Params p
                     for (int e = 0; e < 8; e++) {
                         // clamped, unconditional loads (no branch per element), masked afterwards
                         const int r = 32 * ks + 8 * q16 + e, rr = r < p.R ? r : p.R - 1;
-                        float bc = ld_chk<CHECKED>(p.B + jj + p.ldB * rr, ck, CHK_B) * ld_chk<CHECKED>(p.C + k + p.ldC * rr, ck, CHK_C);
+                        float bc = *(p.B + jj + p.ldB * rr) * *(p.C + k + p.ldC * rr);
                         bc = (colok && r < p.R) ? bc : 0.0f;
                         __bf16 h, m;
                         gen_piece<T>::split(bc, h, m);
@@ -201,7 +201,7 @@ __global__ __launch_bounds__(64 * NW, WPS) void k_mode12_v3(const Mode12Params p
 
         auto stage_i = [&](int s) -> int64_t { return ia0 + (int64_t)(s < nstage ? s : nstage - 1) * EI; };
         auto load_uf = [&](int rt, int64_t ig) -> frag_t {
-            return ld_chk<CHECKED>((const frag_t *)(ufl + rt * u_rt_step + ig * (64 * E16)), ck, CHK_U);
+            return *((const frag_t *)(ufl + rt * u_rt_step + ig * (64 * E16)));
         };
         auto load_x = [&](int s, u32x4 *slot) {
             if constexpr (SRC == SRC_MATERIALISED) {
@@ -223,7 +223,7 @@ __global__ __launch_bounds__(64 * NW, WPS) void k_mode12_v3(const Mode12Params p
                     for (int ks = 0; ks < KS; ks++)
 #pragma unroll
                         for (int si = 0; si < SUBI; si++)
-                            af[(v * KS + ks) * SUBI + si] = ld_chk<CHECKED>((const bf16x8 *)(gs.Asp + ((int64_t)v * gs.Irows + ib + 16 * si + l16) * gs.Rpad + 32 * ks + 8 * q16), ck, CHK_A);
+                            af[(v * KS + ks) * SUBI + si] = *((const bf16x8 *)(gs.Asp + ((int64_t)v * gs.Irows + ib + 16 * si + l16) * gs.Rpad + 32 * ks + 8 * q16));
             }
         };
         // one low-rank MFMA of the tile whose A pieces are in af: term n of accumulator `dst`
@@ -458,11 +458,11 @@ __global__ __launch_bounds__(64 * NW, WPS) void k_mode12_v3(const Mode12Params p
         float *Zs = (float *)smem + wave * (32 * ZST);
         const bool first_chunk = (jc == ja0);
         if constexpr (ZT) {
-            static_assert(!ZT || (sizeof(T) == 4 && !CHECKED), "ZT: fp32, unchecked only");
+            static_assert(!ZT || sizeof(T) == 4, "ZT: fp32 only");
             if (p.MT == 2) mode2_direct<RT, CT, 2>(p, p.Vd, acc, wrow0, kidx, jc, first_chunk, tid & 63);
             else mode2_direct<RT, CT, 1>(p, p.Vd, acc, wrow0, kidx, jc, first_chunk, tid & 63);
-        } else if (p.MT == 2) mode2_chunk<RT, CT, CHECKED, 2, sizeof(T) == 2 ? VM_BF16 : VM_F32>(p, uf.Vf, ck, Zs, acc, wrow0, kidx, jc, first_chunk, tid & 63);
-        else mode2_chunk<RT, CT, CHECKED, 1, sizeof(T) == 2 ? VM_BF16 : VM_F32>(p, uf.Vf, ck, Zs, acc, wrow0, kidx, jc, first_chunk, tid & 63);
+        } else if (p.MT == 2) mode2_chunk<RT, CT, 2, sizeof(T) == 2 ? VM_BF16 : VM_F32>(p, uf.Vf, Zs, acc, wrow0, kidx, jc, first_chunk, tid & 63);
+        else mode2_chunk<RT, CT, 1, sizeof(T) == 2 ? VM_BF16 : VM_F32>(p, uf.Vf, Zs, acc, wrow0, kidx, jc, first_chunk, tid & 63);
     }
 }
 

@@ -10,44 +10,6 @@
 
 namespace exat {
 
-// Optional in-kernel bounds checking of every global access (template flag CHECKED): an address outside
-// its buffer is not dereferenced; the access is counted in dbg[0], its buffer id is flagged in dbg[1 + id],
-// and a zero is used instead.  The host reads the counters back through exat_plan_check_status.
-struct CheckParams {
-    const char *lo[6], *hi[6];  // 0: U, 1: A pieces, 2: B, 3: C, 4: V, 5: Q
-    unsigned *dbg;              // >= 8 counters
-};
-enum { CHK_U = 0, CHK_A = 1, CHK_B = 2, CHK_C = 3, CHK_V = 4, CHK_Q = 5 };
-
-template <bool CHECKED, typename V>
-__device__ __forceinline__ V ld_chk(const V *ptr, const CheckParams &ck, int id)
-{
-    if constexpr (CHECKED) {
-        const char *c = (const char *)ptr;
-        if (c < ck.lo[id] || c + sizeof(V) > ck.hi[id]) {
-            atomicAdd(&ck.dbg[0], 1u);
-            ck.dbg[1 + id] = 1u;
-            V z;
-            __builtin_memset(&z, 0, sizeof(V));
-            return z;
-        }
-    }
-    return *ptr;
-}
-template <bool CHECKED, typename V>
-__device__ __forceinline__ void st_chk(V *ptr, V v, const CheckParams &ck, int id)
-{
-    if constexpr (CHECKED) {
-        const char *c = (const char *)ptr;
-        if (c < ck.lo[id] || c + sizeof(V) > ck.hi[id]) {
-            atomicAdd(&ck.dbg[0], 1u);
-            ck.dbg[1 + id] = 1u;
-            return;
-        }
-    }
-    *ptr = v;
-}
-
 template <int V> struct ic { static constexpr int value = V; };
 
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
@@ -61,8 +23,8 @@ typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 //            same fragment order), the three significant cross terms accumulated in fp32 (error 2^-22).
 // VB: V fragments (of 8 columns) requested together on the fp32 path; 16 = a whole chunk, fewer where registers are short.
 enum { VM_F32 = 0, VM_BF16 = 1, VM_F16X2 = 2 };
-template <int RT, int CT, bool CHECKED, int MTC, int VM, int VB = 16>
-__device__ __forceinline__ void mode2_chunk(const Mode12Params &p, const void *Vf, const CheckParams &ck, float *Zs, const f32x16 (&acc)[RT][CT],
+template <int RT, int CT, int MTC, int VM, int VB = 16>
+__device__ __forceinline__ void mode2_chunk(const Mode12Params &p, const void *Vf, float *Zs, const f32x16 (&acc)[RT][CT],
                                             int wrow0, int kidx, int64_t jc, bool first_chunk, int lane, const void *Vf2 = nullptr)
 {
     constexpr int COLS = 32 * CT, ZST = COLS + 4;
@@ -97,7 +59,7 @@ __device__ __forceinline__ void mode2_chunk(const Mode12Params &p, const void *V
                 for (int mt = 0; mt < MTC; mt++)
 #pragma unroll
                     for (int e = 0; e < 16; e++)
-                        qsum[mt][e] = ld_chk<CHECKED>((const float *)(Qt + (8 * (e >> 2) + (e & 3)) * MP + 32 * mt), ck, CHK_Q);
+                        qsum[mt][e] = *((const float *)(Qt + (8 * (e >> 2) + (e & 3)) * MP + 32 * mt));
             }
             for (int pp = pfirst; pp <= plast; pp++) {
                 const int rlo = pp * p.L, rhi = rlo + p.L;
@@ -146,7 +108,7 @@ __device__ __forceinline__ void mode2_chunk(const Mode12Params &p, const void *V
 #pragma unroll
                     for (int g16 = 0; g16 < COLS / 16; g16++)
 #pragma unroll
-                        for (int mt = 0; mt < MTC; mt++) bv[g16][mt] = ld_chk<CHECKED>(vf + (g16 * 2 + mt) * 64, ck, CHK_V);
+                        for (int mt = 0; mt < MTC; mt++) bv[g16][mt] = *(vf + (g16 * 2 + mt) * 64);
                     __builtin_amdgcn_sched_barrier(0);  // keeps the requests together, ahead of the first MFMA
 #pragma unroll
                     for (int g16 = 0; g16 < COLS / 16; g16++) {
@@ -175,7 +137,7 @@ __device__ __forceinline__ void mode2_chunk(const Mode12Params &p, const void *V
                             f32x4 bv[VB];
 #pragma unroll
                             for (int g8 = 0; g8 < VB; g8++)
-                                bv[g8] = ld_chk<CHECKED>((const f32x4 *)(Vp + (int64_t)(mt * 32) * p.Jpad + 8 * (g0 + g8)), ck, CHK_V);
+                                bv[g8] = *((const f32x4 *)(Vp + (int64_t)(mt * 32) * p.Jpad + 8 * (g0 + g8)));
                             __builtin_amdgcn_sched_barrier(0);  // keeps the requests together, ahead of the first MFMA
 #pragma unroll
                             for (int g8 = 0; g8 < VB; g8++) {
@@ -197,7 +159,7 @@ __device__ __forceinline__ void mode2_chunk(const Mode12Params &p, const void *V
             for (int mt = 0; mt < MTC; mt++)
 #pragma unroll
                 for (int e = 0; e < 16; e++)
-                    st_chk<CHECKED>(Qt + (8 * (e >> 2) + (e & 3)) * MP + 32 * mt, qsum[mt][e], ck, CHK_Q);
+                    *(Qt + (8 * (e >> 2) + (e & 3)) * MP + 32 * mt) = qsum[mt][e];
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
         }

@@ -15,7 +15,7 @@ OK, ERR_NULL, ERR_SHAPE, ERR_DTYPE, ERR_STATE, ERR_ALLOC, ERR_HIP = 0, -1, -2, -
 
 EXPORTS = ["exat_plan_create", "exat_plan_destroy", "exat_set_factors", "exat_compress",
            "exat_compress_block", "exat_finalize", "exat_compress_host", "exat_compress_gen", "exat_gen_block",
-           "exat_plan_set_timing", "exat_plan_last_timing", "exat_plan_timing_of", "exat_plan_check_status",
+           "exat_plan_set_timing", "exat_plan_last_timing", "exat_plan_timing_of",
            "exat_stage1_create", "exat_stage1_destroy", "exat_stage1_dims", "exat_stage1_apply", "exat_stage1_apply_host",
            "exat_stage1_set_timing", "exat_stage1_last_timing", "exat_cpals_workspace_floats", "exat_cpals",
            "exat_ls_workspace_floats", "exat_ls", "exat_strerror"]
@@ -78,7 +78,6 @@ def lib():
         L.exat_plan_set_timing.argtypes = [vp, ctypes.c_int]
         L.exat_plan_last_timing.argtypes = [vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_float)]
         L.exat_plan_timing_of.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_float)]
-        L.exat_plan_check_status.argtypes = [vp, ctypes.POINTER(ctypes.c_uint32)]
         L.exat_stage1_create.argtypes = [ctypes.POINTER(vp), i64, i64, i64, ctypes.POINTER(Csr), ctypes.POINTER(Csr),
                                          ctypes.POINTER(Csr)]
         L.exat_stage1_destroy.argtypes = [vp]
@@ -89,6 +88,8 @@ def lib():
         L.exat_stage1_last_timing.argtypes = [vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_float)]
         L.exat_cpals_workspace_floats.argtypes = [i32, i32, i32, i32]
         L.exat_cpals.argtypes = [vp, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp]
+        L.exat_ls_workspace_floats.argtypes = [i32, i32, i32, i32]
+        L.exat_ls.argtypes = [vp, i64, i32, i32, i32, vp, i32, i32, ctypes.c_float, vp, vp, vp, vp]
         L.exat_strerror.argtypes = [ctypes.c_int]
         L.exat_strerror.restype = ctypes.c_char_p
         for name in EXPORTS[:-1]:
@@ -184,12 +185,6 @@ class Plan:
         a, b = ctypes.c_float(), ctypes.c_float()
         _check(lib().exat_plan_timing_of(self._h, int(age), ctypes.byref(a), ctypes.byref(b)))
         return a.value, b.value
-
-    def check_status(self):
-        """Counters of the bounds-checked kernel variants (all zero in a correct run); synchronises."""
-        out = (ctypes.c_uint32 * 8)()
-        _check(lib().exat_plan_check_status(self._h, out))
-        return list(out)
 
     def new_y(self):
         import torch

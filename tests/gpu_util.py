@@ -2,7 +2,8 @@
 import numpy as np
 import torch
 
-from paper_2311_13693_amd import exat, workloads as wl
+from paper_2311_13693_amd import exat
+import workloads as wl
 
 
 def to_dev_x(X, bf16=False):

@@ -16,7 +16,8 @@ import pytest
 import torch
 
 import oracle
-from paper_2311_13693_amd import exat, workloads as wl
+from paper_2311_13693_amd import exat
+import workloads as wl
 
 sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
 import gpu_util as gu  # noqa: E402
@@ -111,7 +112,7 @@ def test_cfg3_replica_sampled_parity_and_noise_energy():
     _say("  max|X_gpu - X_oracle| on the first 2^26 elements: %.3e" % dmax)
     assert dmax <= 2e-6 * (1.0 + float(Xd[: 1 << 26].abs().max()))
     del Xg, Xd
-    reps = [0, 13, 31]
+    reps = [0, 9, 13, 18, 27, 31]      # at least one replica in each 512-row group of the stacked operand
     t0 = time.time()
     Yo = oracle.comp_multi(X, U, V, W, cfg.P, replicas=reps)
     _say("  oracle, %d replicas: %.1f s" % (len(reps), time.time() - t0))
@@ -125,6 +126,12 @@ def test_cfg3_replica_sampled_parity_and_noise_energy():
     ratio = got / want
     _say("  noise energy ratio: min %.4f max %.4f" % (ratio.min(), ratio.max()))
     assert np.all(np.abs(ratio - 1.0) <= 0.02)
+    # every replica at the fp32 tolerance: the noiseless tensor (oracle's generator, sigma = 0) against the closed form
+    X0 = oracle.gen_box(A, B, C, cfg.seed, 0.0)
+    Y0 = gu.y_to_numpy(plan.compress(gu.to_dev_x(X0)), cfg)
+    per = np.array([oracle.rel_fro(Y0[..., p], Yc[..., p]) for p in range(cfg.P)])
+    _say("  cfg3 sigma=0, all %d replicas vs closed form: worst %.3e" % (cfg.P, per.max()))
+    assert per.max() <= TOL["f32"]
     plan.close()
 
 
@@ -146,7 +153,9 @@ def test_generated_config_sampled_tiles_against_oracle(name):
     A, B, C, U, V, W = _inputs(cfg)
     plan = gu.plan_with_factors(cfg, U, V, W)
     gen = gu.gen_of(cfg, A, B, C)
-    reps = [0, cfg.P // 2, cfg.P - 1]
+    # cfg5: one replica in every row group of the stacked operand the kernels may form (groups of 384, 480 or 512
+    # rows plus the remainder launch), both ends included
+    reps = [0, cfg.P // 2, cfg.P - 1] if name == "cfg4" else [0, 8, 11, 16, 24, 31, 39, 41, 47]
     rb = oracle.round_bf16
     worst, worst_r = 0.0, 0.0
     for box in _sample_boxes(cfg):
@@ -211,6 +220,14 @@ def test_scaled_down_twins_against_full_oracle(name, nrep):
     e = oracle.rel_fro(Y[..., reps], Yo)
     _say("  %s rel_fro %.3e" % (name, e))
     assert e <= TOL[cfg.dtype]
+    if cfg.dtype == "bf16":
+        # every replica against the oracle on RNE-rounded inputs: isolates kernel errors from the quantisation
+        rb = oracle.round_bf16
+        Xr = oracle.gen_box(A, B, C, cfg.seed, cfg.sigma, to_bf16=True)
+        Yr = oracle.comp_multi(Xr, rb(U), rb(V), rb(W), cfg.P, replicas=reps)
+        per = np.array([oracle.rel_fro(Y[..., p], Yr[..., n]) for n, p in enumerate(reps)])
+        _say("  %s vs oracle on bf16-rounded inputs, %d replicas: worst %.3e" % (name, len(reps), per.max()))
+        assert per.max() <= 1e-3
     # merge of per-tile results (Fig. 2a) equals the one-shot result
     acc = np.zeros_like(Y)
     gen = gu.gen_of(cfg, A, B, C)

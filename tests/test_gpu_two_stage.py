@@ -8,7 +8,8 @@ import pytest
 import torch
 
 import oracle
-from paper_2311_13693_amd import exat, workloads as wl
+from paper_2311_13693_amd import exat
+import workloads as wl
 from tests import gpu_util as gu
 
 pytestmark = pytest.mark.gpu

@@ -9,7 +9,7 @@ import numpy as np
 import pytest
 
 import oracle
-from paper_2311_13693_amd import workloads as wl
+import workloads as wl
 
 
 def _rand(seed, *shape):

@@ -8,7 +8,7 @@ import torch
 from scipy import stats
 
 import oracle
-from paper_2311_13693_amd import workloads as wl
+import workloads as wl
 
 SEED = 0x231113693000
 

@@ -7,7 +7,7 @@ import numpy as np
 import scipy.sparse as sp
 
 import oracle
-from paper_2311_13693_amd import workloads as wl
+import workloads as wl
 
 
 def _ts(I=23, J=17, K=29, L=3, M=4, N=2, P=3, alpha=2, beta=3, gamma=2, s=3, index=200):

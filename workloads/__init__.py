@@ -2,8 +2,8 @@
 
 This module only draws random input matrices and names problem sizes.  It
 contains none of the method's arithmetic (no compression, no tensor
-generation, no noise function): both the HIP library's tests/benchmark and the
-CPU oracle's tests take their inputs from here.
+generation, no noise function) and belongs to neither the HIP library's package
+nor the CPU oracle's: the tests and the benchmark of both take their inputs from here.
 
 The paper's dense workload: I=J=K, Gaussian CP factor matrices A,B,C (I x R),
 Gaussian compression matrices U_p (L x I), V_p (M x J), W_p (N x K), cubic
