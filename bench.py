@@ -462,7 +462,7 @@ def main():
         "ttm_frac_of_mfma_peak": cfg.flops * frac / (ms_step * 1e-3) / 1e12 / peak,
         "kernel_ms": {"mode12": ms12, "mode3": ms3},
         "operand_prep_ms": t_prep * 1e3,
-        "roofline": {"bound": "mfma", "kernel": "k_mode12_split" if split else "k_mode12_v3", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
+        "roofline": {"bound": "mfma", "kernel": "k_mode12_split" if split else ("k_mode12_v4" if (cfg.dtype == "bf16" and not cfg.materialised) else "k_mode12_v3"), "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
                      "frac": achieved / peak,
                      "traffic": recorded_traffic(cfg.name) if (frac == 1.0 and not split) else None},
     }

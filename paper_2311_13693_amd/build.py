@@ -11,7 +11,7 @@ _PUBLIC = os.path.join(os.path.dirname(HERE), "include", "exat.h")
 # translation unit -> the headers it includes
 UNITS = {
     "exat.hip": ["exat_device.h", "exat_common.h", "exat_mode12.h", "exat_mode2.h", "exat_mode12_v2.h",
-                 "exat_mode12_v3.h", "exat_mode12_split.h", "exat_aux.h"],
+                 "exat_mode12_v3.h", "exat_mode12_v4.h", "exat_mode12_split.h", "exat_aux.h"],
     "exat_stage1.hip": [],
     "exat_cpals.hip": [],
     "exat_ls.hip": [],

@@ -14,6 +14,7 @@
 #include "exat_mode12.h"
 #include "exat_mode12_v2.h"
 #include "exat_mode12_v3.h"
+#include "exat_mode12_v4.h"
 #include "exat_mode12_split.h"
 
 using namespace exat;
@@ -210,6 +211,28 @@ int launch_v3_gen_bf16(const Mode12Params &mp, const GenSplitParams &gs, const U
     return boxed ? launch_v3_inst<__bf16, 4, RT, SRC_GENERATED, 2, true, 2, 1>(mp, gs, uf, nk, st) : launch_v3_inst<__bf16, 4, RT, SRC_GENERATED, 2, false, 2, 1>(mp, gs, uf, nk, st);
 }
 
+// bf16 generated source, 8 waves x 2 row tiles (512 stacked rows per group), k_mode12_v4
+template <int KS, bool BOXED>
+int launch_v4_inst(const Mode12Params &mp, const GenSplitParams &gs, const UFragParams &uf, int nk, hipStream_t st)
+{
+    typedef Mode12V4Cfg<8, 2> cfg;
+    auto kern = k_mode12_v4<8, 2, KS, BOXED, 2, 0>;
+    static bool attr_done = false;
+    if (!attr_done) {
+        if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, cfg::LDS_BYTES) != hipSuccess) return EXAT_ERR_HIP;
+        attr_done = true;
+    }
+    const int64_t grid = 8LL * ((nk + 7) / 8) * mp.G;
+    if (grid > 2147483647LL) return EXAT_ERR_SHAPE;
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(512), cfg::LDS_BYTES, st, mp, gs, uf);
+    return hipGetLastError() == hipSuccess ? EXAT_OK : EXAT_ERR_HIP;
+}
+int launch_v4_gen_bf16(const Mode12Params &mp, const GenSplitParams &gs, const UFragParams &uf, int ks, bool boxed, int nk, hipStream_t st)
+{
+    if (ks == 1) return boxed ? launch_v4_inst<1, true>(mp, gs, uf, nk, st) : launch_v4_inst<1, false>(mp, gs, uf, nk, st);
+    return boxed ? launch_v4_inst<2, true>(mp, gs, uf, nk, st) : launch_v4_inst<2, false>(mp, gs, uf, nk, st);
+}
+
 // fp32 data on the fp16 matrix cores (two-piece split), materialised source, 4 waves x RT row tiles
 template <int RT>
 int launch_split(const Mode12Params &mp, const SplitParams &sp, int nk, hipStream_t st)
@@ -296,6 +319,11 @@ int run_chain(exat_plan_s *pl, Mode12Params mp, bool generated, float *Yout, int
             else if (pl->d.L % 32 == 0 && env_int("EXAT_ZT", 1))
                 rc = rt == 4 ? launch_v3_mat_zt<8, 2>(mp, gs, uf, nk, st) : launch_v3_mat_zt<4, 2>(mp, gs, uf, nk, st);
             else rc = rt == 4 ? launch_v3_mat<float, 8, 2>(mp, gs, uf, nk, st) : launch_v3_mat<float, 4, 2>(mp, gs, uf, nk, st);
+        } else if (bf && pl->PL > 256 && env_int("EXAT_RT", 0) == 0) {
+            // 512-row groups, two waves per SIMD (k_mode12_v4): the tile is generated once per group, so large groups
+            // are what keeps the generator's vector work below the MFMA work
+            mp.G = (pl->PL + 511) / 512;
+            rc = launch_v4_gen_bf16(mp, gs, uf, ks, boxed, nk, st);
         } else if (bf) {
             if (rt == 3) {
                 // 384-row groups; a remainder of at most 256 rows gets a launch of its own with a smaller tile
