@@ -212,11 +212,11 @@ int launch_v3_gen_bf16(const Mode12Params &mp, const GenSplitParams &gs, const U
 }
 
 // bf16 generated source, 8 waves x 2 row tiles (512 stacked rows per group), k_mode12_v4
-template <int KS, bool BOXED>
+template <bool BOXED>
 int launch_v4_inst(const Mode12Params &mp, const GenSplitParams &gs, const UFragParams &uf, int nk, hipStream_t st)
 {
     typedef Mode12V4Cfg<8, 2> cfg;
-    auto kern = k_mode12_v4<8, 2, KS, BOXED, 2, 0>;
+    auto kern = k_mode12_v4<8, 2, 1, BOXED, 2, 1>;
     static bool attr_done = false;
     if (!attr_done) {
         if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, cfg::LDS_BYTES) != hipSuccess) return EXAT_ERR_HIP;
@@ -227,10 +227,9 @@ int launch_v4_inst(const Mode12Params &mp, const GenSplitParams &gs, const UFrag
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(512), cfg::LDS_BYTES, st, mp, gs, uf);
     return hipGetLastError() == hipSuccess ? EXAT_OK : EXAT_ERR_HIP;
 }
-int launch_v4_gen_bf16(const Mode12Params &mp, const GenSplitParams &gs, const UFragParams &uf, int ks, bool boxed, int nk, hipStream_t st)
+int launch_v4_gen_bf16(const Mode12Params &mp, const GenSplitParams &gs, const UFragParams &uf, bool boxed, int nk, hipStream_t st)
 {
-    if (ks == 1) return boxed ? launch_v4_inst<1, true>(mp, gs, uf, nk, st) : launch_v4_inst<1, false>(mp, gs, uf, nk, st);
-    return boxed ? launch_v4_inst<2, true>(mp, gs, uf, nk, st) : launch_v4_inst<2, false>(mp, gs, uf, nk, st);
+    return boxed ? launch_v4_inst<true>(mp, gs, uf, nk, st) : launch_v4_inst<false>(mp, gs, uf, nk, st);
 }
 
 // fp32 data on the fp16 matrix cores (two-piece split), materialised source, 4 waves x RT row tiles
@@ -319,11 +318,12 @@ int run_chain(exat_plan_s *pl, Mode12Params mp, bool generated, float *Yout, int
             else if (pl->d.L % 32 == 0 && env_int("EXAT_ZT", 1))
                 rc = rt == 4 ? launch_v3_mat_zt<8, 2>(mp, gs, uf, nk, st) : launch_v3_mat_zt<4, 2>(mp, gs, uf, nk, st);
             else rc = rt == 4 ? launch_v3_mat<float, 8, 2>(mp, gs, uf, nk, st) : launch_v3_mat<float, 4, 2>(mp, gs, uf, nk, st);
-        } else if (bf && pl->PL > 256 && env_int("EXAT_RT", 0) == 0) {
+        } else if (bf && pl->PL > 256 && ks == 1 && env_int("EXAT_RT", 0) == 0) {
             // 512-row groups, two waves per SIMD (k_mode12_v4): the tile is generated once per group, so large groups
-            // are what keeps the generator's vector work below the MFMA work
+            // are what keeps the generator's vector work below the MFMA work.  Factor ranks above 32 would need twice
+            // the generator registers, which this build does not have: they take the 384-row kernel below.
             mp.G = (pl->PL + 511) / 512;
-            rc = launch_v4_gen_bf16(mp, gs, uf, ks, boxed, nk, st);
+            rc = launch_v4_gen_bf16(mp, gs, uf, boxed, nk, st);
         } else if (bf) {
             if (rt == 3) {
                 // 384-row groups; a remainder of at most 256 rows gets a launch of its own with a smaller tile

@@ -74,7 +74,12 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void k_mode12_v4(const Mode12Param
         int tidc = tid;
         asm volatile("" : "+v"(tidc));   // per-lane offsets are derived again in every chunk (not kept live over mode 2)
         const int lane = tidc & 63, l32 = lane & 31, hi = lane >> 5, l16 = lane & 15, q16 = lane >> 4;
-        const T *ufl = (const T *)uf.Uf + ((int64_t)(wrow0 >> 5) * uf.nig) * (64 * E16) + lane * E16;
+        // Global addresses are a wave-uniform 64-bit base (scalar registers) plus a 32-bit per-lane byte offset: no
+        // 64-bit per-lane pointer is kept in vector registers and no vector instruction is spent on address arithmetic
+        const unsigned u_lane = (unsigned)lane * 16u;                                           // U fragments: 16 bytes per lane
+        const unsigned a_lane = ((unsigned)l16 * (unsigned)gs.Rpad + 8u * (unsigned)q16) * 2u;  // A pieces: row l16, 8 ranks from 8*q16
+        const char *ubase = (const char *)uf.Uf + ((int64_t)(wrow0 >> 5) * uf.nig) * 1024;
+        const uint32_t iq_lane = 4u * (unsigned)si + (unsigned)q16;                             // quad of i within a stage
         const int xs_r = l32 * ROWB + hi * 16;                                          // + ct*32*ROWB + g2*32
         const int xg_w = (16 * sj0 + l16) * ROWB + (16 * si + 4 * q16) * (int)sizeof(T); // + b*16*ROWB
         f32x16 acc[RT][CT];
@@ -111,7 +116,7 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void k_mode12_v4(const Mode12Param
         }
 
         auto stage_i = [&](int s) -> int64_t { return ia0 + (int64_t)(s < nstage ? s : nstage - 1) * EI; };
-        auto load_uf = [&](int rt, int64_t ig) -> bf16x8 { return *(const bf16x8 *)(ufl + rt * u_rt_step + ig * (64 * E16)); };
+        auto load_uf = [&](int rt, int64_t ig) -> bf16x8 { return *(const bf16x8 *)(ubase + (rt * u_rt_step + ig * (64 * E16)) * 2 + u_lane); };
         // A pieces of rows 16*si .. 16*si+15 of tile s
         auto load_a = [&](int s, bf16x8 *af) {
             const int64_t ib = stage_i(s);
@@ -119,7 +124,7 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void k_mode12_v4(const Mode12Param
             for (int v = 0; v < 2; v++)
 #pragma unroll
                 for (int ks = 0; ks < KS; ks++)
-                    af[v * KS + ks] = *(const bf16x8 *)(gs.Asp + ((int64_t)v * gs.Irows + ib + 16 * si + l16) * gs.Rpad + 32 * ks + 8 * q16);
+                    af[v * KS + ks] = *(const bf16x8 *)((const char *)gs.Asp + ((((int64_t)v * gs.Irows + ib + 16 * si) * gs.Rpad + 32 * ks) * 2) + a_lane);
         };
         // low-rank part of the tile whose A pieces are in af: smallest terms first
         auto gen_lr = [&](f32x4v *dst, const bf16x8 *af) {
@@ -162,7 +167,7 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void k_mode12_v4(const Mode12Param
         auto nstep = [&](auto uc, int64_t ib1, unsigned char *oth, const f32x4v *lrs) {
             constexpr int u = decltype(uc)::value, st = u / NQ, b = u % NQ, w0 = 2 * b, w1 = 2 * b + 1;
             if constexpr (st == 0) {
-                const uint32_t x = ckey[b] ^ (uint32_t)((ib1 + 16 * si + 4 * q16) >> 2);
+                const uint32_t x = ckey[b] ^ ((uint32_t)(ib1 >> 2) + iq_lane);
                 nw[w0] = x ^ (x >> 16);
             } else if constexpr (st == 1) {
                 nw[w1] = nw[w0] * 0x21f0aaadu; nw[w0] *= 0x7feb352du;
