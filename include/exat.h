@@ -252,6 +252,17 @@ int64_t exat_cpals_workspace_floats(int32_t L, int32_t M, int32_t N, int32_t P);
 int exat_cpals(const float *Y, int32_t L, int32_t M, int32_t N, int32_t P, int32_t R, int32_t sweeps,
                float *A, float *B, float *C, float *work, void *stream);
 
+/* exat_cpals for callers that cannot allocate device memory and have no workspace to hand over (code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc): the same sweeps, with the workspace taken
+ * from a static device array of 4194304 floats (16 MiB) that every GPU the library runs on
+ * holds until the process ends.  The call allocates nothing; its first use on a device looks the array's address up.
+ * Problems whose exat_cpals_workspace_floats(L,M,N,P) exceeds that size are rejected with SHAPE (cfg1's and cfg2's
+ * proxy tensors fit, cfg3's do not).  All calls on one GPU share the one array: calls that overlap in time on the
+ * same GPU (different streams, different host threads) race and must be serialised by the caller.
+ * Same arguments, results (bit for bit) and limits as exat_cpals.  Errors: NULL, SHAPE, HIP. */
+int exat_cpals_noalloc(const float *Y, int32_t L, int32_t M, int32_t N, int32_t P, int32_t R, int32_t sweeps,
+                       float *A, float *B, float *C, void *stream);
+
 /* ---- joining the replicas: the stacked least-squares problem (Eq. 4) -------------------------------------
  * After the P decompositions and the alignment of their columns, the factor of the full tensor (up to one common
  * permutation and scaling, A Pi Sigma in the paper's notation) is the least-squares solution X (I x R) of

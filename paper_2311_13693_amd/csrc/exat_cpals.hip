@@ -253,3 +253,35 @@ int exat_cpals(const float *Y, int32_t L, int32_t M, int32_t N, int32_t P, int32
 }
 
 }  // extern "C"
+
+// ---- exat_cpals for callers that cannot allocate: the workspace is a static device array ----
+namespace {
+constexpr int64_t kScratchFloats = 4LL << 20;   // 16 MiB per GPU, held until the process ends
+constexpr int kMaxDevices = 64;
+float *g_scratch_ptr[kMaxDevices] = {};         // device address of `scratch` on each GPU (each holds its own copy)
+}  // namespace
+static __device__ __align__(256) float scratch[kScratchFloats];
+
+extern "C" {
+
+int exat_cpals_noalloc(const float *Y, int32_t L, int32_t M, int32_t N, int32_t P, int32_t R, int32_t sweeps, float *A, float *B,
+                       float *C, void *stream)
+{
+    if (!Y || !A || !B || !C) return EXAT_ERR_NULL;
+    if (L < 1 || M < 1 || N < 1 || R < 1 || P < 1 || sweeps < 0) return EXAT_ERR_SHAPE;
+    if (L > CP_MAX || M > CP_MAX || N > CP_MAX || R > CP_MAX || P > (1 << 20)) return EXAT_ERR_SHAPE;
+    if (exat_cpals_workspace_floats(L, M, N, P) > kScratchFloats) return EXAT_ERR_SHAPE;   // beyond the static workspace
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return EXAT_ERR_HIP;
+    if (!g_scratch_ptr[dev]) {
+        // in host code the array's name is a stand-in, not a device address: ask the runtime for this GPU's copy, once
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) { (void)hipGetLastError(); return EXAT_ERR_HIP; }
+        g_scratch_ptr[dev] = (float *)ptr;
+    }
+    // nothing of the workspace has to start at zero: every sweep writes the permuted copies and the slab sums before
+    // it reads them
+    return exat_cpals(Y, L, M, N, P, R, sweeps, A, B, C, g_scratch_ptr[dev], stream);
+}
+
+}  // extern "C"
