@@ -246,11 +246,18 @@ int exat_stage1_last_timing(exat_stage1_t s, float *ms_mode12, float *ms_mode3);
  *   A,B,C  device, in: start values, out: result; per replica column-major L x R, M x R, N x R:
  *          A[l + L*(r + R*p)] etc.
  *   work   device scratch of exat_cpals_workspace_floats(L,M,N,P) floats (two permuted copies of Y), caller-owned
- * Limits: L, M, N, R <= 64.  The normal matrices must be positive definite (they are for generic data); nothing
- * checks it.  Asynchronous on `stream`.  Errors: NULL, SHAPE, HIP. */
+ * Limits: L, M, N, R <= 64.  The normal matrices must be positive definite (they are for generic data): Alg. 1
+ * writes a pseudo-inverse, which this solve does not provide, so a replica whose normal matrix loses rank ends in
+ * NaN or meaningless factors.  exat_cpals_checked reports that: `status` (device, P int32, written by the call)
+ * counts, per replica, the factor updates whose R x R normal matrix showed a zero, negative or NaN pivot in the
+ * Cholesky factorisation (0 = every update was positive definite); the caller restarts such a replica from other
+ * start values (or drops it), as the restart loop of Alg. 2 does with replicas that fail.  The arithmetic is that of
+ * exat_cpals, bit for bit.  Asynchronous on `stream`.  Errors: NULL, SHAPE, HIP. */
 int64_t exat_cpals_workspace_floats(int32_t L, int32_t M, int32_t N, int32_t P);
 int exat_cpals(const float *Y, int32_t L, int32_t M, int32_t N, int32_t P, int32_t R, int32_t sweeps,
                float *A, float *B, float *C, float *work, void *stream);
+int exat_cpals_checked(const float *Y, int32_t L, int32_t M, int32_t N, int32_t P, int32_t R, int32_t sweeps,
+                       float *A, float *B, float *C, float *work, int32_t *status, void *stream);
 
 /* exat_cpals for callers that cannot allocate device memory and have no workspace to hand over (code under HIP
  * graph capture, tight serving loops, harnesses that forbid hipMalloc): the same sweeps, with the workspace taken

@@ -26,6 +26,7 @@ struct CpUpdate {
     float *F0;              // the updated factor, per replica column-major D0 x R
     float *part;            // [replica][slab][d0][R] partial MTTKRP results
     int D0, D1, D2, R, NS, DS;   // NS slabs of DS values of d2
+    int32_t *status;        // optional, [replica]: incremented by every update whose normal matrix has a non-positive pivot
 };
 
 // Y2[m + M(l + Ln)] and Y3[n + N(l + Lm)] from Y[l + L(m + Mn)], all replicas
@@ -150,8 +151,11 @@ __global__ __launch_bounds__(256) void k_cpals_solve(const CpUpdate p)
     // Cholesky factor, right-looking, one barrier per column: every thread scales the entries of column j that it
     // needs by the pivot's inverse square root on the fly for its share of the trailing triangle, and the scaled
     // column goes to a second matrix Lf (nobody reads column j of G again), so reading and scaling do not collide.
+    bool bad = false;   // the same in every thread: all read the same pivots
     for (int j = 0; j < R; j++) {
-        const float inv = 1.0f / sqrtf(G[j * GS + j]);
+        const float piv = G[j * GS + j];
+        bad = bad || !(piv > 0.0f);   // zero, negative or NaN: the normal matrix is not positive definite in fp32
+        const float inv = 1.0f / sqrtf(piv);
         for (int t = j + tid; t < R; t += 256) Lf[t * GS + j] = G[t * GS + j] * inv;   // t = j: the pivot's square root
         const int n = R - 1 - j;   // trailing triangle: rows t > j, columns j < c <= t
         for (int e = tid; e < n * n; e += 256) {
@@ -163,6 +167,7 @@ __global__ __launch_bounds__(256) void k_cpals_solve(const CpUpdate p)
     // one row of Mx per thread, held in registers: L z = m, then L^T o = z.  The loops are unrolled to the
     // instantiation's largest rank, so the row is indexed statically and the reads of the factor (the same
     // address for every thread) do not depend on the data.
+    if (bad && tid == 0 && p.status) p.status[rep] += 1;   // launches on one stream: nothing else touches this word now
     if (tid < D0) {
         float m[RS];
 #pragma unroll
@@ -223,8 +228,20 @@ int64_t exat_cpals_workspace_floats(int32_t L, int32_t M, int32_t N, int32_t P)
     return 2 * (int64_t)L * M * N * P + (int64_t)P * slabs_for(maxd, P) * CP_MAX * CP_MAX;
 }
 
+__global__ void k_cpals_clear_status(int32_t *status, int P)
+{
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t < P) status[t] = 0;
+}
+
 int exat_cpals(const float *Y, int32_t L, int32_t M, int32_t N, int32_t P, int32_t R, int32_t sweeps, float *A, float *B,
                float *C, float *work, void *stream)
+{
+    return exat_cpals_checked(Y, L, M, N, P, R, sweeps, A, B, C, work, nullptr, stream);
+}
+
+int exat_cpals_checked(const float *Y, int32_t L, int32_t M, int32_t N, int32_t P, int32_t R, int32_t sweeps, float *A, float *B,
+                       float *C, float *work, int32_t *status, void *stream)
 {
     if (!Y || !A || !B || !C || !work) return EXAT_ERR_NULL;
     if (L < 1 || M < 1 || N < 1 || R < 1 || P < 1 || sweeps < 0) return EXAT_ERR_SHAPE;
@@ -232,13 +249,17 @@ int exat_cpals(const float *Y, int32_t L, int32_t M, int32_t N, int32_t P, int32
     hipStream_t st = (hipStream_t)stream;
     const int64_t total = (int64_t)L * M * N * P;
     float *Y2 = work, *Y3 = work + total, *part = work + 2 * total;
+    if (status) {   // a fill kernel, not a memset: the call may be recorded into a graph
+        hipLaunchKernelGGL(k_cpals_clear_status, dim3((unsigned)((P + 255) / 256)), dim3(256), 0, st, status, P);
+        if (hipGetLastError() != hipSuccess) return EXAT_ERR_HIP;
+    }
     if (sweeps > 0) {
         hipLaunchKernelGGL(k_cpals_permute, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, Y, Y2, Y3, L, M, N, total);
         if (hipGetLastError() != hipSuccess) return EXAT_ERR_HIP;
     }
     auto update = [&](const float *Yp, float *F0, const float *F1, const float *F2, int D0, int D1, int D2) {
         CpUpdate u;
-        u.Yp = Yp; u.F0 = F0; u.F1 = F1; u.F2 = F2; u.part = part; u.D0 = D0; u.D1 = D1; u.D2 = D2; u.R = R; u.NS = 1; u.DS = D2;
+        u.Yp = Yp; u.F0 = F0; u.F1 = F1; u.F2 = F2; u.part = part; u.status = status; u.D0 = D0; u.D1 = D1; u.D2 = D2; u.R = R; u.NS = 1; u.DS = D2;
         if (R <= 16) return launch_update<4>(u, P, st);
         if (R <= 32) return launch_update<8>(u, P, st);
         return launch_update<16>(u, P, st);

@@ -18,7 +18,7 @@ EXPORTS = ["exat_plan_create", "exat_plan_destroy", "exat_set_factors", "exat_co
            "exat_plan_set_timing", "exat_plan_last_timing", "exat_plan_timing_of",
            "exat_stage1_create", "exat_stage1_destroy", "exat_stage1_dims", "exat_stage1_apply", "exat_stage1_apply_host",
            "exat_stage1_set_timing", "exat_stage1_last_timing", "exat_cpals_workspace_floats", "exat_cpals",
-           "exat_cpals_noalloc",
+           "exat_cpals_checked", "exat_cpals_noalloc",
            "exat_ls_workspace_floats", "exat_ls", "exat_strerror"]
 
 
@@ -89,6 +89,7 @@ def lib():
         L.exat_stage1_last_timing.argtypes = [vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_float)]
         L.exat_cpals_workspace_floats.argtypes = [i32, i32, i32, i32]
         L.exat_cpals.argtypes = [vp, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp]
+        L.exat_cpals_checked.argtypes = [vp, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp]
         L.exat_cpals_noalloc.argtypes = [vp, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp]
         L.exat_ls_workspace_floats.argtypes = [i32, i32, i32, i32]
         L.exat_ls.argtypes = [vp, i64, i32, i32, i32, vp, i32, i32, ctypes.c_float, vp, vp, vp, vp]
@@ -295,6 +296,19 @@ def cpals(Y, L, M, N, P, R, sweeps, A, B, C, work=None, stream=None):
         work = torch.empty(lib().exat_cpals_workspace_floats(L, M, N, P), dtype=torch.float32, device="cuda")
     _check(lib().exat_cpals(_ptr(Y), L, M, N, P, R, sweeps, _ptr(A), _ptr(B), _ptr(C), _ptr(work), _stream_handle(stream)))
     return A, B, C
+
+
+def cpals_checked(Y, L, M, N, P, R, sweeps, A, B, C, work=None, status=None, stream=None):
+    """cpals that also reports, per replica, how many factor updates met a normal matrix that was not positive definite
+    (int32 CUDA tensor of P entries, all zero in a healthy run).  Returns (A, B, C, status)."""
+    import torch
+    if work is None:
+        work = torch.empty(lib().exat_cpals_workspace_floats(L, M, N, P), dtype=torch.float32, device="cuda")
+    if status is None:
+        status = torch.empty(P, dtype=torch.int32, device="cuda")
+    _check(lib().exat_cpals_checked(_ptr(Y), L, M, N, P, R, sweeps, _ptr(A), _ptr(B), _ptr(C), _ptr(work), _ptr(status),
+                                    _stream_handle(stream)))
+    return A, B, C, status
 
 
 def cpals_noalloc(Y, L, M, N, P, R, sweeps, A, B, C, stream=None):

@@ -101,3 +101,32 @@ def test_exact_low_rank_tensor_is_recovered():
         rec = oracle.cp_reconstruct(*(F[p * D * R:(p + 1) * D * R].cpu().numpy().reshape((D, R), order="F")
                                       for F, D in ((A, L), (B, M), (C, N))))
         assert _rel(rec, Ys[p].astype(np.float64)) <= 1e-4
+
+
+def test_checked_variant_reports_replicas_whose_normal_matrix_is_not_positive_definite():
+    """Alg. 1 applies a pseudo-inverse; the Cholesky solve cannot.  A replica whose start factor B has a zero column gives
+    the first update a normal matrix (C^T C) * (B^T B) with a zero row and column: exat_cpals_checked must count it for
+    that replica, leave the healthy replicas' status at zero, and compute them exactly as exat_cpals does."""
+    L, M, N, R, P, sweeps = 12, 10, 8, 4, 3, 2
+    Ys, starts = _problem(43, L, M, N, R, P)
+    starts = [tuple(f.copy() for f in s) for s in starts]
+    starts[1][1][:, 2] = 0.0                      # replica 1: column 2 of the start value of B
+    Yd = _dev_tensor(Ys)
+    A, B, C = (_dev_factors(starts, i) for i in range(3))
+    A0, B0, C0 = A.clone(), B.clone(), C.clone()
+    exat.cpals(Yd, L, M, N, P, R, sweeps, A0, B0, C0)
+    _, _, _, status = exat.cpals_checked(Yd, L, M, N, P, R, sweeps, A, B, C)
+    torch.cuda.synchronize()
+    st = status.cpu().numpy()
+    print("  status", st, flush=True)
+    assert st[0] == 0 and st[2] == 0 and st[1] >= 1
+    for F, F0, D in ((A, A0, L), (B, B0, M), (C, C0, N)):
+        for p in (0, 2):
+            assert torch.equal(F[p * D * R:(p + 1) * D * R], F0[p * D * R:(p + 1) * D * R])
+            assert torch.isfinite(F[p * D * R:(p + 1) * D * R]).all()
+    # a second call on healthy input clears the counters
+    Ys2, starts2 = _problem(44, L, M, N, R, P)
+    A, B, C = (_dev_factors(starts2, i) for i in range(3))
+    exat.cpals_checked(_dev_tensor(Ys2), L, M, N, P, R, sweeps, A, B, C, status=status)
+    torch.cuda.synchronize()
+    assert (status.cpu().numpy() == 0).all()
