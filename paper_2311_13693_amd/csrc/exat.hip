@@ -269,6 +269,9 @@ int run_chain(exat_plan_s *pl, Mode12Params mp, bool generated, float *Yout, int
         if (bf && generated && pl->PL > 256 && forced != 2 && forced != 4) rt = 3;
         // the bf16 generator has no 8-wave build
         if (bf && generated && rt == 4) rt = 3;
+        // bf16 materialised source: the 8-wave build spills around its mode-2 phase and measured 2.5 times slower than the
+        // 4-wave one on a 10000 x 10000 x 256 slab (621 against 251 ms)
+        if (bf && !generated && forced == 0) rt = 2;
         // a small box (one streamed block) with 512-row groups would not give every compute unit a workgroup
         if (!generated && rt == 4 && forced == 0 && (mp.k1 - mp.k0) * ((pl->PL + 511) / 512) < 256) rt = 2;
     }

@@ -308,8 +308,11 @@ __global__ __launch_bounds__(64 * NW, WPS) void k_mode12_v3(const Mode12Params p
         // one stage: MFMAs of stage s (X tile in LDS buffer PH, A fragments in register set PH) interleaved with
         // the production of the X tile of stage s+1 (into the other buffer), the low-rank MFMAs of stage s+2 and
         // the reload of the A fragment registers for stage s+2
-        // fp32 materialised source: the stage barrier sits mid-stage (see stage); the bf16 build of that form spills
-        constexpr bool MIDBAR = SRC == SRC_MATERIALISED && sizeof(T) == 4;
+        // fp32 sources: the stage barrier sits mid-stage (see stage); the bf16 build of that form spills.  The fp32 generated
+        // source qualifies with two waves per SIMD: its stage holds 64 fp32 MFMAs per wave and one quad of noise per lane,
+        // so the whole tile of stage s+1 is produced under the first half of the MFMAs.
+        constexpr bool MIDBAR_GEN = SRC == SRC_GENERATED && sizeof(T) == 4 && NW == 8;
+        constexpr bool MIDBAR = (SRC == SRC_MATERIALISED && sizeof(T) == 4) || MIDBAR_GEN;
         frag_t bx0[MIDBAR ? CT : 1];   // first-group X fragments of the stage about to run
         auto stage = [&](auto sic, int s) {
             constexpr int SI = decltype(sic)::value;  // s mod UNR
@@ -318,6 +321,42 @@ __global__ __launch_bounds__(64 * NW, WPS) void k_mode12_v3(const Mode12Params p
             unsigned char *oth = smem + (PH ^ 1) * XBUF;
             const int64_t ib1 = stage_i(s + 1);
             const int64_t ig2 = stage_i(s + DU) / GI;
+            if constexpr (MIDBAR_GEN) {
+                // As below, for the generated source: the noise steps and the generator's MFMAs of the stage all sit in the
+                // first half (the MFMAs of the first i group), so that every wave has stored its part of the tile of stage
+                // s+1 when it reaches the barrier between the two halves.
+                frag_t bx1[CT];
+#pragma unroll
+                for (int ct = 0; ct < CT; ct++) bx1[ct] = *(const frag_t *)(cur + xs_r + ct * 32 * ROWB + 32);
+                __builtin_amdgcn_sched_barrier(0);
+                constexpr int NH = NMAIN / 2;
+                static_for<NMAIN>([&](auto mc) {
+                    constexpr int m = decltype(mc)::value, g2 = m / (RT * CT), rt = (m / CT) % RT, ct = m % CT;
+                    if constexpr (m == NH) {
+                        __syncthreads();
+#pragma unroll
+                        for (int c2 = 0; c2 < CT; c2++) bx0[c2] = *(const frag_t *)(oth + xs_r + c2 * 32 * ROWB);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    const frag_t &bxe = g2 == 0 ? bx0[ct] : bx1[ct];
+                    if constexpr (ZT) mma_frag<T>::mma(acc[rt][ct], bxe, ufr[US][rt][g2]);
+                    else mma_frag<T>::mma(acc[rt][ct], ufr[US][rt][g2], bxe);
+                    if constexpr (ct == CT - 1) ufr[US][rt][g2] = load_uf(rt, ig2 + g2);  // last use this stage: refill for stage s+DU
+                    __builtin_amdgcn_sched_barrier(0);
+                    if constexpr (m < NH) {
+                        // steps u0..u1 of the NUOP noise steps and generator MFMAs g0..g1 of NGEN behind main MFMA m
+                        constexpr int u0 = m * NUOP / NH, u1 = (m + 1) * NUOP / NH, g0 = m * NGEN / NH, g1 = (m + 1) * NGEN / NH;
+                        static_for<u1 - u0>([&](auto uc) { uop(ic<u0 + decltype(uc)::value>(), ib1, oth, accg[PH ^ 1]); });
+                        __builtin_amdgcn_sched_barrier(0);
+                        static_for<g1 - g0>([&](auto gc) {
+                            gen_one(g0 + decltype(gc)::value, accg[PH], afrag[PH % NAB]);
+                            __builtin_amdgcn_sched_barrier(0);
+                        });
+                        if constexpr (g1 == NGEN && g0 < NGEN) load_a(s + 2 + NAB, afrag[PH % NAB]);  // these A pieces are free now
+                    }
+                });
+                return;
+            }
             if constexpr (MIDBAR) {
                 // Materialised fp32 source: the tile of stage s+1 is complete in LDS as soon as every wave has stored its
                 // part at the start of stage s, so the stage's barrier sits between its two halves (the MFMAs of the
