@@ -78,7 +78,11 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void k_mode12_v4(const Mode12Param
         // 64-bit per-lane pointer is kept in vector registers and no vector instruction is spent on address arithmetic
         const unsigned u_lane = (unsigned)lane * 16u;                                           // U fragments: 16 bytes per lane
         const unsigned a_lane = ((unsigned)l16 * (unsigned)gs.Rpad + 8u * (unsigned)q16) * 2u;  // A pieces: row l16, 8 ranks from 8*q16
-        const char *ubase = (const char *)uf.Uf + ((int64_t)(wrow0 >> 5) * uf.nig) * 1024;
+        // buffer addressing: the descriptor holds the base, a scalar register the wave-uniform part of the offset, and the
+        // one vector register u_lane / a_lane the per-lane part, so that a request costs no vector instruction at all
+        const __amdgpu_buffer_rsrc_t urs = __builtin_amdgcn_make_buffer_rsrc(
+            (void *)((const char *)uf.Uf + ((int64_t)(wrow0 >> 5) * uf.nig) * 1024), 0, (int)(RT * u_rt_step * 2), 0x00020000);
+        const __amdgpu_buffer_rsrc_t ars = __builtin_amdgcn_make_buffer_rsrc((void *)gs.Asp, 0, (int)(2 * gs.Irows * gs.Rpad * 2), 0x00020000);
         const uint32_t iq_lane = 4u * (unsigned)si + (unsigned)q16;                             // quad of i within a stage
         const int xs_r = l32 * ROWB + hi * 16;                                          // + ct*32*ROWB + g2*32
         const int xg_w = (16 * sj0 + l16) * ROWB + (16 * si + 4 * q16) * (int)sizeof(T); // + b*16*ROWB
@@ -116,7 +120,9 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void k_mode12_v4(const Mode12Param
         }
 
         auto stage_i = [&](int s) -> int64_t { return ia0 + (int64_t)(s < nstage ? s : nstage - 1) * EI; };
-        auto load_uf = [&](int rt, int64_t ig) -> bf16x8 { return *(const bf16x8 *)(ubase + (rt * u_rt_step + ig * (64 * E16)) * 2 + u_lane); };
+        auto load_uf = [&](int rt, int64_t ig) -> bf16x8 {
+            return __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(urs, (int)u_lane, (int)((rt * u_rt_step + ig * (64 * E16)) * 2), 0));
+        };
         // A pieces of rows 16*si .. 16*si+15 of tile s
         auto load_a = [&](int s, bf16x8 *af) {
             const int64_t ib = stage_i(s);
@@ -124,7 +130,8 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void k_mode12_v4(const Mode12Param
             for (int v = 0; v < 2; v++)
 #pragma unroll
                 for (int ks = 0; ks < KS; ks++)
-                    af[v * KS + ks] = *(const bf16x8 *)((const char *)gs.Asp + ((((int64_t)v * gs.Irows + ib + 16 * si) * gs.Rpad + 32 * ks) * 2) + a_lane);
+                    af[v * KS + ks] = __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(
+                        ars, (int)a_lane, (int)((((int64_t)v * gs.Irows + ib + 16 * si) * gs.Rpad + 32 * ks) * 2), 0));
         };
         // low-rank part of the tile whose A pieces are in af: smallest terms first
         auto gen_lr = [&](f32x4v *dst, const bf16x8 *af) {
@@ -277,6 +284,12 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void k_mode12_v4(const Mode12Param
         };
 
         // ---- prologue ----
+        load_a(0, afrag[0]);
+        load_a(1, afrag[1]);
+        gen_lr(lr[0], afrag[0]);
+        load_a(2, afrag[0]);
+        gen_lr(lr[1], afrag[1]);
+        load_a(3, afrag[1]);
 #pragma unroll
         for (int d = 0; d < DU; d++) {
             const int64_t igd = stage_i(d) / GI;
@@ -285,14 +298,8 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void k_mode12_v4(const Mode12Param
 #pragma unroll
                 for (int g2 = 0; g2 < 2; g2++) ufr[d][rt][g2] = load_uf(rt, igd + g2);
         }
-        load_a(0, afrag[0]);
-        load_a(1, afrag[1]);
-        gen_lr(lr[0], afrag[0]);
-        load_a(2, afrag[0]);
         __syncthreads();  // the previous chunk's epilogue is done with the LDS
         noise_store(0, smem, lr[0]);
-        gen_lr(lr[1], afrag[1]);
-        load_a(3, afrag[1]);
         __syncthreads();
 
         int s = 0;

@@ -29,11 +29,18 @@ __device__ __forceinline__ void mode2_chunk(const Mode12Params &p, const void *V
 {
     constexpr int COLS = 32 * CT, ZST = COLS + 4;
     constexpr int MP = 32 * MTC;  // = p.Mpad; a constant here so that the 32 Q accesses of a tile differ by immediates
-    const int l32 = lane & 31, hi = lane >> 5;
 #pragma unroll
     for (int rt = 0; rt < RT; rt++) {
         const int q0 = wrow0 + rt * 32;  // wave-uniform
         if (q0 < p.PL) {
+            // The lane number is made opaque here, so that every per-lane address below is derived after the stage loop,
+            // where registers are free.  Left visible, the addresses of the Q rows and V fragments are loop invariants: the
+            // compiler computes them once per workgroup, spills them, and reloads each in front of its access behind a full
+            // memory wait -- some forty dependent round trips to memory per tile and chunk.
+            int ln = lane;
+            asm volatile("" : "+v"(ln));
+            const int l32 = ln & 31, hi = ln >> 5;
+            lane = ln;
 #pragma unroll
             for (int ct = 0; ct < CT; ct++)
 #pragma unroll
