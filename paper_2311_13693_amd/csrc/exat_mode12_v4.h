@@ -26,13 +26,16 @@ struct Mode12V4Cfg {
     static constexpr int XBUF_BYTES = COLS * ROWB;
     static constexpr int ZST = COLS + 4;
     static constexpr int EPI_BYTES = NW * 32 * ZST * 4;
-    static constexpr int LDS_BYTES = 2 * XBUF_BYTES > EPI_BYTES ? 2 * XBUF_BYTES : EPI_BYTES;
+    static constexpr int MAX_XBUFS = 8;
+    static constexpr int LDS_BYTES = MAX_XBUFS * XBUF_BYTES > EPI_BYTES ? MAX_XBUFS * XBUF_BYTES : EPI_BYTES;
 };
 
 // KS: 32-wide steps of the factor rank (R <= 32*KS); BOXED: the box is a proper sub-range in i; DU: register sets of
 // U fragments (requested DU stages ahead); SCHED: 0 = leave the stage to the compiler's scheduler, 1 = interleave
-// matrix and vector instructions through scheduling-group hints
-template <int NW, int RT, int KS, bool BOXED, int DU, int SCHED>
+// matrix and vector instructions through scheduling-group hints; NXB: X tiles in the LDS ring (2, 4 or 8).  A stage
+// reads tile s from slot s mod NXB and writes tile s + NXB/2, and the workgroup meets at a barrier only after every
+// NXB/2-th stage: between two barriers the slots read and the slots written are disjoint.
+template <int NW, int RT, int KS, bool BOXED, int DU, int SCHED, int NXB = 2>
 __global__ __launch_bounds__(64 * NW, NW / 4) void k_mode12_v4(const Mode12Params p, const GenSplitParams gs, const UFragParams uf)
 {
     typedef Mode12V4Cfg<NW, RT> cfg;
@@ -42,8 +45,10 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void k_mode12_v4(const Mode12Param
     constexpr int SJW = 16 / NW;            // 16-column blocks of the generated tile per wave (all in one 16-row half)
     constexpr int NQ = SJW;                 // quads of 4 consecutive i per lane and stage
     constexpr int NTERM = 3;                // a_m b_h + a_h b_m + a_h b_h
-    constexpr int UNR = lcm_i(2, DU);
+    constexpr int W = NXB / 2;              // a stage produces the tile W stages ahead
+    constexpr int UNR = lcm_i(lcm_i(2, DU), NXB);
     static_assert(NW == 4 || NW == 8, "4 or 8 waves");
+    static_assert((NXB == 2 || NXB == 4 || NXB == 8) && NXB <= cfg::MAX_XBUFS && (SCHED == 1 || NXB == 2), "ring of 2, 4 or 8 X tiles");
     extern __shared__ __align__(16) unsigned char smem[];
 
     const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -222,8 +227,9 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void k_mode12_v4(const Mode12Param
         auto stage = [&](auto sic, int s) {
             constexpr int SI = decltype(sic)::value;  // s mod UNR
             constexpr int PH = SI & 1, US = SI % DU;
-            const unsigned char *cur = smem + PH * XBUF;
-            unsigned char *oth = smem + (PH ^ 1) * XBUF;
+            constexpr int PN = (PH + W) & 1, PG = PN ^ 1;   // parities of the tile whose noise / whose low-rank part this stage makes
+            const unsigned char *cur = smem + (SI % NXB) * XBUF;
+            unsigned char *oth = smem + ((SI + W) % NXB) * XBUF;
             const int64_t ig2 = stage_i(s + DU) / GI;
             constexpr int NGEN = NTERM * KS * SJW, NMAIN = 2 * RT * CT;
             // X fragment f = g2*CT + ct: columns 32 ct .. 32 ct + 31, i group g2
@@ -244,12 +250,12 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void k_mode12_v4(const Mode12Param
                         ufr[US][rt][g2] = load_uf(rt, ig2 + g2);   // refill for stage s+DU
                     }
             } else {
-                const int64_t ib1 = stage_i(s + 1);
+                const int64_t ib1 = stage_i(s + W);
                 constexpr int NU = NSTEP * NQ, NFRONT = NU / 6;
                 constexpr int MG = (NMAIN * 2) / 3;                 // the generator's MFMAs follow main MFMAs 0 .. MG-1
-                constexpr int W = 2 * NMAIN + NGEN;                 // total weight: main 2, generator 1
+                constexpr int WT = 2 * NMAIN + NGEN;                // total weight: main 2, generator 1
                 auto gens_before = [](int m) constexpr { return (m * NGEN + MG - 1) / MG < NGEN ? (m * NGEN + MG - 1) / MG : NGEN; };
-                auto step_at = [](int w) constexpr { return NFRONT + w * (NU - NFRONT) / W; };
+                auto step_at = [](int w) constexpr { return NFRONT + w * (NU - NFRONT) / WT; };
                 // main MFMA m = (g2*CT + ct)*RT + rt: an X fragment serves RT consecutive MFMAs and is requested BXA
                 // fragments ahead (a ring of BXA + 1 register sets)
                 constexpr int BXA = 2;
@@ -257,7 +263,7 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void k_mode12_v4(const Mode12Param
 #pragma unroll
                 for (int f = 0; f < BXA; f++) bx[f] = load_bx(f);
                 __builtin_amdgcn_sched_barrier(0);
-                static_for<NFRONT>([&](auto uc) { nstep(uc, ib1, oth, lr[PH ^ 1]); });
+                static_for<NFRONT>([&](auto uc) { nstep(uc, ib1, oth, lr[PN]); });
                 __builtin_amdgcn_sched_barrier(0);
                 static_for<NMAIN>([&](auto mc) {
                     constexpr int m = decltype(mc)::value, f = m / RT, rt = m % RT, g2 = f / CT, ct = f % CT;
@@ -266,17 +272,17 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void k_mode12_v4(const Mode12Param
                     if constexpr (ct == CT - 1) ufr[US][rt][g2] = load_uf(rt, ig2 + g2);   // last use this stage: refill for stage s+DU
                     __builtin_amdgcn_sched_barrier(0);
                     constexpr int g0 = gens_before(m), g1 = gens_before(m + 1), wb = 2 * m + g0;
-                    static_for<step_at(wb + 2) - step_at(wb)>([&](auto uc) { nstep(ic<step_at(wb) + decltype(uc)::value>(), ib1, oth, lr[PH ^ 1]); });
+                    static_for<step_at(wb + 2) - step_at(wb)>([&](auto uc) { nstep(ic<step_at(wb) + decltype(uc)::value>(), ib1, oth, lr[PN]); });
                     __builtin_amdgcn_sched_barrier(0);
                     static_for<g1 - g0>([&](auto gc) {
                         constexpr int n = g0 + decltype(gc)::value, term = n % NTERM, ks = (n / NTERM) % KS, b = n / (NTERM * KS);
                         constexpr int av = term == 0 ? 1 : 0, bv = term == 1 ? 1 : 0;   // a_m b_h, a_h b_m, a_h b_h
                         const f32x4v zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
-                        lr[PH][b] = gen_piece<T>::mfma(afrag[PH][av * KS + ks], bfrag[(bv * KS + ks) * SJW + b], (term == 0 && ks == 0) ? zero4 : lr[PH][b]);
-                        if constexpr (n == NGEN - 1) load_a(s + 4, afrag[PH]);             // these A pieces are free now
+                        lr[PG][b] = gen_piece<T>::mfma(afrag[PG][av * KS + ks], bfrag[(bv * KS + ks) * SJW + b], (term == 0 && ks == 0) ? zero4 : lr[PG][b]);
+                        if constexpr (n == NGEN - 1) load_a(s + W + 3, afrag[PG]);         // these A pieces are free now
                         __builtin_amdgcn_sched_barrier(0);
                         constexpr int v0 = step_at(wb + 2 + n - g0), v1 = step_at(wb + 3 + n - g0);
-                        static_for<v1 - v0>([&](auto uc) { nstep(ic<v0 + decltype(uc)::value>(), ib1, oth, lr[PH ^ 1]); });
+                        static_for<v1 - v0>([&](auto uc) { nstep(ic<v0 + decltype(uc)::value>(), ib1, oth, lr[PN]); });
                         __builtin_amdgcn_sched_barrier(0);
                     });
                 });
@@ -284,36 +290,49 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void k_mode12_v4(const Mode12Param
         };
 
         // ---- prologue ----
-        load_a(0, afrag[0]);
-        load_a(1, afrag[1]);
-        gen_lr(lr[0], afrag[0]);
-        load_a(2, afrag[0]);
-        gen_lr(lr[1], afrag[1]);
-        load_a(3, afrag[1]);
+        // Tiles 0 .. W-1 go to the ring, the low-rank part of tile W to its register set, and the A pieces of tiles W+1 and
+        // W+2 to theirs.  Order of the requests: all A pieces first, the U fragments last.  The compiler derives the wait in
+        // front of a stage's first generator MFMA from the smaller of two counts of requests issued after the A pieces it
+        // reads, the one on the way in from here and the one around the loop; with the U requests ahead of the A pieces that
+        // count made every other stage wait for requests issued a fraction of a stage before.
+        {
+            bf16x8 at[W + 3][2 * KS];
 #pragma unroll
-        for (int d = 0; d < DU; d++) {
-            const int64_t igd = stage_i(d) / GI;
+            for (int t = 0; t < W + 3; t++) load_a(t, at[t]);
 #pragma unroll
-            for (int rt = 0; rt < RT; rt++)
+            for (int d = 0; d < DU; d++) {
+                const int64_t igd = stage_i(d) / GI;
 #pragma unroll
-                for (int g2 = 0; g2 < 2; g2++) ufr[d][rt][g2] = load_uf(rt, igd + g2);
+                for (int rt = 0; rt < RT; rt++)
+#pragma unroll
+                    for (int g2 = 0; g2 < 2; g2++) ufr[d][rt][g2] = load_uf(rt, igd + g2);
+            }
+            __syncthreads();  // the previous chunk's epilogue is done with the LDS
+#pragma unroll
+            for (int t = 0; t < W; t++) {
+                f32x4v l0[NQ];
+                gen_lr(l0, at[t]);
+                noise_store(t, smem + t * XBUF, l0);
+            }
+            gen_lr(lr[W & 1], at[W]);
+#pragma unroll
+            for (int q = 0; q < 2 * KS; q++) { afrag[(W + 1) & 1][q] = at[W + 1][q]; afrag[W & 1][q] = at[W + 2][q]; }
+            __syncthreads();
         }
-        __syncthreads();  // the previous chunk's epilogue is done with the LDS
-        noise_store(0, smem, lr[0]);
-        __syncthreads();
 
         int s = 0;
         for (; s + UNR <= nstage; s += UNR)
             static_for<UNR>([&](auto c) {
                 stage(c, s + decltype(c)::value);
-                __syncthreads();
+                if constexpr ((decltype(c)::value + 1) % W == 0) __syncthreads();
             });
         static_for<UNR - 1>([&](auto c) {
             if (s + decltype(c)::value < nstage) {
                 stage(c, s + decltype(c)::value);
-                __syncthreads();
+                if constexpr ((decltype(c)::value + 1) % W == 0) __syncthreads();
             }
         });
+        if constexpr (W > 1) __syncthreads();  // every wave is done with the ring before mode 2 reuses the LDS
 
         // ---- mode 2 on the finished Z chunk ----
         float *Zs = (float *)smem + wave * (32 * ZST);
