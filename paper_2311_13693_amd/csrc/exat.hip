@@ -32,6 +32,7 @@ struct exat_plan_s {
     int64_t Ipad, Jpad;
     void *Upack = nullptr;
     void *Ufrag = nullptr;  // U in MFMA fragment order (k_pack_u_frag), same size as Upack
+    void *Vfragz = nullptr; // bf16 plans: V in the fragment order of mode2_direct_bf16 (k_pack_v_frag with perm = 1)
     void *Vfrag = nullptr;  // bf16 plans: V in bf16 MFMA fragment order (k_pack_v_frag); fp32 plans: V in the order
                             // mode2_direct consumes (k_pack_v_direct)
     _Float16 *Ufh = nullptr, *Ufl = nullptr, *Vfh = nullptr, *Vfl = nullptr;  // split plans: fp16 pieces in fragment order
@@ -315,7 +316,7 @@ int run_chain(exat_plan_s *pl, Mode12Params mp, bool generated, float *Yout, int
         const bool boxed = generated && (mp.i0 != 0 || mp.i1 != pl->d.I);
         const int ks = gs.Rpad / 32;
         UFragParams uf;
-        uf.Uf = pl->Ufrag; uf.nig = pl->Ipad / (bf ? 16 : 8); uf.Vf = pl->Vfrag;
+        uf.Uf = pl->Ufrag; uf.nig = pl->Ipad / (bf ? 16 : 8); uf.Vf = pl->Vfrag; uf.Vz = pl->Vfragz;
         if (!generated) {
             if (bf) rc = rt == 4 ? launch_v3_mat<__bf16, 8, 2>(mp, gs, uf, nk, st) : launch_v3_mat<__bf16, 4, 2>(mp, gs, uf, nk, st);
             else if (pl->d.L % 32 == 0 && env_int("EXAT_ZT", 1))
@@ -430,7 +431,8 @@ int exat_plan_create(exat_plan_t *plan, const exat_desc_t *desc)
     pl->ub = ub; pl->vb = vb; pl->qb = qb; pl->ab = (size_t)3 * pl->Ipad * 64 * 2;
     if (hipMalloc((void **)&pl->Asplit, pl->ab) != hipSuccess ||
         hipMalloc(&pl->Upack, ub) != hipSuccess || hipMalloc(&pl->Ufrag, ub) != hipSuccess ||
-        (desc->in_dtype == EXAT_BF16 && hipMalloc(&pl->Vfrag, (size_t)desc->P * pl->Jpad * 64 * 2) != hipSuccess) ||
+        (desc->in_dtype == EXAT_BF16 && (hipMalloc(&pl->Vfrag, (size_t)desc->P * pl->Jpad * 64 * 2) != hipSuccess ||
+                                         hipMalloc(&pl->Vfragz, (size_t)desc->P * pl->Jpad * 64 * 2) != hipSuccess)) ||
         (desc->in_dtype != EXAT_BF16 && hipMalloc(&pl->Vfrag, (size_t)desc->P * pl->Mpad * pl->Jpad * 4) != hipSuccess) ||
         (desc->in_dtype == EXAT_F32_SPLIT &&
          (hipMalloc((void **)&pl->Ufh, (size_t)pl->PLpad * pl->Ipad * 2) != hipSuccess || hipMalloc((void **)&pl->Ufl, (size_t)pl->PLpad * pl->Ipad * 2) != hipSuccess ||
@@ -457,7 +459,7 @@ int exat_plan_destroy(exat_plan_t pl)
         if (pl->copy_stream) (void)hipStreamDestroy(pl->copy_stream);
     }
     if (!pl) return EXAT_OK;
-    (void)hipFree(pl->Upack); (void)hipFree(pl->Ufrag); (void)hipFree(pl->Vfrag);
+    (void)hipFree(pl->Upack); (void)hipFree(pl->Ufrag); (void)hipFree(pl->Vfrag); (void)hipFree(pl->Vfragz);
     (void)hipFree(pl->Ufh); (void)hipFree(pl->Ufl); (void)hipFree(pl->Vfh); (void)hipFree(pl->Vfl); (void)hipFree(pl->Vpack); (void)hipFree(pl->Wpack); (void)hipFree(pl->Q);
     (void)hipFree(pl->slots); (void)hipFree(pl->used_dev); (void)hipFree(pl->Asplit);
     for (auto &tr : pl->evr)
@@ -477,7 +479,8 @@ int exat_set_factors(exat_plan_t pl, const float *U, int64_t ldU, const float *V
     if (d.in_dtype == EXAT_BF16) {
         hipLaunchKernelGGL(k_pack_u<__bf16>, dim3(grid_for(nu)), dim3(256), 0, st, U, ldU, pl->PL, d.I, (__bf16 *)pl->Upack, pl->PLpad, pl->Ipad);
         hipLaunchKernelGGL(k_pack_u_frag<__bf16>, dim3(grid_for(nu)), dim3(256), 0, st, U, ldU, pl->PL, d.I, (__bf16 *)pl->Ufrag, pl->PLpad / 32, pl->Ipad / 16);
-        hipLaunchKernelGGL(k_pack_v_frag, dim3(grid_for((int64_t)d.P * pl->Jpad * 64)), dim3(256), 0, st, V, ldV, d.P, d.M, d.J, (__bf16 *)pl->Vfrag, pl->Jpad);
+        hipLaunchKernelGGL(k_pack_v_frag, dim3(grid_for((int64_t)d.P * pl->Jpad * 64)), dim3(256), 0, st, V, ldV, d.P, d.M, d.J, (__bf16 *)pl->Vfrag, pl->Jpad, 0);
+        hipLaunchKernelGGL(k_pack_v_frag, dim3(grid_for((int64_t)d.P * pl->Jpad * 64)), dim3(256), 0, st, V, ldV, d.P, d.M, d.J, (__bf16 *)pl->Vfragz, pl->Jpad, 1);
         hipLaunchKernelGGL(k_pack_v<__bf16>, dim3(grid_for(nv)), dim3(256), 0, st, V, ldV, d.P, d.M, d.J, pl->Vpack, pl->Mpad, pl->Jpad);
         hipLaunchKernelGGL(k_pack_w<__bf16>, dim3(grid_for(nw)), dim3(256), 0, st, W, ldW, d.P, d.N, d.K, pl->Wpack, pl->Npad);
     } else {

@@ -31,6 +31,9 @@ struct UFragParams {
     int64_t nig;     // Ipad / GI
     const void *Vf;  // bf16 plans: [P][Jpad/16][2][64][8 bf16]: lane l of fragment (p, j16, mt) holds
                      // V_p[m = 32*mt + l%32, j = 16*j16 + 8*(l/32) .. +7]
+    const void *Vz;  // bf16 plans: the same fragments with the 16 columns of a fragment in the order in which the
+                     // accumulators of a transposed mode 1 hold them (mode2_direct_bf16): element e of lane l is
+                     // V_p[m = 32*mt + l%32, j = 16*j16 + 4*(l/32) + e%4 + 8*(e/4)]
 };
 
 template <int NW, int RT>
@@ -524,14 +527,15 @@ __global__ void k_pack_u_frag(const float *src, int64_t ld, int rows, int64_t co
 
 // Stacked fp32 V (P*M x J) -> bf16 B fragments of the 32x32x16 MFMA, [P][Jpad/16][2][64 lanes][8], zero padded:
 // lane l of fragment (p, j16, mt) holds V_p[m = 32*mt + l%32, j = 16*j16 + 8*(l/32) .. +7].
-__global__ void k_pack_v_frag(const float *src, int64_t ld, int P, int M, int64_t J, __bf16 *dst, int64_t Jpad)
+// perm: the column order of mode2_direct_bf16 (UFragParams::Vz) instead.
+__global__ void k_pack_v_frag(const float *src, int64_t ld, int P, int M, int64_t J, __bf16 *dst, int64_t Jpad, int perm)
 {
     const int64_t n = (int64_t)P * Jpad * 64;
     for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < n; idx += (int64_t)gridDim.x * blockDim.x) {
         const int e = (int)(idx & 7), l = (int)((idx >> 3) & 63), mt = (int)((idx >> 9) & 1);
         const int64_t f = idx >> 10, j16 = f % (Jpad / 16), pr = f / (Jpad / 16);
         const int m = 32 * mt + (l & 31);
-        const int64_t j = 16 * j16 + 8 * (l >> 5) + e;
+        const int64_t j = perm ? 16 * j16 + 4 * (l >> 5) + (e & 3) + 8 * (e >> 2) : 16 * j16 + 8 * (l >> 5) + e;
         const float v = (m < M && j < J) ? src[(pr * M + m) * ld + j] : 0.0f;
         dst[idx] = (__bf16)v;
     }

@@ -24,10 +24,8 @@ template <int NW, int RT>
 struct Mode12V4Cfg {
     static constexpr int ROWS = 32 * NW * RT, COLS = 128, ROWB = 80;
     static constexpr int XBUF_BYTES = COLS * ROWB;
-    static constexpr int ZST = COLS + 4;
-    static constexpr int EPI_BYTES = NW * 32 * ZST * 4;
     static constexpr int MAX_XBUFS = 8;
-    static constexpr int LDS_BYTES = MAX_XBUFS * XBUF_BYTES > EPI_BYTES ? MAX_XBUFS * XBUF_BYTES : EPI_BYTES;
+    static constexpr int LDS_BYTES = MAX_XBUFS * XBUF_BYTES;   // the ring of X tiles is all the LDS the kernel uses
 };
 
 // KS: 32-wide steps of the factor rank (R <= 32*KS); BOXED: the box is a proper sub-range in i; DU: register sets of
@@ -40,7 +38,7 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void k_mode12_v4(const Mode12Param
 {
     typedef Mode12V4Cfg<NW, RT> cfg;
     typedef __bf16 T;
-    constexpr int CT = 4, ROWS = cfg::ROWS, COLS = cfg::COLS, ROWB = cfg::ROWB, ZST = cfg::ZST, XBUF = cfg::XBUF_BYTES;
+    constexpr int CT = 4, ROWS = cfg::ROWS, COLS = cfg::COLS, ROWB = cfg::ROWB, XBUF = cfg::XBUF_BYTES;
     constexpr int EI = 32, GI = 16, E16 = 8;
     constexpr int SJW = 16 / NW;            // 16-column blocks of the generated tile per wave (all in one 16-row half)
     constexpr int NQ = SJW;                 // quads of 4 consecutive i per lane and stage
@@ -92,12 +90,14 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void k_mode12_v4(const Mode12Param
         const int xs_r = l32 * ROWB + hi * 16;                                          // + ct*32*ROWB + g2*32
         const int xg_w = (16 * sj0 + l16) * ROWB + (16 * si + 4 * q16) * (int)sizeof(T); // + b*16*ROWB
         f32x16 acc[RT][CT];
+        float zero = 0.0f;
+        asm volatile("" : "+v"(zero));   // a zero the compiler cannot keep as a 16-register vector across the chunks
 #pragma unroll
         for (int rt = 0; rt < RT; rt++)
 #pragma unroll
             for (int ct = 0; ct < CT; ct++)
 #pragma unroll
-                for (int e = 0; e < 16; e++) acc[rt][ct][e] = 0.0f;
+                for (int e = 0; e < 16; e++) acc[rt][ct][e] = zero;
 
         // ---- per-chunk set-up: the generator's B operand bc[j, r] = B[j,r] C[k,r] of this lane's columns ----
 #pragma unroll
@@ -246,7 +246,7 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void k_mode12_v4(const Mode12Param
 #pragma unroll
                     for (int rt = 0; rt < RT; rt++) {
 #pragma unroll
-                        for (int ct = 0; ct < CT; ct++) acc[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ufr[US][rt][g2], bx[g2][ct], acc[rt][ct], 0, 0, 0);
+                        for (int ct = 0; ct < CT; ct++) acc[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bx[g2][ct], ufr[US][rt][g2], acc[rt][ct], 0, 0, 0);
                         ufr[US][rt][g2] = load_uf(rt, ig2 + g2);   // refill for stage s+DU
                     }
             } else {
@@ -268,7 +268,7 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void k_mode12_v4(const Mode12Param
                 static_for<NMAIN>([&](auto mc) {
                     constexpr int m = decltype(mc)::value, f = m / RT, rt = m % RT, g2 = f / CT, ct = f % CT;
                     if constexpr (rt == 0 && f + BXA < 2 * CT) bx[(f + BXA) % (BXA + 1)] = load_bx(f + BXA);
-                    acc[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ufr[US][rt][g2], bx[f % (BXA + 1)], acc[rt][ct], 0, 0, 0);
+                    acc[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bx[f % (BXA + 1)], ufr[US][rt][g2], acc[rt][ct], 0, 0, 0);
                     if constexpr (ct == CT - 1) ufr[US][rt][g2] = load_uf(rt, ig2 + g2);   // last use this stage: refill for stage s+DU
                     __builtin_amdgcn_sched_barrier(0);
                     constexpr int g0 = gens_before(m), g1 = gens_before(m + 1), wb = 2 * m + g0;
@@ -307,7 +307,7 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void k_mode12_v4(const Mode12Param
 #pragma unroll
                     for (int g2 = 0; g2 < 2; g2++) ufr[d][rt][g2] = load_uf(rt, igd + g2);
             }
-            __syncthreads();  // the previous chunk's epilogue is done with the LDS
+            __syncthreads();  // every wave is done with the ring slots of the previous chunk's last stages
 #pragma unroll
             for (int t = 0; t < W; t++) {
                 f32x4v l0[NQ];
@@ -332,13 +332,12 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void k_mode12_v4(const Mode12Param
                 if constexpr ((decltype(c)::value + 1) % W == 0) __syncthreads();
             }
         });
-        if constexpr (W > 1) __syncthreads();  // every wave is done with the ring before mode 2 reuses the LDS
 
-        // ---- mode 2 on the finished Z chunk ----
-        float *Zs = (float *)smem + wave * (32 * ZST);
+        // ---- mode 2 on the finished chunk, straight from the accumulators (they hold Z^T: the MFMAs above take the X
+        //      fragment as first and the U fragment as second operand) ----
         const bool first_chunk = (jc == ja0);
-        if (p.MT == 2) mode2_chunk<RT, CT, 2, VM_BF16>(p, uf.Vf, Zs, acc, wrow0, kidx, jc, first_chunk, tid & 63);
-        else mode2_chunk<RT, CT, 1, VM_BF16>(p, uf.Vf, Zs, acc, wrow0, kidx, jc, first_chunk, tid & 63);
+        if (p.MT == 2) mode2_direct_bf16<RT, CT, 2>(p, uf.Vz, acc, wrow0, kidx, jc, first_chunk, tid & 63);
+        else mode2_direct_bf16<RT, CT, 1>(p, uf.Vz, acc, wrow0, kidx, jc, first_chunk, tid & 63);
     }
 }
 

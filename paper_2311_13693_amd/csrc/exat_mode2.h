@@ -241,4 +241,85 @@ __device__ __forceinline__ void mode2_direct(const Mode12Params &p, const float 
     }
 }
 
+// Mode 2 straight from the accumulators on the bf16 matrix cores, for kernels that ran mode 1 with the MFMA operands
+// swapped (a tile's accumulator holds Z^T: rows 32 fibres j, columns 32 stacked rows q).  Registers 8t .. 8t+7 of lane l
+// are Z^T[j = 16t + 4(l/32) + e%4 + 8(e/4)][q = l%32], e = 0..7: converted to bf16 they are the second operand of a
+// 32x32x16 MFMA whose 16 contraction slots stand for the 16 fibres 16t .. 16t+15 in that order, and V comes packed in
+// the same order (UFragParams::Vz), so Q^T[m, q] += sum_j V_p[m, j] Z^T[j, q] needs no trip through LDS and no wave
+// barrier.  Z goes in as two bf16 pieces (error 2^-17), as in mode2_chunk<VM_BF16>.  A tile of 32 rows q may touch two
+// replicas: both products are formed and each lane keeps the one of its row's replica.  Q keeps its layout [k][q][m]: a
+// lane owns one row q and reads and writes 16-byte pieces of it.
+template <int RT, int CT, int MTC, int RSTRIDE = 32>
+__device__ __forceinline__ void mode2_direct_bf16(const Mode12Params &p, const void *Vz, const f32x16 (&acc)[RT][CT], int wrow0, int kidx,
+                                                  int64_t jc, bool first_chunk, int lane)
+{
+    constexpr int MP = 32 * MTC;   // = p.Mpad
+#pragma unroll
+    for (int rt = 0; rt < RT; rt++) {
+        const int q0 = wrow0 + rt * RSTRIDE;   // wave-uniform
+        if (q0 < p.PL) {
+            int ln = lane;
+            asm volatile("" : "+v"(ln));       // per-lane addresses are derived here, after the stage loop (see mode2_chunk)
+            const int l32 = ln & 31, hi = ln >> 5;
+            const int q = q0 + l32;
+            const int qlast = (q0 + 31 < p.PL - 1) ? q0 + 31 : p.PL - 1;
+            const int pfirst = q0 / p.L, plast = qlast / p.L;
+            const float *Qt = p.Q + ((int64_t)kidx * p.PLpad + q) * MP + 4 * hi;   // + 32*mt + 8*b
+            f32x4 qsum[MTC][4];
+#pragma unroll
+            for (int mt = 0; mt < MTC; mt++)
+#pragma unroll
+                for (int b = 0; b < 4; b++) qsum[mt][b] = first_chunk ? f32x4{0.0f, 0.0f, 0.0f, 0.0f} : *(const f32x4 *)(Qt + 32 * mt + 8 * b);
+            for (int pp = pfirst; pp <= plast; pp++) {
+                const bool mine = q >= pp * p.L && q < (pp + 1) * p.L;
+                // fragment (ct, t, mt) of this chunk: j16 = jc/16 + 2 ct + t
+                const bf16x8 *vz = (const bf16x8 *)Vz + (((int64_t)pp * (p.Jpad / 16) + jc / 16) * 2) * 64 + ln;
+                f32x16 qa[MTC];   // started by the first MFMA (its addend is the constant zero)
+                const f32x16 zero16 = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
+                // step st = 2 ct + t takes the fragments (st, mt); they are requested two steps ahead (a ring of three sets)
+                bf16x8 bv[3][MTC];
+#pragma unroll
+                for (int st = 0; st < 2; st++)
+#pragma unroll
+                    for (int mt = 0; mt < MTC; mt++) bv[st][mt] = vz[(st * 2 + mt) * 64];
+#pragma unroll
+                for (int st = 0; st < 2 * CT; st++) {
+                    const int ct = st >> 1, t = st & 1;
+                    if (st + 2 < 2 * CT) {
+#pragma unroll
+                        for (int mt = 0; mt < MTC; mt++) bv[(st + 2) % 3][mt] = vz[((st + 2) * 2 + mt) * 64];
+                    }
+                    __builtin_amdgcn_sched_barrier(0);   // the requests stay ahead of the MFMAs
+                    bf16x8 zh, zl;
+#pragma unroll
+                    for (int e = 0; e < 8; e++) {
+                        const float z = acc[rt][ct][8 * t + e];
+                        zh[e] = (__bf16)z;
+                        zl[e] = (__bf16)(z - (float)zh[e]);
+                    }
+#pragma unroll
+                    for (int mt = 0; mt < MTC; mt++) {
+                        qa[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bv[st % 3][mt], zl, st == 0 ? zero16 : qa[mt], 0, 0, 0);
+                        qa[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bv[st % 3][mt], zh, qa[mt], 0, 0, 0);
+                    }
+                }
+#pragma unroll
+                for (int mt = 0; mt < MTC; mt++)
+#pragma unroll
+                    for (int b = 0; b < 4; b++)
+#pragma unroll
+                        for (int r = 0; r < 4; r++) qsum[mt][b][r] += mine ? qa[mt][4 * b + r] : 0.0f;
+            }
+            // (the row's address is derived a second time rather than kept across the loop above, where registers are short)
+            int ls = lane;
+            asm volatile("" : "+v"(ls));
+            float *Qs = p.Q + ((int64_t)kidx * p.PLpad + q0 + (ls & 31)) * MP + 4 * (ls >> 5);
+#pragma unroll
+            for (int mt = 0; mt < MTC; mt++)
+#pragma unroll
+                for (int b = 0; b < 4; b++) *(f32x4 *)(Qs + 32 * mt + 8 * b) = qsum[mt][b];
+        }
+    }
+}
+
 }  // namespace exat
