@@ -12,12 +12,21 @@
 //   k_stage1_sum_ranges  adds the partial results of the column ranges (only when a slice was split).
 //   k_stage1_mode3   X1[a,b,c] = sum_k W[c,k] Q[k][b][a], a thread per (a,b,c), the non-zeros of row c in
 //                    stored order.
+//   k_stage1_mfma    the same two modes when every value of U is exactly representable in bf16 (sign matrices are): U is
+//                    taken as a DENSE A1 x I bf16 matrix and mode 1 runs on the matrix cores, which are otherwise idle in
+//                    this read-bound stage, with X read straight from HBM into MFMA operand registers (a lane owns a column
+//                    and walks down it 8 values at a time: no LDS tile, no gather, no barrier in the loop) several steps
+//                    ahead, and split on the fly into three truncated bf16 pieces (8 + 8 + 8 significand bits: the split is
+//                    exact, so the products are too).  16 times the arithmetic of the sparse form, on a unit with nothing
+//                    else to do; what it buys is that the bytes in flight per compute unit are set by a register ring, not
+//                    by how many LDS tiles fit.  Mode 2 is the sparse one above, on the finished tile in LDS.
 // Every sum has a fixed order, so results are bit-identical from run to run.
 #include "../../include/exat.h"
 
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <type_traits>
 #include <cstdint>
 #include <cstdlib>
 #include <cstring>
@@ -217,6 +226,266 @@ __global__ __launch_bounds__(S1_NT, 6) void k_stage1_mode12(const S1Params p)
     }
 }
 
+
+// ---- mode 1 on the matrix cores (U dense in bf16), mode 2 as above -------------------------------------------------
+constexpr int SM_NW = 4;            // waves per workgroup
+constexpr int SM_CT = 2;            // 32-column tiles per wave
+constexpr int SM_TJ = 32 * SM_CT * SM_NW;   // columns per workgroup tile (256)
+constexpr int SM_GI = 32;           // rows i per step (two MFMA contraction lengths)
+
+typedef __bf16 s1_bf16x8 __attribute__((ext_vector_type(8)));
+typedef float s1_f32x16 __attribute__((ext_vector_type(16)));
+typedef float s1_f32x4 __attribute__((ext_vector_type(4)));
+typedef s1_f32x4 s1_f32x4_u __attribute__((aligned(4)));   // a column of X starts at a multiple of 4 bytes, not of 16
+typedef unsigned int s1_u32x4 __attribute__((ext_vector_type(4)));
+
+struct S1MParams {
+    const float *X;
+    int64_t I, J;
+    int A1, B1;
+    const __bf16 *Ud;  // [RT][nks + 1][64 lanes][8]: lane l of fragment (rt, ks) holds U[32 rt + l%32][16 ks + 8 (l/32) .. +7], zero
+                       // padded; fragment nks is all zeros (the padding steps of a tile multiply with it)
+    const __bf16 *Vd;  // [MT][16 ntile][64 lanes][8]: element e of lane l of fragment (mt, j16) holds
+                       // V[32 mt + l%32][16 j16 + 4 (l/32) + e%4 + 8 (e/4)] (the order in which a transposed accumulator holds
+                       // its 16 columns), zero padded
+    float *Q;          // [K][B1][A1]
+    int64_t k0;
+};
+
+template <int N, typename F> __device__ __forceinline__ void s1_static_for_(F &&f, std::integral_constant<int, N>, std::integral_constant<int, N>) {}
+template <int N, int I_, typename F> __device__ __forceinline__ void s1_static_for_(F &&f, std::integral_constant<int, I_>, std::integral_constant<int, N> n)
+{
+    f(std::integral_constant<int, I_>());
+    s1_static_for_(f, std::integral_constant<int, I_ + 1>(), n);
+}
+template <int N, typename F> __device__ __forceinline__ void s1_static_for(F &&f) { s1_static_for_(f, std::integral_constant<int, 0>(), std::integral_constant<int, N>()); }
+
+// RT, MT = 32-row tiles of a and of b (A1 <= 32 RT, B1 <= 32 MT), D = steps of X a wave keeps in flight, RAGGED: I is no
+// multiple of 32 (what a request reads past the end of a column is set to zero).
+//
+// Mode 1.  A wave owns 64 columns of the workgroup's 256-column tile and walks down them in steps of 32 rows.  A step's
+// 8 KiB are requested with eight 16-byte-per-lane loads that run ALONG the columns (eight lanes cover the 128 bytes of one
+// column, a load covers eight columns: every request is a whole cache line), D steps ahead, together with the U fragments
+// of the same step -- a wave's loads come back in issue order, so a request with a shorter lead would wait behind the long
+// ones and cut their lead to its own.  When a step arrives the wave writes it into its private LDS slot (column-major, the
+// 16-byte pieces of a column XOR-swizzled with the column number so that neither the writes along the columns nor the
+// fragment reads across them collide on a bank), reads it back as MFMA operands (lane l: column l%32 of a 32-column tile,
+// eight consecutive rows), splits each value into three truncated bf16 pieces (8 + 8 + 8 significand bits: the split is
+// exact, so are the products with the bf16 U) and issues three MFMAs per row tile, X as first operand: the accumulators
+// hold Z^T (rows: columns j, columns: rows a).  Nothing in the step loop waits for another wave: no barrier, no branch
+// (steps past the end of a tile are made harmless instead: they multiply a valid step of the same columns with the
+// all-zero U fragment).
+// Mode 2, at the end of a tile, is on the matrix cores as well: the waves put their Z^T tiles into LDS in operand order
+// (registers 8t .. 8t+7 of a transposed accumulator are the 16 columns 16t .. 16t+15 in the order Vd is packed in), and the
+// RT x MT blocks of the slice's B1 x A1 result are dealt out to the four waves (block b = mt RT + rt to wave b mod 4), each
+// of which adds, over the tile's 16 column blocks, V fragment x split Z^T fragment to the blocks it owns, in registers,
+// for the whole slice.  No two waves add to the same number, so every sum has a fixed order.
+template <int RT, int MT, int D, bool RAGGED>
+__global__ __launch_bounds__(64 * SM_NW, 1) void k_stage1_mfma(const S1MParams p)
+{
+    extern __shared__ float smem[];
+    constexpr int DL = 2;                           // LDS slots per wave
+    constexpr int UN = D % DL == 0 ? D : D * DL;    // steps per unrolled group: ring slots are compile-time constants
+    constexpr int SLOT = 64 * SM_GI;                // floats per slot: 64 columns x 32 rows
+    constexpr int NBW = (RT * MT + SM_NW - 1) / SM_NW;   // result blocks per wave
+    constexpr bool ONE_RT = SM_NW % RT == 0;        // all blocks of a wave lie in one row tile rt: its Z fragments are split once
+    const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, hi = lane >> 5;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    float *xs = smem + w * (DL * SLOT);
+    float *zt = smem;                               // Z^T fragments of a finished tile: [16 jb][RT][2 halves][64 lanes][4]
+    const int64_t k = blockIdx.x;
+    const float *Xk = p.X + k * p.I * p.J;
+    const int nks = (int)((p.I + 15) / 16);         // U fragments per row tile (plus the zero fragment)
+    const int ng = (int)((p.I + SM_GI - 1) / SM_GI);
+    const int ntile = (int)((p.J + SM_TJ - 1) / SM_TJ);
+    const int ngp = (ng + UN - 1) / UN * UN;        // steps per tile, padded to whole groups
+
+    s1_f32x16 acc[RT][SM_CT];
+#pragma unroll
+    for (int rt = 0; rt < RT; rt++)
+#pragma unroll
+        for (int ct = 0; ct < SM_CT; ct++)
+#pragma unroll
+            for (int e = 0; e < 16; e++) acc[rt][ct][e] = 0.0f;
+    s1_f32x16 qacc[NBW];                            // block w + 4 i of the slice's result, transposed: rows b, columns a
+#pragma unroll
+    for (int i = 0; i < NBW; i++)
+#pragma unroll
+        for (int e = 0; e < 16; e++) qacc[i][e] = 0.0f;
+
+    // the slice as a buffer: a request past its end (columns past J) returns zeros
+    const __amdgpu_buffer_rsrc_t xrs = __builtin_amdgcn_make_buffer_rsrc((void *)Xk, 0, (int)(p.I * p.J * 4), 0x00020000);
+    const int x_lane = (int)(((lane >> 3) * p.I + 4 * (lane & 7)) * 4);        // column lane/8 of a load's eight, piece lane%8
+    const int f_lane = lane * 16;
+    const __amdgpu_buffer_rsrc_t urs = __builtin_amdgcn_make_buffer_rsrc((void *)p.Ud, 0, (int)((int64_t)RT * (nks + 1) * 1024), 0x00020000);
+    const __amdgpu_buffer_rsrc_t vrs = __builtin_amdgcn_make_buffer_rsrc((void *)p.Vd, 0, (int)((int64_t)MT * 16 * ntile * 1024), 0x00020000);
+    // LDS offset (floats) of piece q (4 rows) of column c in a slot
+    auto swz = [](int c, int q) { return c * SM_GI + 4 * (q ^ ((c >> 1) & 7)); };
+
+    s1_f32x4 xr[D][8];             // ring of steps of X as requested: xr[d][m] = this lane's piece of load m
+    s1_bf16x8 ur[D][2][RT];        // the U fragments of the same steps: [half-step][row tile]
+
+    // requests of padded step n = tile * ngp + g: X of the step itself if it exists, else of the last step of the tile
+    // (or of the last tile), which is then multiplied with the zero fragment
+    auto request_x = [&](int n, s1_f32x4 (&dst)[8]) {
+        int tile = n / ngp, g = n - tile * ngp;
+        tile = tile < ntile ? tile : ntile - 1;
+        g = g < ng ? g : ng - 1;
+        const int soff = (int)((((int64_t)tile * SM_TJ + 64 * w) * p.I + (int64_t)SM_GI * g) * 4);
+#pragma unroll
+        for (int m = 0; m < 8; m++) {
+            s1_f32x4 v = __builtin_bit_cast(s1_f32x4, __builtin_amdgcn_raw_buffer_load_b128(xrs, x_lane, soff + (int)(8 * m * p.I * 4), 0));
+            if (RAGGED) {
+                const bool in = (int64_t)SM_GI * g + 4 * (lane & 7) < p.I;   // I is a multiple of 4: a piece is inside or outside
+#pragma unroll
+                for (int e = 0; e < 4; e++) v[e] = in ? v[e] : 0.0f;
+            }
+            dst[m] = v;
+        }
+    };
+    auto request_u = [&](int n, s1_bf16x8 (&dst)[2][RT]) {
+        const int tile = n / ngp, g = n - tile * ngp;
+#pragma unroll
+        for (int h = 0; h < 2; h++) {
+            int ks = 2 * g + h;
+            ks = (g < ng && ks < nks) ? ks : nks;      // the zero fragment for what lies past the end
+#pragma unroll
+            for (int rt = 0; rt < RT; rt++)
+                dst[h][rt] = __builtin_bit_cast(s1_bf16x8, __builtin_amdgcn_raw_buffer_load_b128(urs, f_lane, (rt * (nks + 1) + ks) * 1024, 0));
+        }
+    };
+    // x = h + m + l with h, m, l the three 8-bit slices of the significand, each a bf16 value (truncation: the residuals
+    // are exact); two values per register
+    auto split3 = [&](const s1_f32x4 (&x)[2], s1_bf16x8 &h, s1_bf16x8 &m, s1_bf16x8 &l) {
+        s1_u32x4 ph, pm, pl;
+#pragma unroll
+        for (int q = 0; q < 4; q++) {
+            const float x0 = x[q >> 1][2 * (q & 1)], x1 = x[q >> 1][2 * (q & 1) + 1];
+            const unsigned b0 = __builtin_bit_cast(unsigned, x0), b1 = __builtin_bit_cast(unsigned, x1);
+            const float r0 = x0 - __builtin_bit_cast(float, b0 & 0xffff0000u), r1 = x1 - __builtin_bit_cast(float, b1 & 0xffff0000u);
+            const unsigned c0 = __builtin_bit_cast(unsigned, r0), c1 = __builtin_bit_cast(unsigned, r1);
+            const float s0 = r0 - __builtin_bit_cast(float, c0 & 0xffff0000u), s1 = r1 - __builtin_bit_cast(float, c1 & 0xffff0000u);
+            ph[q] = __builtin_amdgcn_perm(b1, b0, 0x07060302u);
+            pm[q] = __builtin_amdgcn_perm(c1, c0, 0x07060302u);
+            pl[q] = __builtin_amdgcn_perm(__builtin_bit_cast(unsigned, s1), __builtin_bit_cast(unsigned, s0), 0x07060302u);
+        }
+        h = __builtin_bit_cast(s1_bf16x8, ph); m = __builtin_bit_cast(s1_bf16x8, pm); l = __builtin_bit_cast(s1_bf16x8, pl);
+    };
+    // mode 2 on the finished tile
+    auto finish_tile = [&](int tile) {
+        __syncthreads();   // every wave is done with its slots: the Z^T fragments take the LDS over
+#pragma unroll
+        for (int rt = 0; rt < RT; rt++)
+#pragma unroll
+            for (int ct = 0; ct < SM_CT; ct++)
+#pragma unroll
+                for (int t = 0; t < 2; t++) {
+                    const int jb = 4 * w + 2 * ct + t;      // 16-column block of the tile
+                    float *dst = zt + ((jb * RT + rt) * 2) * 256 + lane * 4;
+                    s1_f32x4 lo, up;
+#pragma unroll
+                    for (int e = 0; e < 4; e++) { lo[e] = acc[rt][ct][8 * t + e]; up[e] = acc[rt][ct][8 * t + 4 + e]; }
+                    *(s1_f32x4 *)dst = lo;
+                    *(s1_f32x4 *)(dst + 256) = up;
+                }
+#pragma unroll
+        for (int rt = 0; rt < RT; rt++)
+#pragma unroll
+            for (int ct = 0; ct < SM_CT; ct++)
+#pragma unroll
+                for (int e = 0; e < 16; e++) acc[rt][ct][e] = 0.0f;
+        __syncthreads();
+        // V fragments of column block jb for the wave's blocks, requested one block ahead
+        s1_bf16x8 vr[2][NBW];
+        auto request_v = [&](int jb, s1_bf16x8 (&dst)[NBW]) {
+#pragma unroll
+            for (int i = 0; i < NBW; i++) {
+                const int blk = w + SM_NW * i, mt = blk / RT;    // past the last block: a request past the buffer, zeros
+                dst[i] = __builtin_bit_cast(s1_bf16x8, __builtin_amdgcn_raw_buffer_load_b128(vrs, f_lane, (mt * 16 * ntile + 16 * tile + jb) * 1024, 0));
+            }
+        };
+        request_v(0, vr[0]);
+#pragma unroll
+        for (int jb = 0; jb < 16; jb++) {
+            if (jb + 1 < 16) request_v(jb + 1, vr[(jb + 1) & 1]);
+            s1_bf16x8 zh, zm, zl;
+            if constexpr (ONE_RT) {
+                const int rt = w % RT;
+                const float *src = zt + ((jb * RT + rt) * 2) * 256 + lane * 4;
+                s1_f32x4 x[2];
+                x[0] = *(const s1_f32x4 *)src; x[1] = *(const s1_f32x4 *)(src + 256);
+                split3(x, zh, zm, zl);
+            }
+#pragma unroll
+            for (int i = 0; i < NBW; i++) {
+                if constexpr (!ONE_RT) {
+                    const int rt = (w + SM_NW * i) % RT;
+                    const float *src = zt + ((jb * RT + rt) * 2) * 256 + lane * 4;
+                    s1_f32x4 x[2];
+                    x[0] = *(const s1_f32x4 *)src; x[1] = *(const s1_f32x4 *)(src + 256);
+                    split3(x, zh, zm, zl);
+                }
+                qacc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vr[jb & 1][i], zl, qacc[i], 0, 0, 0);
+                qacc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vr[jb & 1][i], zm, qacc[i], 0, 0, 0);
+                qacc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vr[jb & 1][i], zh, qacc[i], 0, 0, 0);
+            }
+        }
+        __syncthreads();   // the slots take the LDS back
+    };
+
+    s1_static_for<D>([&](auto dc) {
+        constexpr int d = decltype(dc)::value;
+        request_x(d, xr[d]);
+        request_u(d, ur[d]);
+    });
+    for (int tile = 0; tile < ntile; tile++) {
+        for (int g0 = 0; g0 < ngp; g0 += UN) {
+            s1_static_for<UN>([&](auto dc) {
+                constexpr int dd = decltype(dc)::value, d = dd % D, sl = dd % DL;
+                const int n = tile * ngp + g0 + dd;
+                float *slot = xs + sl * SLOT;
+                // the step that has arrived goes to the wave's LDS slot, and its registers out again for step n + D
+#pragma unroll
+                for (int m = 0; m < 8; m++) *(s1_f32x4 *)(slot + swz(8 * m + (lane >> 3), lane & 7)) = xr[d][m];
+                request_x(n + D, xr[d]);
+#pragma unroll
+                for (int h = 0; h < 2; h++)
+#pragma unroll
+                    for (int ct = 0; ct < SM_CT; ct++) {
+                        const int j = 32 * ct + l32;
+                        s1_f32x4 x[2];
+                        x[0] = *(const s1_f32x4 *)(slot + swz(j, 4 * h + 2 * hi));
+                        x[1] = *(const s1_f32x4 *)(slot + swz(j, 4 * h + 2 * hi + 1));
+                        s1_bf16x8 xh, xm, xl;
+                        split3(x, xh, xm, xl);
+#pragma unroll
+                        for (int rt = 0; rt < RT; rt++) {
+                            acc[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xl, ur[d][h][rt], acc[rt][ct], 0, 0, 0);
+                            acc[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xm, ur[d][h][rt], acc[rt][ct], 0, 0, 0);
+                            acc[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh, ur[d][h][rt], acc[rt][ct], 0, 0, 0);
+                        }
+                    }
+                request_u(n + D, ur[d]);
+            });
+        }
+        finish_tile(tile);
+    }
+    // block (mt, rt) of the wave: register 4 b4 + r of lane l is Q[b = 32 mt + 8 b4 + 4 (l/32) + r][a = 32 rt + l%32]
+    float *Qk = p.Q + (p.k0 + k) * p.B1 * p.A1;
+#pragma unroll
+    for (int i = 0; i < NBW; i++) {
+        const int blk = w + SM_NW * i, mt = blk / RT, rt = blk % RT;
+        const int a = 32 * rt + l32;
+        if (blk < RT * MT && a < p.A1) {
+#pragma unroll
+            for (int e = 0; e < 16; e++) {
+                const int b = 32 * mt + 8 * (e >> 2) + 4 * hi + (e & 3);
+                if (b < p.B1) Qk[(int64_t)b * p.A1 + a] = qacc[i][e];
+            }
+        }
+    }
+}
+
 // Q[0][..] += Q[1][..] + ... + Q[JS-1][..] (the column ranges in order), four floats per thread; n4 = K*A1*B1/4
 // rounded up, the allocation is padded accordingly.
 __global__ __launch_bounds__(256) void k_stage1_sum_ranges(float *Q, int JS, int64_t stride, int64_t n4)
@@ -375,6 +644,79 @@ int launch12(const S1Params &p, dim3 grid, size_t lds, hipStream_t st)
     return hipGetLastError() == hipSuccess ? EXAT_OK : EXAT_ERR_HIP;
 }
 
+template <int RT, int MT, int D, bool RAGGED>
+int launch_mfma_inst(const S1MParams &p, unsigned nk, hipStream_t st)
+{
+    const size_t zt = (size_t)16 * RT * 2 * 256 * sizeof(float), slots = (size_t)SM_NW * 2 * 64 * SM_GI * sizeof(float);
+    const size_t lds = zt > slots ? zt : slots;
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_stage1_mfma<RT, MT, D, RAGGED>),
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (attr != hipSuccess) return EXAT_ERR_HIP;
+    hipLaunchKernelGGL((k_stage1_mfma<RT, MT, D, RAGGED>), dim3(nk), dim3(64 * SM_NW), lds, st, p);
+    return hipGetLastError() == hipSuccess ? EXAT_OK : EXAT_ERR_HIP;
+}
+template <int RT, int MT, int D>
+int launch_mfma(const S1MParams &p, unsigned nk, hipStream_t st)
+{
+    return (p.I % SM_GI) ? launch_mfma_inst<RT, MT, D, true>(p, nk, st) : launch_mfma_inst<RT, MT, D, false>(p, nk, st);
+}
+template <int RT, int D>
+int launch_mfma_rt(const S1MParams &p, unsigned nk, hipStream_t st)
+{
+    switch ((p.B1 + 31) / 32) {
+    case 1: return launch_mfma<RT, 1, D>(p, nk, st);
+    case 2: return launch_mfma<RT, 2, D>(p, nk, st);
+    case 3: return launch_mfma<RT, 3, D>(p, nk, st);
+    default: return launch_mfma<RT, 4, D>(p, nk, st);
+    }
+}
+
+// Dense bf16 copy of U in MFMA fragment order, if every value (duplicates summed) is a bf16 value; false otherwise
+bool dense_bf16_frags(const exat_csr_t &m, int64_t I, std::vector<uint16_t> &frag)
+{
+    const int RT = (m.rows + 31) / 32;
+    const int64_t nks = (I + 15) / 16;
+    std::vector<float> acc((size_t)RT * (nks + 1) * 64 * 8, 0.0f);   // one more fragment per row tile, all zeros
+    for (int r = 0; r < m.rows; r++)
+        for (int64_t e = m.rowptr[r]; e < m.rowptr[r + 1]; e++) {
+            const int64_t i = m.colidx[e];
+            const int64_t ks = i / 16;
+            const int lane = (r % 32) + 32 * (int)((i % 16) / 8);
+            acc[(((size_t)(r / 32) * (nks + 1) + ks) * 64 + lane) * 8 + (size_t)(i % 8)] += m.val[e];
+        }
+    frag.resize(acc.size());
+    for (size_t t = 0; t < acc.size(); t++) {
+        uint32_t b;
+        memcpy(&b, &acc[t], 4);
+        if (b & 0xffffu) return false;
+        frag[t] = (uint16_t)(b >> 16);
+    }
+    return true;
+}
+
+// Dense bf16 copy of V in the fragment order of k_stage1_mfma's mode 2 (S1MParams::Vd), if every value is a bf16 value
+bool dense_bf16_frags_v(const exat_csr_t &m, int64_t J, std::vector<uint16_t> &frag)
+{
+    const int MT = (m.rows + 31) / 32;
+    const int64_t nj16 = 16 * ((J + SM_TJ - 1) / SM_TJ);
+    std::vector<float> acc((size_t)MT * nj16 * 64 * 8, 0.0f);
+    for (int r = 0; r < m.rows; r++)
+        for (int64_t e = m.rowptr[r]; e < m.rowptr[r + 1]; e++) {
+            const int64_t j = m.colidx[e];
+            const int c = (int)(j % 16);                            // column inside its block of 16: c = 4 half + e%4 + 8 (e/4)
+            const int half = (c >> 2) & 1, el = (c & 3) + 4 * (c >> 3);
+            acc[(((size_t)(r / 32) * nj16 + j / 16) * 64 + (r % 32) + 32 * half) * 8 + el] += m.val[e];
+        }
+    frag.resize(acc.size());
+    for (size_t t = 0; t < acc.size(); t++) {
+        uint32_t b;
+        memcpy(&b, &acc[t], 4);
+        if (b & 0xffffu) return false;
+        frag[t] = (uint16_t)(b >> 16);
+    }
+    return true;
+}
+
 }  // namespace
 
 struct exat_stage1_s {
@@ -384,6 +726,8 @@ struct exat_stage1_s {
     int *Uch = nullptr, *Vtp = nullptr, *Wrp = nullptr, *Wci = nullptr;
     SEnt *Vent = nullptr;
     float *Wval = nullptr, *Q = nullptr;
+    uint16_t *Ud = nullptr;   // dense bf16 U and V in fragment order when the first two modes run on the matrix cores
+    uint16_t *Vd = nullptr;   // (k_stage1_mfma), else null
     int JS = 1, jt_per = 1;   // column ranges per slice (more workgroups when K alone would not fill the chip)
     bool timing = false, timing_valid = false;
     hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
@@ -406,7 +750,7 @@ extern "C" {
 int exat_stage1_destroy(exat_stage1_t s)
 {
     if (!s) return EXAT_OK;
-    void *bufs[] = {s->Uoc, s->Uch, s->Vtp, s->Wrp, s->Wci, s->Vent, s->Wval, s->Q};
+    void *bufs[] = {s->Uoc, s->Uch, s->Vtp, s->Wrp, s->Wci, s->Vent, s->Wval, s->Q, s->Ud, s->Vd};
     for (void *b : bufs)
         if (b) (void)hipFree(b);
     for (auto &e : s->ev)
@@ -442,6 +786,14 @@ int exat_stage1_create(exat_stage1_t *out, int64_t I, int64_t J, int64_t K, cons
         std::vector<int> ch;
         if (!chunk_csr(*U, oc, ch)) { exat_stage1_destroy(s); return EXAT_ERR_SHAPE; }
         if ((rc = upload(oc, &s->Uoc)) == EXAT_OK) rc = upload(ch, &s->Uch);
+        // modes 1 and 2 on the matrix cores when U and V are bf16 matrices (EXAT_STAGE1_MFMA=0 keeps the sparse form: a
+        // testing aid).  The kernel reads columns 16 bytes at a time and addresses a slice with 32-bit byte offsets.
+        const char *env = getenv("EXAT_STAGE1_MFMA");
+        std::vector<uint16_t> fragu, fragv;
+        if (rc == EXAT_OK && !(env && atoi(env) == 0) && I % 4 == 0 && I * J * 4 < 2147483647LL && dense_bf16_frags(*U, I, fragu) &&
+            dense_bf16_frags_v(*V, J, fragv)) {
+            if ((rc = upload(fragu, &s->Ud)) == EXAT_OK) rc = upload(fragv, &s->Vd);
+        }
         if (rc == EXAT_OK) {
             if (!tile_csr(*V, S1_JT, tp, ent)) { exat_stage1_destroy(s); return EXAT_ERR_SHAPE; }
             if ((rc = upload(tp, &s->Vtp)) == EXAT_OK) rc = upload(ent, &s->Vent);
@@ -470,6 +822,7 @@ int exat_stage1_create(exat_stage1_t *out, int64_t I, int64_t J, int64_t K, cons
         }
         s->jt_per = (int)((njt + best - 1) / best);
         s->JS = (int)((njt + s->jt_per - 1) / s->jt_per);
+        if (s->Ud) { s->JS = 1; s->jt_per = (int)njt; }   // k_stage1_mfma: one workgroup per slice, all its columns
     }
     if (rc == EXAT_OK && hipMalloc((void **)&s->Q, (size_t)s->JS * qstride_of(s) * sizeof(float)) != hipSuccess) {
         s->Q = nullptr;
@@ -492,6 +845,18 @@ namespace {
 // modes 1 and 2 over the nk frontal slices starting at X (slices k0 .. k0+nk-1 of the tensor)
 int run_mode12(exat_stage1_s *s, const float *X, int64_t k0, int64_t nk, hipStream_t st)
 {
+    if (s->Ud) {
+        S1MParams m;
+        m.X = X; m.I = s->I; m.J = s->J; m.A1 = s->A1; m.B1 = s->B1; m.Ud = (const __bf16 *)s->Ud; m.Vd = (const __bf16 *)s->Vd;
+        m.Q = s->Q; m.k0 = k0;
+        // steps in flight per wave: what the registers of one workgroup per compute unit hold
+        switch ((s->A1 + 31) / 32) {
+        case 1: return launch_mfma_rt<1, 6>(m, (unsigned)nk, st);
+        case 2: return launch_mfma_rt<2, 4>(m, (unsigned)nk, st);
+        case 3: return launch_mfma_rt<3, 3>(m, (unsigned)nk, st);
+        default: return launch_mfma_rt<4, 3>(m, (unsigned)nk, st);
+        }
+    }
     S1Params p;
     p.X = X; p.I = s->I; p.J = s->J; p.K = s->K; p.A1 = s->A1; p.B1 = s->B1; p.k0 = k0;
     p.Uoc = s->Uoc; p.Uch = s->Uch; p.Vtp = s->Vtp; p.Vent = s->Vent; p.Q = s->Q; p.jt_per = s->jt_per; p.qstride = qstride_of(s);
