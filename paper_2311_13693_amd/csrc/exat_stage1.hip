@@ -280,8 +280,8 @@ template <int N, typename F> __device__ __forceinline__ void s1_static_for(F &&f
 // RT x MT blocks of the slice's B1 x A1 result are dealt out to the four waves (block b = mt RT + rt to wave b mod 4), each
 // of which adds, over the tile's 16 column blocks, V fragment x split Z^T fragment to the blocks it owns, in registers,
 // for the whole slice.  No two waves add to the same number, so every sum has a fixed order.
-template <int RT, int MT, int D, bool RAGGED>
-__global__ __launch_bounds__(64 * SM_NW, 1) void k_stage1_mfma(const S1MParams p)
+template <int RT, int MT, int D, bool RAGGED, int WPC = 1>
+__global__ __launch_bounds__(64 * SM_NW, WPC) void k_stage1_mfma(const S1MParams p)
 {
     extern __shared__ float smem[];
     constexpr int DL = 2;                           // LDS slots per wave
@@ -416,18 +416,26 @@ __global__ __launch_bounds__(64 * SM_NW, 1) void k_stage1_mfma(const S1MParams p
                 x[0] = *(const s1_f32x4 *)src; x[1] = *(const s1_f32x4 *)(src + 256);
                 split3(x, zh, zm, zl);
             }
+            if constexpr (ONE_RT) {
+                // pieces outside, blocks inside: consecutive MFMAs go to different accumulators
 #pragma unroll
-            for (int i = 0; i < NBW; i++) {
-                if constexpr (!ONE_RT) {
+                for (int i = 0; i < NBW; i++) qacc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vr[jb & 1][i], zl, qacc[i], 0, 0, 0);
+#pragma unroll
+                for (int i = 0; i < NBW; i++) qacc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vr[jb & 1][i], zm, qacc[i], 0, 0, 0);
+#pragma unroll
+                for (int i = 0; i < NBW; i++) qacc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vr[jb & 1][i], zh, qacc[i], 0, 0, 0);
+            } else {
+#pragma unroll
+                for (int i = 0; i < NBW; i++) {
                     const int rt = (w + SM_NW * i) % RT;
                     const float *src = zt + ((jb * RT + rt) * 2) * 256 + lane * 4;
                     s1_f32x4 x[2];
                     x[0] = *(const s1_f32x4 *)src; x[1] = *(const s1_f32x4 *)(src + 256);
                     split3(x, zh, zm, zl);
+                    qacc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vr[jb & 1][i], zl, qacc[i], 0, 0, 0);
+                    qacc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vr[jb & 1][i], zm, qacc[i], 0, 0, 0);
+                    qacc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vr[jb & 1][i], zh, qacc[i], 0, 0, 0);
                 }
-                qacc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vr[jb & 1][i], zl, qacc[i], 0, 0, 0);
-                qacc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vr[jb & 1][i], zm, qacc[i], 0, 0, 0);
-                qacc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vr[jb & 1][i], zh, qacc[i], 0, 0, 0);
             }
         }
         __syncthreads();   // the slots take the LDS back
@@ -449,22 +457,26 @@ __global__ __launch_bounds__(64 * SM_NW, 1) void k_stage1_mfma(const S1MParams p
                 for (int m = 0; m < 8; m++) *(s1_f32x4 *)(slot + swz(8 * m + (lane >> 3), lane & 7)) = xr[d][m];
                 request_x(n + D, xr[d]);
 #pragma unroll
-                for (int h = 0; h < 2; h++)
+                for (int h = 0; h < 2; h++) {
+                    s1_bf16x8 xp[3][SM_CT];   // pieces l, m, h of the two column tiles
 #pragma unroll
                     for (int ct = 0; ct < SM_CT; ct++) {
                         const int j = 32 * ct + l32;
                         s1_f32x4 x[2];
                         x[0] = *(const s1_f32x4 *)(slot + swz(j, 4 * h + 2 * hi));
                         x[1] = *(const s1_f32x4 *)(slot + swz(j, 4 * h + 2 * hi + 1));
-                        s1_bf16x8 xh, xm, xl;
-                        split3(x, xh, xm, xl);
-#pragma unroll
-                        for (int rt = 0; rt < RT; rt++) {
-                            acc[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xl, ur[d][h][rt], acc[rt][ct], 0, 0, 0);
-                            acc[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xm, ur[d][h][rt], acc[rt][ct], 0, 0, 0);
-                            acc[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh, ur[d][h][rt], acc[rt][ct], 0, 0, 0);
-                        }
+                        split3(x, xp[2][ct], xp[1][ct], xp[0][ct]);
                     }
+                    // smallest pieces first; consecutive MFMAs go to different accumulators (one that adds to the result of
+                    // the instruction before it waits for that result)
+#pragma unroll
+                    for (int pc = 0; pc < 3; pc++)
+#pragma unroll
+                        for (int ct = 0; ct < SM_CT; ct++)
+#pragma unroll
+                            for (int rt = 0; rt < RT; rt++)
+                                acc[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xp[pc][ct], ur[d][h][rt], acc[rt][ct], 0, 0, 0);
+                }
                 request_u(n + D, ur[d]);
             });
         }
@@ -644,30 +656,30 @@ int launch12(const S1Params &p, dim3 grid, size_t lds, hipStream_t st)
     return hipGetLastError() == hipSuccess ? EXAT_OK : EXAT_ERR_HIP;
 }
 
-template <int RT, int MT, int D, bool RAGGED>
+template <int RT, int MT, int D, bool RAGGED, int WPC = 1>
 int launch_mfma_inst(const S1MParams &p, unsigned nk, hipStream_t st)
 {
     const size_t zt = (size_t)16 * RT * 2 * 256 * sizeof(float), slots = (size_t)SM_NW * 2 * 64 * SM_GI * sizeof(float);
     const size_t lds = zt > slots ? zt : slots;
-    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_stage1_mfma<RT, MT, D, RAGGED>),
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_stage1_mfma<RT, MT, D, RAGGED, WPC>),
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (attr != hipSuccess) return EXAT_ERR_HIP;
-    hipLaunchKernelGGL((k_stage1_mfma<RT, MT, D, RAGGED>), dim3(nk), dim3(64 * SM_NW), lds, st, p);
+    hipLaunchKernelGGL((k_stage1_mfma<RT, MT, D, RAGGED, WPC>), dim3(nk), dim3(64 * SM_NW), lds, st, p);
     return hipGetLastError() == hipSuccess ? EXAT_OK : EXAT_ERR_HIP;
 }
-template <int RT, int MT, int D>
+template <int RT, int MT, int D, int WPC>
 int launch_mfma(const S1MParams &p, unsigned nk, hipStream_t st)
 {
-    return (p.I % SM_GI) ? launch_mfma_inst<RT, MT, D, true>(p, nk, st) : launch_mfma_inst<RT, MT, D, false>(p, nk, st);
+    return (p.I % SM_GI) ? launch_mfma_inst<RT, MT, D, true, WPC>(p, nk, st) : launch_mfma_inst<RT, MT, D, false, WPC>(p, nk, st);
 }
-template <int RT, int D>
+template <int RT, int D, int WPC>
 int launch_mfma_rt(const S1MParams &p, unsigned nk, hipStream_t st)
 {
     switch ((p.B1 + 31) / 32) {
-    case 1: return launch_mfma<RT, 1, D>(p, nk, st);
-    case 2: return launch_mfma<RT, 2, D>(p, nk, st);
-    case 3: return launch_mfma<RT, 3, D>(p, nk, st);
-    default: return launch_mfma<RT, 4, D>(p, nk, st);
+    case 1: return launch_mfma<RT, 1, D, WPC>(p, nk, st);
+    case 2: return launch_mfma<RT, 2, D, WPC>(p, nk, st);
+    case 3: return launch_mfma<RT, 3, D, WPC>(p, nk, st);
+    default: return launch_mfma<RT, 4, D, WPC>(p, nk, st);
     }
 }
 
@@ -849,12 +861,14 @@ int run_mode12(exat_stage1_s *s, const float *X, int64_t k0, int64_t nk, hipStre
         S1MParams m;
         m.X = X; m.I = s->I; m.J = s->J; m.A1 = s->A1; m.B1 = s->B1; m.Ud = (const __bf16 *)s->Ud; m.Vd = (const __bf16 *)s->Vd;
         m.Q = s->Q; m.k0 = k0;
-        // steps in flight per wave: what the registers of one workgroup per compute unit hold
+        // Two steps in flight per wave measured best at every size (three or more cost registers and gain nothing: the
+        // waves of a compute unit together keep 64 to 128 KiB on their way).  Up to 64 rows a the registers allow two
+        // workgroups per compute unit, which is worth more than depth (cfg2: 0.116 -> 0.101 ms).
         switch ((s->A1 + 31) / 32) {
-        case 1: return launch_mfma_rt<1, 6>(m, (unsigned)nk, st);
-        case 2: return launch_mfma_rt<2, 4>(m, (unsigned)nk, st);
-        case 3: return launch_mfma_rt<3, 3>(m, (unsigned)nk, st);
-        default: return launch_mfma_rt<4, 3>(m, (unsigned)nk, st);
+        case 1: return launch_mfma_rt<1, 2, 2>(m, (unsigned)nk, st);
+        case 2: return launch_mfma_rt<2, 2, 2>(m, (unsigned)nk, st);
+        case 3: return launch_mfma_rt<3, 2, 1>(m, (unsigned)nk, st);
+        default: return launch_mfma_rt<4, 2, 1>(m, (unsigned)nk, st);
         }
     }
     S1Params p;

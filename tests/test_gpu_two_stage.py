@@ -48,6 +48,11 @@ def _first_stage_gpu(ts, X, mats):
     dict(I=140, J=70, K=6, L=11, M=45, N=9, beta=2),                     # A1=22, B1=90
     dict(I=384, J=130, K=4, L=64, M=64, N=2),                            # A1=B1=128: the largest supported
     dict(I=5, J=3, K=2, L=1, M=1, N=1, alpha=1, beta=1, gamma=1, s=1),   # everything smaller than a tile
+    # the matrix-core form (I a multiple of 4, values +-1/2): three row tiles of a (result blocks of a wave in different
+    # row tiles), three 256-column tiles with a ragged last one, a ragged last step of 32 rows
+    dict(I=268, J=600, K=5, L=48, M=24, N=3),                            # A1=96, B1=48
+    dict(I=512, J=512, K=3, L=16, M=64, N=2),                            # A1=32, B1=128: one row tile, four result blocks
+    dict(I=96, J=40, K=4, L=32, M=32, N=2, s=3),                         # values 3**-0.5 are no bf16 numbers: the sparse form
 ])
 def test_first_stage_matches_oracle(shape):
     ts = _ts(**shape)
@@ -61,6 +66,21 @@ def test_first_stage_matches_oracle(shape):
     print("  rel_fro=%.3e" % err, flush=True)
     assert err <= TOL
     assert np.abs(got - ref).max() <= 1e-5 * np.abs(ref).max()
+
+
+def test_first_stage_matrix_core_form_agrees_with_sparse_form(monkeypatch):
+    """Both forms compute the same sums from the same operands; the matrix-core form splits X exactly, so they differ
+    by the order of fp32 additions only."""
+    ts = _ts(I=320, J=300, K=6, L=32, M=32, N=4, index=303)
+    b = ts.base
+    X = _x(17, b.I, b.J, b.K)
+    mats = wl.first_stage_matrices(ts)
+    got = _first_stage_gpu(ts, X, mats)
+    monkeypatch.setenv("EXAT_STAGE1_MFMA", "0")
+    sparse = _first_stage_gpu(ts, X, mats)
+    err = _rel(got, sparse)
+    print("  matrix-core form against sparse form: rel_fro=%.3e" % err, flush=True)
+    assert err <= 1e-6 and err > 0.0   # > 0: the two runs did take different kernels
 
 
 def test_first_stage_general_csr_and_run_to_run():
