@@ -314,7 +314,7 @@ def two_stage(args):
         "kernel_ms": {"stage1_mode12": ms12, "stage1_mode3": ms3},
         "read_only_pass_over_X": {"what": "torch.sum over the same tensor", "ms": ms_read,
                                   "GB/s": 4.0 * cfg.elements / (ms_read * 1e-3) / 1e9},
-        "roofline": {"bound": "hbm", "kernel": "k_stage1_mode12", "achieved": achieved, "peak": 8000.0, "unit": "GB/s",
+        "roofline": {"bound": "hbm", "kernel": "k_stage1_mfma (k_stage1_mode12 when U or V is no bf16 matrix)", "achieved": achieved, "peak": 8000.0, "unit": "GB/s",
                      "frac": achieved / 8000.0, "traffic": recorded_traffic(cfg.name + "_two_stage")},
     }
     if args.check:

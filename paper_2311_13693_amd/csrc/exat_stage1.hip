@@ -1,7 +1,7 @@
 // First stage of the two-stage compression (paper Sec. 4.4): X1 = X x1 U x2 V x3 W with sparse U, V, W
 // shared by all replicas.  Declarations and contracts in include/exat.h.
 //
-// The stage reads X once from HBM (4 bytes per element against 2*nnz_per_column flops) and uses no matrix cores:
+// The stage reads X once from HBM (4 bytes per element against 2*nnz_per_column flops):
 //   k_stage1_mode12  one workgroup per (frontal slice k, range of column tiles).  It walks its part of the slice
 //                    in 64-column x 128-row tiles that go HBM -> registers -> LDS, each element once.  Mode 1: a
 //                    lane owns a column j of the tile; the non-zeros of U inside the row tile are dealt to the
@@ -12,14 +12,13 @@
 //   k_stage1_sum_ranges  adds the partial results of the column ranges (only when a slice was split).
 //   k_stage1_mode3   X1[a,b,c] = sum_k W[c,k] Q[k][b][a], a thread per (a,b,c), the non-zeros of row c in
 //                    stored order.
-//   k_stage1_mfma    the same two modes when every value of U is exactly representable in bf16 (sign matrices are): U is
-//                    taken as a DENSE A1 x I bf16 matrix and mode 1 runs on the matrix cores, which are otherwise idle in
-//                    this read-bound stage, with X read straight from HBM into MFMA operand registers (a lane owns a column
-//                    and walks down it 8 values at a time: no LDS tile, no gather, no barrier in the loop) several steps
-//                    ahead, and split on the fly into three truncated bf16 pieces (8 + 8 + 8 significand bits: the split is
-//                    exact, so the products are too).  16 times the arithmetic of the sparse form, on a unit with nothing
-//                    else to do; what it buys is that the bytes in flight per compute unit are set by a register ring, not
-//                    by how many LDS tiles fit.  Mode 2 is the sparse one above, on the finished tile in LDS.
+//   k_stage1_mfma    the same two modes on the matrix cores, which are otherwise idle in this read-bound stage, when every
+//                    value of U and V is exactly representable in bf16 (sign matrices are) and I is a multiple of 4: U and V
+//                    are taken as DENSE bf16 matrices, X is read along its columns in whole cache lines, transposed through
+//                    wave-private LDS slots and split on the fly into three truncated bf16 pieces (an exact split, so the
+//                    products are exact too); described at the kernel.  16 times the arithmetic of the sparse form on a unit
+//                    with nothing else to do; the sparse form's per-non-zero instruction streams and dependent scalar loads
+//                    are what kept it below half of the HBM peak.
 // Every sum has a fixed order, so results are bit-identical from run to run.
 #include "../../include/exat.h"
 
