@@ -187,7 +187,11 @@ int exat_plan_timing_of(exat_plan_t plan, int32_t age, float *ms_mode12, float *
  *
  *     X1[a,b,c] = sum_{i,j,k} U[a,i] V[b,j] W[c,k] X[i,j,k],
  *
- * is what exat_stage1_apply computes: one pass over X that is bound by reading it (no matrix cores).
+ * is what exat_stage1_apply computes: one pass over X that is bound by reading it.  When every entry of U and
+ * of V (repeated entries added) is a bf16 number, as the entries of sign matrices are, and I is a multiple of 4,
+ * the first two modes run on the matrix cores with X split exactly into three bf16 pieces (same result up to
+ * the order of the fp32 additions); otherwise, or with EXAT_STAGE1_MFMA=0 in the environment at creation, a
+ * sparse form runs that uses the vector units only.
  * The second stage is the dense multi-replica compression of X1: an ordinary plan with I,J,K = A1,B1,C1
  * and U', V', W' as its factors, fed with X1 through exat_compress.
  *
