@@ -175,6 +175,12 @@ def test_first_stage_degenerate_shapes():
         (40, 70, 3, zero_csr(4), dense_csr(rng.standard_normal((5, 70))), dense_csr(rng.standard_normal((2, 3)))),
         (300, 90, 5, dense_csr(rng.standard_normal((128, 300))), dense_csr(rng.standard_normal((128, 90))),
          dense_csr(rng.standard_normal((7, 5)))),
+        # bf16-valued U and V with I a multiple of 4: the matrix-core form, on one short step of one ragged tile, with an
+        # all-zero U, and with dense sign matrices over three column tiles
+        (4, 1, 1, dense_csr(np.array([[1.0, -2.0, 0.5, 4.0]])), dense_csr(np.array([[3.0]])), dense_csr(np.array([[5.0]]))),
+        (8, 3, 2, zero_csr(4), dense_csr(np.sign(rng.standard_normal((5, 3)))), dense_csr(rng.standard_normal((2, 2)))),
+        (64, 520, 3, dense_csr(0.5 * np.sign(rng.standard_normal((128, 64)))), dense_csr(np.sign(rng.standard_normal((128, 520)))),
+         dense_csr(rng.standard_normal((7, 3)))),
     ]
     for I, J, K, U, V, W in cases:
         print("case", I, J, K, len(U[0]) - 1, len(V[0]) - 1, len(W[0]) - 1, flush=True)
