@@ -322,12 +322,12 @@ int run_chain(exat_plan_s *pl, Mode12Params mp, bool generated, float *Yout, int
             else if (pl->d.L % 32 == 0 && env_int("EXAT_ZT", 1))
                 rc = rt == 4 ? launch_v3_mat_zt<8, 2>(mp, gs, uf, nk, st) : launch_v3_mat_zt<4, 2>(mp, gs, uf, nk, st);
             else rc = rt == 4 ? launch_v3_mat<float, 8, 2>(mp, gs, uf, nk, st) : launch_v3_mat<float, 4, 2>(mp, gs, uf, nk, st);
-        } else if (bf && pl->PL > 256 && ks == 1 && env_int("EXAT_RT", 0) == 0 && pl->Ipad < (1LL << 24)) {
+        } else if (bf && pl->PL > 256 && ks == 1 && env_int("EXAT_RT", 0) == 0 && pl->Ipad < (1LL << 21)) {
             // 512-row groups, two waves per SIMD (k_mode12_v4): the tile is generated once per group, so large groups
             // are what keeps the generator's vector work below the MFMA work.  Factor ranks above 32 would need twice
             // the generator registers, which this build does not have: they take the 384-row kernel below.  The kernel
-            // addresses U and the generator's A pieces with 32-bit byte offsets (128 bytes per padded column and wave):
-            // 2^24 padded columns and more take the 384-row kernel as well.
+            // addresses U and the generator's A pieces with 32-bit byte offsets (a wave's two row tiles are 8 tiles, 576
+            // bytes per padded column, apart): 2^21 padded columns and more take the 384-row kernel as well.
             mp.G = (pl->PL + 511) / 512;
             rc = launch_v4_gen_bf16(mp, gs, uf, boxed, nk, st);
         } else if (bf) {

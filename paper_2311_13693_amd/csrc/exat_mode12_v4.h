@@ -59,7 +59,10 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void k_mode12_v4(const Mode12Param
     if (kidx >= nk) return;
     const int64_t k = p.k0 + kidx;
     const int row0 = p.row_base + g * ROWS;
-    const int wrow0 = row0 + wave * (RT * 32);
+    // row tile rt of wave w is tile w + NW*rt of the group: when the group's last tiles lie beyond the stacked rows (cfg5's
+    // fifth group has 11 of 16), the waves that lose a tile are spread over all four SIMDs
+    const int wrow0 = row0 + wave * 32;
+    const bool two_tiles = RT == 2 && wrow0 + NW * 32 < p.PL;   // wave-uniform: this wave's second tile holds stacked rows
     const int64_t ia0 = p.i0 & ~(int64_t)(EI - 1);
     const int nstage = (int)((p.i1 - ia0 + EI - 1) / EI);
     const int64_t ja0 = (p.j0 / COLS) * COLS;
@@ -84,7 +87,7 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void k_mode12_v4(const Mode12Param
         // buffer addressing: the descriptor holds the base, a scalar register the wave-uniform part of the offset, and the
         // one vector register u_lane / a_lane the per-lane part, so that a request costs no vector instruction at all
         const __amdgpu_buffer_rsrc_t urs = __builtin_amdgcn_make_buffer_rsrc(
-            (void *)((const char *)uf.Uf + ((int64_t)(wrow0 >> 5) * uf.nig) * 1024), 0, (int)(RT * u_rt_step * 2), 0x00020000);
+            (void *)((const char *)uf.Uf + ((int64_t)(wrow0 >> 5) * uf.nig) * 1024), 0, (int)(((RT - 1) * NW + 1) * u_rt_step * 2), 0x00020000);
         const __amdgpu_buffer_rsrc_t ars = __builtin_amdgcn_make_buffer_rsrc((void *)gs.Asp, 0, (int)(2 * gs.Irows * gs.Rpad * 2), 0x00020000);
         const uint32_t iq_lane = 4u * (unsigned)si + (unsigned)q16;                             // quad of i within a stage
         const int xs_r = l32 * ROWB + hi * 16;                                          // + ct*32*ROWB + g2*32
@@ -126,7 +129,7 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void k_mode12_v4(const Mode12Param
 
         auto stage_i = [&](int s) -> int64_t { return ia0 + (int64_t)(s < nstage ? s : nstage - 1) * EI; };
         auto load_uf = [&](int rt, int64_t ig) -> bf16x8 {
-            return __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(urs, (int)u_lane, (int)((rt * u_rt_step + ig * (64 * E16)) * 2), 0));
+            return __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(urs, (int)u_lane, (int)((rt * NW * u_rt_step + ig * (64 * E16)) * 2), 0));
         };
         // A pieces of rows 16*si .. 16*si+15 of tile s
         auto load_a = [&](int s, bf16x8 *af) {
@@ -224,14 +227,15 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void k_mode12_v4(const Mode12Param
         // the noise steps in proportion to the MFMA's duration"; the generator's MFMAs sit between the main ones of the
         // first two thirds; a request for operands of a later stage follows the last MFMA that reads the registers it
         // refills; the first steps run ahead of the first MFMA, under the latency of the LDS reads.
-        auto stage = [&](auto sic, int s) {
+        auto stage = [&](auto sic, auto rac, int s) __attribute__((always_inline)) {
             constexpr int SI = decltype(sic)::value;  // s mod UNR
+            constexpr int RA = decltype(rac)::value;  // row tiles of this wave that hold stacked rows (1 .. RT)
             constexpr int PH = SI & 1, US = SI % DU;
             constexpr int PN = (PH + W) & 1, PG = PN ^ 1;   // parities of the tile whose noise / whose low-rank part this stage makes
             const unsigned char *cur = smem + (SI % NXB) * XBUF;
             unsigned char *oth = smem + ((SI + W) % NXB) * XBUF;
             const int64_t ig2 = stage_i(s + DU) / GI;
-            constexpr int NGEN = NTERM * KS * SJW, NMAIN = 2 * RT * CT;
+            constexpr int NGEN = NTERM * KS * SJW, NMAIN = 2 * RA * CT;
             // X fragment f = g2*CT + ct: columns 32 ct .. 32 ct + 31, i group g2
             auto load_bx = [&](int f) -> bf16x8 { return *(const bf16x8 *)(cur + xs_r + (f % CT) * 32 * ROWB + (f / CT) * 32); };
             if constexpr (SCHED == 0) {
@@ -244,7 +248,7 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void k_mode12_v4(const Mode12Param
 #pragma unroll
                 for (int g2 = 0; g2 < 2; g2++)
 #pragma unroll
-                    for (int rt = 0; rt < RT; rt++) {
+                    for (int rt = 0; rt < RA; rt++) {
 #pragma unroll
                         for (int ct = 0; ct < CT; ct++) acc[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bx[g2][ct], ufr[US][rt][g2], acc[rt][ct], 0, 0, 0);
                         ufr[US][rt][g2] = load_uf(rt, ig2 + g2);   // refill for stage s+DU
@@ -266,7 +270,7 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void k_mode12_v4(const Mode12Param
                 static_for<NFRONT>([&](auto uc) { nstep(uc, ib1, oth, lr[PN]); });
                 __builtin_amdgcn_sched_barrier(0);
                 static_for<NMAIN>([&](auto mc) {
-                    constexpr int m = decltype(mc)::value, f = m / RT, rt = m % RT, g2 = f / CT, ct = f % CT;
+                    constexpr int m = decltype(mc)::value, f = m / RA, rt = m % RA, g2 = f / CT, ct = f % CT;
                     if constexpr (rt == 0 && f + BXA < 2 * CT) bx[(f + BXA) % (BXA + 1)] = load_bx(f + BXA);
                     acc[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bx[f % (BXA + 1)], ufr[US][rt][g2], acc[rt][ct], 0, 0, 0);
                     if constexpr (ct == CT - 1) ufr[US][rt][g2] = load_uf(rt, ig2 + g2);   // last use this stage: refill for stage s+DU
@@ -290,6 +294,10 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void k_mode12_v4(const Mode12Param
         };
 
         // ---- prologue ----
+        // (the stage loop exists twice: for waves with RT row tiles, and for waves whose second tile lies beyond the stacked
+        //  rows, which then run half the main MFMAs and request half the U fragments; the choice is wave-uniform)
+        auto run = [&](auto rac) __attribute__((always_inline)) {
+            constexpr int RA = decltype(rac)::value;
         // Tiles 0 .. W-1 go to the ring, the low-rank part of tile W to its register set, and the A pieces of tiles W+1 and
         // W+2 to theirs.  Order of the requests: all A pieces first, the U fragments last.  The compiler derives the wait in
         // front of a stage's first generator MFMA from the smaller of two counts of requests issued after the A pieces it
@@ -303,7 +311,7 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void k_mode12_v4(const Mode12Param
             for (int d = 0; d < DU; d++) {
                 const int64_t igd = stage_i(d) / GI;
 #pragma unroll
-                for (int rt = 0; rt < RT; rt++)
+                for (int rt = 0; rt < RA; rt++)
 #pragma unroll
                     for (int g2 = 0; g2 < 2; g2++) ufr[d][rt][g2] = load_uf(rt, igd + g2);
             }
@@ -323,21 +331,24 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void k_mode12_v4(const Mode12Param
         int s = 0;
         for (; s + UNR <= nstage; s += UNR)
             static_for<UNR>([&](auto c) {
-                stage(c, s + decltype(c)::value);
+                stage(c, rac, s + decltype(c)::value);
                 if constexpr ((decltype(c)::value + 1) % W == 0) __syncthreads();
             });
         static_for<UNR - 1>([&](auto c) {
             if (s + decltype(c)::value < nstage) {
-                stage(c, s + decltype(c)::value);
+                stage(c, rac, s + decltype(c)::value);
                 if constexpr ((decltype(c)::value + 1) % W == 0) __syncthreads();
             }
         });
 
+        };
+        if (two_tiles) run(ic<RT>()); else run(ic<1>());
+
         // ---- mode 2 on the finished chunk, straight from the accumulators (they hold Z^T: the MFMAs above take the X
         //      fragment as first and the U fragment as second operand) ----
         const bool first_chunk = (jc == ja0);
-        if (p.MT == 2) mode2_direct_bf16<RT, CT, 2>(p, uf.Vz, acc, wrow0, kidx, jc, first_chunk, tid & 63);
-        else mode2_direct_bf16<RT, CT, 1>(p, uf.Vz, acc, wrow0, kidx, jc, first_chunk, tid & 63);
+        if (p.MT == 2) mode2_direct_bf16<RT, CT, 2, NW * 32>(p, uf.Vz, acc, wrow0, kidx, jc, first_chunk, tid & 63);
+        else mode2_direct_bf16<RT, CT, 1, NW * 32>(p, uf.Vz, acc, wrow0, kidx, jc, first_chunk, tid & 63);
     }
 }
 
