@@ -251,7 +251,7 @@ int launch_split(const Mode12Params &mp, const SplitParams &sp, int nk, hipStrea
 }
 
 // fills the plan-dependent part of the parameters and launches mode 1+2 followed by mode 3
-int run_chain(exat_plan_s *pl, Mode12Params mp, bool generated, float *Yout, int accumulate, hipStream_t st)
+int run_chain(exat_plan_s *pl, Mode12Params mp, bool generated, float *Yout, int accumulate, hipStream_t st, unsigned char *flag = nullptr)
 {
     // The pipelined kernels need whole 64-byte stages of i inside the box (materialised source) or a factor
     // rank that fits their generator (generated source); everything else takes the generic kernel.
@@ -371,7 +371,7 @@ int run_chain(exat_plan_s *pl, Mode12Params mp, bool generated, float *Yout, int
     m3.Q = pl->Q; m3.W = pl->Wpack; m3.Y = Yout;
     m3.L = pl->d.L; m3.M = pl->d.M; m3.N = pl->d.N; m3.PL = pl->PL; m3.PLpad = pl->PLpad; m3.Mpad = pl->Mpad;
     m3.Npad = pl->Npad;
-    m3.K = pl->d.K; m3.k0 = mp.k0; m3.k1 = mp.k1; m3.accumulate = accumulate;
+    m3.K = pl->d.K; m3.k0 = mp.k0; m3.k1 = mp.k1; m3.accumulate = accumulate; m3.flag = flag;
     const int64_t ntile = ((int64_t)pl->PL * pl->Mpad + 31) / 32;
     dim3 grid((unsigned)ntile, (unsigned)((pl->Npad + 63) / 64));
     const bool longk = (m3.k1 - m3.k0) > 512LL * M3_WAVES - 8;   // a wave's slab (rounded up to even) may exceed 512
@@ -391,7 +391,6 @@ int run_chain(exat_plan_s *pl, Mode12Params mp, bool generated, float *Yout, int
     return EXAT_OK;
 }
 
-__global__ void k_set_flag(unsigned char *flags, int idx, unsigned char v) { flags[idx] = v; }
 __global__ void k_clear_flags(unsigned char *flags, int n)
 {
     for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) flags[i] = 0;
@@ -570,13 +569,11 @@ int exat_compress_block(exat_plan_t pl, const void *Xblk, int32_t bi, int32_t bj
     const int e16 = 16 / (int)esize(d.in_dtype);
     mp.x_vec = (di % e16 == 0) && (mp.xo_i % e16 == 0) && (((uintptr_t)Xblk & 15) == 0);
     mp.i0 = mp.xo_i; mp.i1 = mp.xo_i + di; mp.j0 = mp.xo_j; mp.j1 = mp.xo_j + dj; mp.k0 = mp.xo_k; mp.k1 = mp.xo_k + dk;
-    int rc = run_chain(pl, mp, false, pl->slots + (int64_t)slot * pl->ysize, pl->slot_used[(size_t)slot] ? 1 : 0, st);
+    // the mode-3 launch of the block marks its slot as holding a partial result (the merge adds marked slots only)
+    int rc = run_chain(pl, mp, false, pl->slots + (int64_t)slot * pl->ysize, pl->slot_used[(size_t)slot] ? 1 : 0, st,
+                       pl->slot_used[(size_t)slot] ? nullptr : pl->used_dev + slot);
     if (rc != EXAT_OK) return rc;
-    if (!pl->slot_used[(size_t)slot]) {
-        hipLaunchKernelGGL(k_set_flag, dim3(1), dim3(1), 0, st, pl->used_dev, slot, (unsigned char)1);
-        if (hipGetLastError() != hipSuccess) return EXAT_ERR_HIP;
-        pl->slot_used[(size_t)slot] = 1;
-    }
+    pl->slot_used[(size_t)slot] = 1;
     pl->submitted[(size_t)blk] = 1;
     pl->nsubmitted++;
     return EXAT_OK;

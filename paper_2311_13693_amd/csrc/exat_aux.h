@@ -59,6 +59,7 @@ struct Mode3Params {
     int L, M, N, PL, PLpad, Mpad, Npad;
     int64_t K, k0, k1;
     int accumulate;
+    unsigned char *flag;  // if not null, set to 1 by the launch (block streaming: "this slot holds a partial result")
 };
 
 // One workgroup per 32 (q, m) positions x <= 64 columns n; its M3_WAVES waves split the k range into contiguous
@@ -75,6 +76,7 @@ __global__ __launch_bounds__(64 * M3_WAVES, LONGK ? 1 : 2) void k_mode3(const Mo
     constexpr int KFLUSH = 512;
     __shared__ float part[M3_WAVES - 1][NT][16][64];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, l32 = lane & 31, hi = lane >> 5;
+    if (p.flag != nullptr && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *p.flag = 1;
     const int64_t pos0 = (int64_t)blockIdx.x * 32;
     if (pos0 >= (int64_t)p.PL * p.Mpad) return;  // whole workgroup
     const int q = (int)(pos0 / p.Mpad), m0 = (int)(pos0 % p.Mpad);
