@@ -55,6 +55,9 @@ def parse():
                          "resident in HBM as its own array, through exat_compress_block, then exat_finalize) instead of the "
                          "one-shot call on the whole tensor; the algorithmic flops stay those of the three modes once each, "
                          "so the per-block repetition of modes 2 and 3 shows up as a lower fraction")
+    ap.add_argument("--slab", type=int, default=0,
+                    help="with --blocks: compress the blocks in slabs of this many block layers along k per call "
+                         "(exat_compress_blocks; all blocks of a slab resident at once) instead of one call per block")
     ap.add_argument("--split", action="store_true",
                     help="fp32 materialised configurations only: run the contractions on the fp16 matrix cores with "
                          "two-piece operands (EXAT_F32_SPLIT) instead of fp32 MFMA; reported against the fp16 MFMA peak")
@@ -435,9 +438,21 @@ def main():
         del X
         X = None
 
+        nbi, nbj, nbk = cfg.I // cfg.dI, cfg.J // cfg.dJ, cfg.K // cfg.dK
+        slabs = []
+        if args.slab > 0:
+            per_layer = nbi * nbj
+            for bk0 in range(0, nbk, args.slab):
+                bk1 = min(nbk, bk0 + args.slab)
+                slabs.append(([t for _, _, _, t in blocks[bk0 * per_layer:bk1 * per_layer]], bk0, bk1))
+
         def step():
-            for bi, bj, bk, t in blocks:
-                plan.compress_block(t, bi, bj, bk)
+            if slabs:
+                for ts, bk0, bk1 in slabs:
+                    plan.compress_blocks(ts, 0, nbj, bk0, bk1)
+            else:
+                for bi, bj, bk, t in blocks:
+                    plan.compress_block(t, bi, bj, bk)
             plan.finalize(Y)
 
     plan.set_timing(True)
@@ -454,7 +469,7 @@ def main():
         step()                         # back to back: nothing waits inside the timed region
     e1.record()
     torch.cuda.synchronize()
-    calls_per_step = len(blocks) if blocks else 1
+    calls_per_step = (len(slabs) if slabs else len(blocks)) if blocks else 1
     covered = max(1, min(steps, 128 // calls_per_step))   # whole passes inside the library's ring of 128 timed calls
     for age in range(min(covered * calls_per_step, 128)):
         a, b = plan.timing_of(age)
@@ -480,7 +495,9 @@ def main():
         "data": "synthetic",
         "config": {"workload": "%s: %dx%dx%d %s, R=%d, P=%d, L=M=N=%d, %s" % (
             cfg.name, cfg.I, cfg.J, cfg.K, cfg.dtype, cfg.R, cfg.P, cfg.L,
-            ("block-streamed from HBM in %dx%dx%d blocks (exat_compress_block + exat_finalize)" % (cfg.dI, cfg.dJ, cfg.dK)) if blocks
+            (("block-streamed from HBM in %dx%dx%d blocks, " % (cfg.dI, cfg.dJ, cfg.dK)) +
+             (("slabs of %d block layers per call (exat_compress_blocks + exat_finalize)" % args.slab) if slabs
+              else "one call per block (exat_compress_block + exat_finalize)")) if blocks
             else ("materialised in HBM" if cfg.materialised else "generated on chip")),
             "sigma": cfg.sigma},
         "ttm_tflops": cfg.flops * frac / (ms_step * 1e-3) / 1e12,

@@ -137,6 +137,24 @@ int exat_compress(exat_plan_t plan, const void *X, float *Y, void *stream);
 int exat_compress_block(exat_plan_t plan, const void *Xblk, int32_t bi, int32_t bj, int32_t bk,
                         void *stream);
 
+/* Block-streamed compression with several blocks resident at once (Sec. 4.3, Fig. 2: the blocks are independent,
+ * so as many as the memory holds can be taken together): one call compresses the SLAB of blocks
+ * { (bi, bj, bk) : 0 <= bi < ceil(I/dI), bj0 <= bj < bj1, bk0 <= bk < bk1 }, i.e. whole block columns along i.
+ * Xblk: HOST array of ceil(I/dI)*(bj1-bj0)*(bk1-bk0) device pointers, bi fastest, then bj, then bk; each block
+ * column-major in its actual extents as for exat_compress_block.  The array is read before the call returns; the
+ * blocks must stay valid until the work on `stream` has completed.
+ * A slab is compressed as one sub-tensor: mode 1 runs over the whole i extent before mode 2 is applied and mode 2
+ * over the slab's j range before mode 3, so every mode is applied once per element (a lone block repeats modes 2
+ * and 3) and one launch fills the chip.  The slab leaves one partial result, which exat_finalize merges with those
+ * of the other slabs and single blocks of the pass in a fixed order: Y does not depend on the order of the calls,
+ * only on how the blocks were grouped into slabs (rounding).  Requirements of the one-launch form: EXAT_F32, L a
+ * multiple of 32, dI a multiple of 16 that divides I, dJ a multiple of 128, 16-byte aligned blocks; any other
+ * slab is compressed block by block, as by exat_compress_block.  Allocates on its first use with a plan (the block
+ * partials and a table of one pointer per block).
+ * Errors: NULL, STATE (factors not set, a block of the slab submitted twice), SHAPE, ALLOC, HIP. */
+int exat_compress_blocks(exat_plan_t plan, const void *const *Xblk, int32_t bj0, int32_t bj1, int32_t bk0,
+                         int32_t bk1, void *stream);
+
 /* Merges the block partials into Y (overwritten) and resets the plan's block state so
  * that a new sequence of exat_compress_block calls can start.
  * Errors: NULL, STATE (no block submitted), HIP. */

@@ -45,6 +45,7 @@ struct exat_plan_s {
     int64_t nblocks = 0, ysize = 0;
     std::vector<unsigned char> submitted, slot_used;
     int64_t nsubmitted = 0;
+    const void **xtab = nullptr;   // device: one pointer per block of X (exat_compress_blocks), [nbk][nbj][nbi]
     // host-streamed compression: ring of device block buffers, a copy stream, and per buffer an event "copy done"
     // (recorded on the copy stream) and an event "buffer consumed" (recorded on the compute stream)
     static constexpr int kRing = 3;
@@ -172,11 +173,11 @@ int launch_v2_gen_f32(const Mode12Params &mp, const GenSplitParams &gs, int ks, 
     return boxed ? launch_v2_inst<float, NW, RT, SRC_GENERATED, 2, true>(mp, gs, nk, st) : launch_v2_inst<float, NW, RT, SRC_GENERATED, 2, false>(mp, gs, nk, st);
 }
 
-template <typename T, int NW, int RT, int SRC, int KS, bool BOXED, int DU, int DX, int WPS = (NW + 3) / 4, bool ZT = false>
+template <typename T, int NW, int RT, int SRC, int KS, bool BOXED, int DU, int DX, int WPS = (NW + 3) / 4, bool ZT = false, bool TAB = false>
 int launch_v3_inst(const Mode12Params &mp, const GenSplitParams &gs, const UFragParams &uf, int nk, hipStream_t st)
 {
     typedef Mode12V3Cfg<NW, RT> cfg;
-    auto kern = k_mode12_v3<T, NW, RT, SRC, KS, BOXED, DU, DX, WPS, ZT>;
+    auto kern = k_mode12_v3<T, NW, RT, SRC, KS, BOXED, DU, DX, WPS, ZT, TAB>;
     static bool attr_done = false;
     if (!attr_done) {
         if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, cfg::LDS_BYTES) != hipSuccess) return EXAT_ERR_HIP;
@@ -202,6 +203,13 @@ template <int NW, int RT>
 int launch_v3_mat_zt(const Mode12Params &mp, const GenSplitParams &gs, const UFragParams &uf, int nk, hipStream_t st)
 {
     return launch_v3_inst<float, NW, RT, SRC_MATERIALISED, 1, false, 2, 1, (NW + 3) / 4, true>(mp, gs, uf, nk, st);
+}
+
+// the same over a slab of separate blocks (Mode12Params::xtab)
+template <int NW, int RT>
+int launch_v3_mat_zt_tab(const Mode12Params &mp, const GenSplitParams &gs, const UFragParams &uf, int nk, hipStream_t st)
+{
+    return launch_v3_inst<float, NW, RT, SRC_MATERIALISED, 1, false, 2, 1, (NW + 3) / 4, true, true>(mp, gs, uf, nk, st);
 }
 
 // bf16 generated source, 4 waves
@@ -261,6 +269,7 @@ int run_chain(exat_plan_s *pl, Mode12Params mp, bool generated, float *Yout, int
     bool pipelined = env_int("EXAT_PIPELINED", 1) != 0;
     if (generated) pipelined = pipelined && mp.R <= 64;
     else pipelined = pipelined && mp.x_vec && (mp.i0 % ei == 0) && ((mp.i1 - mp.i0) % ei == 0);
+    if (mp.xtab && (!pipelined || generated || bf || pl->d.in_dtype != EXAT_F32)) return EXAT_ERR_STATE;   // only k_mode12_v3<float, ..., TAB> reads the block table
     int rt = choose_rt(pl, generated);
     if (pipelined) {
         // rt = 128-row units of the workgroup tile: 2 = 4 waves x 2 row tiles, 3 = 4 waves x 3, 4 = 8 waves x 2
@@ -319,6 +328,8 @@ int run_chain(exat_plan_s *pl, Mode12Params mp, bool generated, float *Yout, int
         uf.Uf = pl->Ufrag; uf.nig = pl->Ipad / (bf ? 16 : 8); uf.Vf = pl->Vfrag; uf.Vz = pl->Vfragz;
         if (!generated) {
             if (bf) rc = rt == 4 ? launch_v3_mat<__bf16, 8, 2>(mp, gs, uf, nk, st) : launch_v3_mat<__bf16, 4, 2>(mp, gs, uf, nk, st);
+            else if (mp.xtab)   // a slab of blocks: exat_compress_blocks has checked that this kernel applies
+                rc = rt == 4 ? launch_v3_mat_zt_tab<8, 2>(mp, gs, uf, nk, st) : launch_v3_mat_zt_tab<4, 2>(mp, gs, uf, nk, st);
             else if (pl->d.L % 32 == 0 && env_int("EXAT_ZT", 1))
                 rc = rt == 4 ? launch_v3_mat_zt<8, 2>(mp, gs, uf, nk, st) : launch_v3_mat_zt<4, 2>(mp, gs, uf, nk, st);
             else rc = rt == 4 ? launch_v3_mat<float, 8, 2>(mp, gs, uf, nk, st) : launch_v3_mat<float, 4, 2>(mp, gs, uf, nk, st);
@@ -396,6 +407,35 @@ __global__ void k_clear_flags(unsigned char *flags, int n)
     for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) flags[i] = 0;
 }
 
+// up to 32 entries of the block-pointer table per launch, carried in the kernel arguments
+struct PtrChunk { const void *p[32]; int64_t idx[32]; };
+__global__ void k_set_ptrs(const void **tab, PtrChunk c, int n)
+{
+    const int t = threadIdx.x;
+    if (t < n) tab[c.idx[t]] = c.p[t];
+}
+
+// the partial-result slots of the block-streamed calls, allocated at their first use with a plan
+int ensure_slots(exat_plan_s *pl, hipStream_t st)
+{
+    if (pl->slots) return EXAT_OK;
+    int64_t ns = kSlotBudgetBytes / (pl->ysize * 4);
+    if (ns < 1) ns = 1;
+    if (ns > pl->nblocks) ns = pl->nblocks;
+    if (ns > (1 << 20)) ns = 1 << 20;
+    if (hipMalloc((void **)&pl->slots, (size_t)ns * pl->ysize * 4) != hipSuccess || hipMalloc((void **)&pl->used_dev, (size_t)ns) != hipSuccess) {
+        (void)hipGetLastError();
+        (void)hipFree(pl->slots); (void)hipFree(pl->used_dev);
+        pl->slots = nullptr; pl->used_dev = nullptr;
+        return EXAT_ERR_ALLOC;
+    }
+    pl->nslots = (int)ns;
+    pl->submitted.assign((size_t)pl->nblocks, 0);
+    pl->slot_used.assign((size_t)ns, 0);
+    pl->nsubmitted = 0;
+    hipLaunchKernelGGL(k_clear_flags, dim3(grid_for(ns)), dim3(256), 0, st, pl->used_dev, (int)ns);
+    return hipGetLastError() == hipSuccess ? EXAT_OK : EXAT_ERR_HIP;
+}
 
 }  // namespace
 
@@ -460,7 +500,7 @@ int exat_plan_destroy(exat_plan_t pl)
     if (!pl) return EXAT_OK;
     (void)hipFree(pl->Upack); (void)hipFree(pl->Ufrag); (void)hipFree(pl->Vfrag); (void)hipFree(pl->Vfragz);
     (void)hipFree(pl->Ufh); (void)hipFree(pl->Ufl); (void)hipFree(pl->Vfh); (void)hipFree(pl->Vfl); (void)hipFree(pl->Vpack); (void)hipFree(pl->Wpack); (void)hipFree(pl->Q);
-    (void)hipFree(pl->slots); (void)hipFree(pl->used_dev); (void)hipFree(pl->Asplit);
+    (void)hipFree(pl->slots); (void)hipFree(pl->used_dev); (void)hipFree(pl->Asplit); (void)hipFree((void *)pl->xtab);
     for (auto &tr : pl->evr)
         for (hipEvent_t e : tr) if (e) (void)hipEventDestroy(e);
     delete pl;
@@ -541,23 +581,8 @@ int exat_compress_block(exat_plan_t pl, const void *Xblk, int32_t bi, int32_t bj
     const int64_t nbi = cdiv(d.I, d.dI), nbj = cdiv(d.J, d.dJ), nbk = cdiv(d.K, d.dK);
     if (bi < 0 || bj < 0 || bk < 0 || bi >= nbi || bj >= nbj || bk >= nbk) return EXAT_ERR_SHAPE;
     hipStream_t st = (hipStream_t)stream;
-    if (!pl->slots) {
-        int64_t ns = kSlotBudgetBytes / (pl->ysize * 4);
-        if (ns < 1) ns = 1;
-        if (ns > pl->nblocks) ns = pl->nblocks;
-        if (ns > (1 << 20)) ns = 1 << 20;
-        if (hipMalloc((void **)&pl->slots, (size_t)ns * pl->ysize * 4) != hipSuccess || hipMalloc((void **)&pl->used_dev, (size_t)ns) != hipSuccess) {
-            (void)hipGetLastError();
-            (void)hipFree(pl->slots); (void)hipFree(pl->used_dev);
-            pl->slots = nullptr; pl->used_dev = nullptr;
-            return EXAT_ERR_ALLOC;
-        }
-        pl->nslots = (int)ns;
-        pl->submitted.assign((size_t)pl->nblocks, 0);
-        pl->slot_used.assign((size_t)ns, 0);
-        pl->nsubmitted = 0;
-        hipLaunchKernelGGL(k_clear_flags, dim3(grid_for(ns)), dim3(256), 0, st, pl->used_dev, (int)ns);
-    }
+    const int rcs = ensure_slots(pl, st);
+    if (rcs != EXAT_OK) return rcs;
     const int64_t blk = bi + nbi * (bj + nbj * (int64_t)bk);
     if (pl->submitted[(size_t)blk]) return EXAT_ERR_STATE;
     const int slot = (int)(blk % pl->nslots);
@@ -576,6 +601,81 @@ int exat_compress_block(exat_plan_t pl, const void *Xblk, int32_t bi, int32_t bj
     pl->slot_used[(size_t)slot] = 1;
     pl->submitted[(size_t)blk] = 1;
     pl->nsubmitted++;
+    return EXAT_OK;
+}
+
+int exat_compress_blocks(exat_plan_t pl, const void *const *Xblk, int32_t bj0, int32_t bj1, int32_t bk0, int32_t bk1, void *stream)
+{
+    if (!pl || !Xblk) return EXAT_ERR_NULL;
+    if (!pl->factors_set) return EXAT_ERR_STATE;
+    const exat_desc_t &d = pl->d;
+    const int64_t nbi = cdiv(d.I, d.dI), nbj = cdiv(d.J, d.dJ), nbk = cdiv(d.K, d.dK);
+    if (bj0 < 0 || bk0 < 0 || bj0 >= bj1 || bk0 >= bk1 || bj1 > nbj || bk1 > nbk) return EXAT_ERR_SHAPE;
+    const int64_t n = nbi * (bj1 - bj0) * (int64_t)(bk1 - bk0);
+    for (int64_t q = 0; q < n; q++)
+        if (!Xblk[q]) return EXAT_ERR_NULL;
+    hipStream_t st = (hipStream_t)stream;
+    const int rcs = ensure_slots(pl, st);
+    if (rcs != EXAT_OK) return rcs;
+    for (int64_t bk = bk0; bk < bk1; bk++)
+        for (int64_t bj = bj0; bj < bj1; bj++)
+            for (int64_t bi = 0; bi < nbi; bi++)
+                if (pl->submitted[(size_t)(bi + nbi * (bj + nbj * bk))]) return EXAT_ERR_STATE;
+    // One launch over the slab needs the kernel that reads X through a table of block pointers: fp32 plans with
+    // L a multiple of 32, whole 16-value stages of i and whole 128-fibre chunks inside every block, 16-byte aligned
+    // blocks.  Any other slab is compressed block by block.
+    bool one_launch = d.in_dtype == EXAT_F32 && d.L % 32 == 0 && d.I % d.dI == 0 && d.dI % 16 == 0 && d.dJ % 128 == 0 &&
+                      env_int("EXAT_PIPELINED", 1) != 0 && env_int("EXAT_ZT", 1) != 0 && env_int("EXAT_SLAB", 1) != 0;
+    for (int64_t q = 0; q < n && one_launch; q++)
+        if ((uintptr_t)Xblk[q] & 15) one_launch = false;
+    if (!one_launch) {
+        int64_t q = 0;
+        for (int64_t bk = bk0; bk < bk1; bk++)
+            for (int64_t bj = bj0; bj < bj1; bj++)
+                for (int64_t bi = 0; bi < nbi; bi++, q++) {
+                    const int rc = exat_compress_block(pl, Xblk[q], (int32_t)bi, (int32_t)bj, (int32_t)bk, stream);
+                    if (rc != EXAT_OK) return rc;
+                }
+        return EXAT_OK;
+    }
+    if (!pl->xtab) {
+        if (pl->nblocks > (1LL << 24)) return EXAT_ERR_SHAPE;
+        if (hipMalloc((void **)&pl->xtab, (size_t)pl->nblocks * sizeof(void *)) != hipSuccess) { (void)hipGetLastError(); pl->xtab = nullptr; return EXAT_ERR_ALLOC; }
+    }
+    // the slab's entries of the table (the kernel indexes it by global block coordinates)
+    {
+        PtrChunk c;
+        int m = 0;
+        int64_t q = 0;
+        for (int64_t bk = bk0; bk < bk1; bk++)
+            for (int64_t bj = bj0; bj < bj1; bj++)
+                for (int64_t bi = 0; bi < nbi; bi++, q++) {
+                    c.p[m] = Xblk[q]; c.idx[m] = bi + nbi * (bj + nbj * bk);
+                    if (++m == 32 || q == n - 1) {
+                        hipLaunchKernelGGL(k_set_ptrs, dim3(1), dim3(64), 0, st, pl->xtab, c, m);
+                        m = 0;
+                    }
+                }
+        if (hipGetLastError() != hipSuccess) return EXAT_ERR_HIP;
+    }
+    Mode12Params mp;
+    memset(&mp, 0, sizeof(mp));
+    mp.xtab = pl->xtab; mp.x_dI = d.dI; mp.x_dJ = d.dJ; mp.x_dK = d.dK; mp.tab_nbi = (int)nbi; mp.tab_nbj = (int)nbj;
+    mp.x_vec = 1;
+    mp.i0 = 0; mp.i1 = d.I;
+    mp.j0 = (int64_t)bj0 * d.dJ; mp.j1 = std::min<int64_t>(d.J, (int64_t)bj1 * d.dJ);
+    mp.k0 = (int64_t)bk0 * d.dK; mp.k1 = std::min<int64_t>(d.K, (int64_t)bk1 * d.dK);
+    // the slab's partial result goes to the slot of its first block
+    const int64_t first = nbi * (bj0 + nbj * (int64_t)bk0);
+    const int slot = (int)(first % pl->nslots);
+    const int rc = run_chain(pl, mp, false, pl->slots + (int64_t)slot * pl->ysize, pl->slot_used[(size_t)slot] ? 1 : 0, st,
+                             pl->slot_used[(size_t)slot] ? nullptr : pl->used_dev + slot);
+    if (rc != EXAT_OK) return rc;
+    pl->slot_used[(size_t)slot] = 1;
+    for (int64_t bk = bk0; bk < bk1; bk++)
+        for (int64_t bj = bj0; bj < bj1; bj++)
+            for (int64_t bi = 0; bi < nbi; bi++) pl->submitted[(size_t)(bi + nbi * (bj + nbj * bk))] = 1;
+    pl->nsubmitted += n;
     return EXAT_OK;
 }
 

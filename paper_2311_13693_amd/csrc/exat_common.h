@@ -13,6 +13,11 @@ struct Mode12Params {
     const void *X;
     int64_t x_sj, x_sk, xo_i, xo_j, xo_k;
     int x_vec;  // 16-byte loads of X are aligned
+    // materialised source held as separate blocks (k_mode12_v3 with TAB): xtab[bi + tab_nbi*(bj + tab_nbj*bk)] is the
+    // column-major x_dI x dj x dk block (bi, bj, bk) of X (dj, dk shorter in the last block of an axis); X is unused
+    const void *const *xtab;
+    int64_t x_dI, x_dJ, x_dK;
+    int tab_nbi, tab_nbj;
     // generated source
     const float *A, *B, *C;
     int64_t ldA, ldB, ldC;

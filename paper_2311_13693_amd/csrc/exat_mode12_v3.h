@@ -88,7 +88,10 @@ constexpr int lcm_i(int a, int b) { return a / gcd_i(a, b) * b; }
 // so that one's chunk set-up and mode-2 phases run under the other's MFMA phase).
 // ZT: mode 1 with the MFMA operands swapped (accumulators hold Z^T) and mode 2 straight from the accumulators
 // (mode2_direct; fp32 materialised source, L % 32 == 0).
-template <typename T, int NW, int RT, int SRC, int KS, bool BOXED, int DU = 2, int DX = 1, int WPS = (NW + 3) / 4, bool ZT = false>
+// TAB: the materialised X is a set of separate blocks addressed through Mode12Params::xtab (a slab of streamed blocks
+// compressed in one launch: the box covers the whole i extent, its j and k ranges are whole blocks); needs whole stages
+// of i and whole 128-fibre chunks inside every block.
+template <typename T, int NW, int RT, int SRC, int KS, bool BOXED, int DU = 2, int DX = 1, int WPS = (NW + 3) / 4, bool ZT = false, bool TAB = false>
 __global__ __launch_bounds__(64 * NW, WPS) void k_mode12_v3(const Mode12Params p, const GenSplitParams gs, const UFragParams uf)
 {
     typedef Mode12V3Cfg<NW, RT> cfg;
@@ -167,7 +170,19 @@ __global__ __launch_bounds__(64 * NW, WPS) void k_mode12_v3(const Mode12Params p
         // ---- per-chunk set-up ----
         int64_t x_off[XPT];
         bool x_ok[XPT];
-        if constexpr (SRC == SRC_MATERIALISED) {
+        const void *const *tabrow = nullptr;   // TAB: the block pointers of this chunk's column, indexed by bi
+        if constexpr (SRC == SRC_MATERIALISED && TAB) {
+            // the chunk lies inside block column (bj, bk): offsets are relative to the start of a block of that column
+            const int64_t bj = jc / p.x_dJ, bk = k / p.x_dK;
+            const int64_t jb0 = bj * p.x_dJ, djb = (p.j1 - jb0 < p.x_dJ) ? p.j1 - jb0 : p.x_dJ;
+            tabrow = p.xtab + (bk * p.tab_nbj + bj) * p.tab_nbi;
+#pragma unroll
+            for (int u = 0; u < XPT; u++) {
+                const int64_t j = jc + pr0 + PSTEP * u;
+                x_ok[u] = (j >= p.j0) && (j < p.j1);
+                x_off[u] = pf * E16 + (j - jb0) * p.x_dI + (k - bk * p.x_dK) * p.x_dI * djb;
+            }
+        } else if constexpr (SRC == SRC_MATERIALISED) {
 #pragma unroll
             for (int u = 0; u < XPT; u++) {
                 const int64_t j = jc + pr0 + PSTEP * u;
@@ -206,15 +221,31 @@ __global__ __launch_bounds__(64 * NW, WPS) void k_mode12_v3(const Mode12Params p
         auto load_uf = [&](int rt, int64_t ig) -> frag_t {
             return *((const frag_t *)(ufl + rt * u_rt_step + ig * (64 * E16)));
         };
+        // TAB: start of stage s inside its block (block bi of the chunk's column).  The pointer is read from the table a
+        // whole stage before the loads that use it are issued, behind the loads of the stage before.
+        const T *tab_next = nullptr;
+        auto tab_fetch = [&](int s) {
+            if constexpr (TAB) {
+                const int ii = (int)stage_i(s), bi = ii / (int)p.x_dI;
+                tab_next = (const T *)tabrow[bi] + (ii - bi * (int)p.x_dI);
+            }
+        };
+        if constexpr (TAB) {
+            static_assert(!TAB || DX == 1, "TAB: one register set of X");
+            tab_fetch(have_next ? 1 : 0);   // the first load of the prologue: stage 0, or stage 1 when tile 0 was prefetched
+        }
         auto load_x = [&](int s, u32x4 *slot) {
             if constexpr (SRC == SRC_MATERIALISED) {
-                const T *xb = (const T *)p.X + stage_i(s);
+                const T *xb;
+                if constexpr (TAB) xb = tab_next;   // fetched behind the previous call's loads
+                else xb = (const T *)p.X + stage_i(s);
 #pragma unroll
                 for (int u = 0; u < XPT; u++) {
                     u32x4 v = {0u, 0u, 0u, 0u};
                     if (x_ok[u]) v = *(const u32x4 *)(xb + x_off[u]);
                     slot[u] = v;
                 }
+                if constexpr (TAB) tab_fetch(s + 1);   // the calls come in the order of the stages
             }
         };
         auto load_a = [&](int s, bf16x8 *af) {
@@ -486,6 +517,18 @@ __global__ __launch_bounds__(64 * NW, WPS) void k_mode12_v3(const Mode12Params p
         if constexpr (SRC == SRC_MATERIALISED) {
             have_next = jc + COLS < p.j1;
             if (have_next) {
+                if constexpr (TAB) {
+                    const int64_t jn = jc + COLS, bj = jn / p.x_dJ, bk = k / p.x_dK;
+                    const int64_t jb0 = bj * p.x_dJ, djb = (p.j1 - jb0 < p.x_dJ) ? p.j1 - jb0 : p.x_dJ;
+                    const T *xb = (const T *)p.xtab[(bk * p.tab_nbj + bj) * p.tab_nbi];   // block bi = 0 of the next chunk's column
+#pragma unroll
+                    for (int u = 0; u < XPT; u++) {
+                        const int64_t j = jn + pr0 + PSTEP * u;
+                        u32x4 v = {0u, 0u, 0u, 0u};
+                        if (j >= p.j0 && j < p.j1) v = *(const u32x4 *)(xb + pf * E16 + (j - jb0) * p.x_dI + (k - bk * p.x_dK) * p.x_dI * djb);
+                        xnext[u] = v;
+                    }
+                } else {
                 const T *xb = (const T *)p.X + stage_i(0);
 #pragma unroll
                 for (int u = 0; u < XPT; u++) {
@@ -493,6 +536,7 @@ __global__ __launch_bounds__(64 * NW, WPS) void k_mode12_v3(const Mode12Params p
                     u32x4 v = {0u, 0u, 0u, 0u};
                     if (j >= p.j0 && j < p.j1) v = *(const u32x4 *)(xb + (pf * E16 - p.xo_i) + (j - p.xo_j) * p.x_sj + (k - p.xo_k) * p.x_sk);
                     xnext[u] = v;
+                }
                 }
             }
         }

@@ -14,7 +14,7 @@ EXAT_F32, EXAT_BF16, EXAT_F32_SPLIT = 0, 1, 2
 OK, ERR_NULL, ERR_SHAPE, ERR_DTYPE, ERR_STATE, ERR_ALLOC, ERR_HIP = 0, -1, -2, -3, -4, -5, -6
 
 EXPORTS = ["exat_plan_create", "exat_plan_destroy", "exat_set_factors", "exat_compress",
-           "exat_compress_block", "exat_finalize", "exat_compress_host", "exat_compress_gen", "exat_gen_block",
+           "exat_compress_block", "exat_compress_blocks", "exat_finalize", "exat_compress_host", "exat_compress_gen", "exat_gen_block",
            "exat_plan_set_timing", "exat_plan_last_timing", "exat_plan_timing_of",
            "exat_stage1_create", "exat_stage1_destroy", "exat_stage1_dims", "exat_stage1_apply", "exat_stage1_apply_host",
            "exat_stage1_set_timing", "exat_stage1_last_timing", "exat_cpals_workspace_floats", "exat_cpals",
@@ -72,6 +72,7 @@ def lib():
         L.exat_set_factors.argtypes = [vp, vp, i64, vp, i64, vp, i64, vp]
         L.exat_compress.argtypes = [vp, vp, vp, vp]
         L.exat_compress_block.argtypes = [vp, vp, i32, i32, i32, vp]
+        L.exat_compress_blocks.argtypes = [vp, ctypes.POINTER(vp), i32, i32, i32, i32, vp]
         L.exat_finalize.argtypes = [vp, vp, vp]
         L.exat_compress_host.argtypes = [vp, vp, vp, vp]
         L.exat_compress_gen.argtypes = [vp, ctypes.POINTER(Gen), ctypes.POINTER(Box), vp, vp]
@@ -201,6 +202,11 @@ class Plan:
 
     def compress_block(self, Xblk, bi, bj, bk, stream=None):
         _check(lib().exat_compress_block(self._h, _ptr(Xblk), bi, bj, bk, _stream_handle(stream)))
+
+    def compress_blocks(self, blocks, bj0, bj1, bk0, bk1, stream=None):
+        """blocks: device tensors of the slab's blocks, bi fastest, then bj, then bk (whole block columns along i)."""
+        arr = (ctypes.c_void_p * len(blocks))(*[b.data_ptr() for b in blocks])
+        _check(lib().exat_compress_blocks(self._h, arr, bj0, bj1, bk0, bk1, _stream_handle(stream)))
 
     def finalize(self, Y=None, stream=None):
         Y = self.new_y() if Y is None else Y

@@ -76,8 +76,15 @@ def test_cfg2_full_parity_materialised_generated_and_block_streamed():
                 blk = Xv[bk * d:(bk + 1) * d, bj * d:(bj + 1) * d, bi * d:(bi + 1) * d].contiguous()
                 plan.compress_block(blk, bi, bj, bk)
     e3 = oracle.rel_fro(gu.y_to_numpy(plan.finalize(), cfg), Yo)
-    _say("  cfg2 rel_fro: materialised %.3e, generated on chip %.3e, block-streamed %.3e" % (e1, e2, e3))
-    assert max(e1, e2, e3) <= TOL["f32"]
+    # the same blocks in slabs of two block layers along k (32 blocks resident per call), as bench.py --blocks times them
+    nb = cfg.I // d
+    for bk0 in range(0, cfg.K // d, 2):
+        slab = [Xv[bk * d:(bk + 1) * d, bj * d:(bj + 1) * d, bi * d:(bi + 1) * d].contiguous()
+                for bk in range(bk0, bk0 + 2) for bj in range(cfg.J // d) for bi in range(nb)]
+        plan.compress_blocks(slab, 0, cfg.J // d, bk0, bk0 + 2)
+    e3s = oracle.rel_fro(gu.y_to_numpy(plan.finalize(), cfg), Yo)
+    _say("  cfg2 rel_fro: materialised %.3e, generated on chip %.3e, block-streamed %.3e, in slabs %.3e" % (e1, e2, e3, e3s))
+    assert max(e1, e2, e3, e3s) <= TOL["f32"]
     plan.close()
     # the same tensor through the fp16 matrix cores with two-piece operands: same tolerance
     from dataclasses import replace
