@@ -179,13 +179,17 @@ int launch_v3_inst(const Mode12Params &mp, const GenSplitParams &gs, const UFrag
     typedef Mode12V3Cfg<NW, RT> cfg;
     auto kern = k_mode12_v3<T, NW, RT, SRC, KS, BOXED, DU, DX, WPS, ZT, TAB>;
     static bool attr_done = false;
+    constexpr int lds_max = ZT ? cfg::zt_lds_bytes(2) : cfg::LDS_BYTES;
+    static_assert(lds_max <= 160 * 1024, "LDS of a compute unit");
     if (!attr_done) {
-        if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, cfg::LDS_BYTES) != hipSuccess) return EXAT_ERR_HIP;
+        if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds_max) != hipSuccess) return EXAT_ERR_HIP;
         attr_done = true;
     }
     const int64_t grid = 8LL * ((nk + 7) / 8) * mp.G;
     if (grid > 2147483647LL) return EXAT_ERR_SHAPE;
-    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(64 * NW), cfg::LDS_BYTES, st, mp, gs, uf);
+    if (ZT && (mp.MT < 1 || mp.MT > 2)) return EXAT_ERR_SHAPE;
+    const int lds = ZT ? cfg::zt_lds_bytes(mp.MT) : cfg::LDS_BYTES;
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(64 * NW), lds, st, mp, gs, uf);
     return hipGetLastError() == hipSuccess ? EXAT_OK : EXAT_ERR_HIP;
 }
 

@@ -43,6 +43,8 @@ struct Mode12V3Cfg {
     static constexpr int ZST = COLS + 4;
     static constexpr int EPI_BYTES = NW * 32 * ZST * 4;
     static constexpr int LDS_BYTES = 2 * XBUF_BYTES > EPI_BYTES ? 2 * XBUF_BYTES : EPI_BYTES;
+    // kernels that take mode 2 straight from the accumulators (ZT): the two X buffers and the running sums of Q
+    static constexpr int zt_lds_bytes(int MT) { return 2 * XBUF_BYTES + NW * RT * MT * 4 * 64 * 16; }
 };
 
 template <typename T> struct gen_terms;
@@ -545,8 +547,11 @@ __global__ __launch_bounds__(64 * NW, WPS) void k_mode12_v3(const Mode12Params p
         const bool first_chunk = (jc == ja0);
         if constexpr (ZT) {
             static_assert(!ZT || sizeof(T) == 4, "ZT: fp32 only");
-            if (p.MT == 2) mode2_direct<RT, CT, 2>(p, p.Vd, acc, wrow0, kidx, jc, first_chunk, tid & 63);
-            else mode2_direct<RT, CT, 1>(p, p.Vd, acc, wrow0, kidx, jc, first_chunk, tid & 63);
+            // running sums of Q: behind the two X buffers, RT * MT * 4 KiB per wave (Mode12V3Cfg::zt_lds_bytes)
+            f32x4 *qlds = (f32x4 *)(smem + 2 * XBUF) + wave * (RT * p.MT * 4 * 64);
+            const bool last_chunk = jc + COLS >= p.j1;
+            if (p.MT == 2) mode2_direct<RT, CT, 2>(p, p.Vd, acc, wrow0, kidx, jc, first_chunk, last_chunk, qlds, tid & 63);
+            else mode2_direct<RT, CT, 1>(p, p.Vd, acc, wrow0, kidx, jc, first_chunk, last_chunk, qlds, tid & 63);
         } else if (p.MT == 2) mode2_chunk<RT, CT, 2, sizeof(T) == 2 ? VM_BF16 : VM_F32>(p, uf.Vf, Zs, acc, wrow0, kidx, jc, first_chunk, tid & 63);
         else mode2_chunk<RT, CT, 1, sizeof(T) == 2 ? VM_BF16 : VM_F32>(p, uf.Vf, Zs, acc, wrow0, kidx, jc, first_chunk, tid & 63);
     }

@@ -183,9 +183,12 @@ __device__ __forceinline__ void mode2_chunk(const Mode12Params &p, const void *V
 // The RT * MTC output tiles are taken one after the other in steps of one column tile ct (16 MFMAs); the V
 // fragments of a step are requested three steps ahead (a ring of four register sets), so that after the first
 // step the requests are always in flight behind the matrix instructions, also across the stores of a finished tile.
+// Q between the chunks: the rows a wave adds to are its own for the whole launch, so the running sums stay in a
+// wave-private piece of LDS (qlds: RT * MTC * 4 pieces of 64 lanes x 16 bytes, each lane reading back exactly what it
+// wrote: no bank conflicts, no barrier) and only the last chunk's result goes to memory; Q is written once and never read.
 template <int RT, int CT, int MTC>
 __device__ __forceinline__ void mode2_direct(const Mode12Params &p, const float *Vd, const f32x16 (&acc)[RT][CT], int wrow0, int kidx,
-                                             int64_t jc, bool first_chunk, int lane)
+                                             int64_t jc, bool first_chunk, bool last_chunk, f32x4 *qlds, int lane)
 {
     constexpr int MP = 32 * MTC;   // = p.Mpad
     constexpr int NS = RT * MTC * CT, AHEAD = 3;
@@ -216,7 +219,7 @@ __device__ __forceinline__ void mode2_direct(const Mode12Params &p, const float 
         if (s + AHEAD < NS) load_step(s + AHEAD);
         if (ct == 0 && q0 < p.PL) {
 #pragma unroll
-            for (int b = 0; b < 4; b++) qold[b] = first_chunk ? f32x4{0.0f, 0.0f, 0.0f, 0.0f} : *(const f32x4 *)(Qt + 8 * b);
+            for (int b = 0; b < 4; b++) qold[b] = first_chunk ? f32x4{0.0f, 0.0f, 0.0f, 0.0f} : qlds[(((rt * MTC + mt) * 4) + b) * 64 + lane];
 #pragma unroll
             for (int e = 0; e < 16; e++) d[e] = 0.0f;
         }
@@ -234,7 +237,8 @@ __device__ __forceinline__ void mode2_direct(const Mode12Params &p, const float 
                     f32x4 o;
 #pragma unroll
                     for (int r = 0; r < 4; r++) o[r] = d[4 * b + r] + qold[b][r];
-                    *(f32x4 *)(Qt + 8 * b) = o;
+                    if (last_chunk) *(f32x4 *)(Qt + 8 * b) = o;
+                    else qlds[(((rt * MTC + mt) * 4) + b) * 64 + lane] = o;
                 }
             }
         }
