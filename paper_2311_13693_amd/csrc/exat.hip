@@ -195,11 +195,11 @@ int launch_v3_inst(const Mode12Params &mp, const GenSplitParams &gs, const UFrag
 
 // materialised source: fp32 stages are long (fp32 MFMA), two register sets suffice; bf16 stages are 16 times
 // shorter and want the tiles requested further ahead
-template <typename T, int NW, int RT>
+template <typename T, int NW, int RT, bool TAB = false>
 int launch_v3_mat(const Mode12Params &mp, const GenSplitParams &gs, const UFragParams &uf, int nk, hipStream_t st)
 {
     constexpr int D = sizeof(T) == 2 ? 3 : 2, DXV = sizeof(T) == 2 ? 3 : 1;
-    return launch_v3_inst<T, NW, RT, SRC_MATERIALISED, 1, false, D, DXV>(mp, gs, uf, nk, st);
+    return launch_v3_inst<T, NW, RT, SRC_MATERIALISED, 1, false, D, DXV, (NW + 3) / 4, false, TAB>(mp, gs, uf, nk, st);
 }
 
 // fp32 materialised source with mode 2 straight from the (transposed) accumulators; needs L % 32 == 0
@@ -273,7 +273,7 @@ int run_chain(exat_plan_s *pl, Mode12Params mp, bool generated, float *Yout, int
     bool pipelined = env_int("EXAT_PIPELINED", 1) != 0;
     if (generated) pipelined = pipelined && mp.R <= 64;
     else pipelined = pipelined && mp.x_vec && (mp.i0 % ei == 0) && ((mp.i1 - mp.i0) % ei == 0);
-    if (mp.xtab && (!pipelined || generated || bf || pl->d.in_dtype != EXAT_F32)) return EXAT_ERR_STATE;   // only k_mode12_v3<float, ..., TAB> reads the block table
+    if (mp.xtab && (!pipelined || generated || pl->d.in_dtype == EXAT_F32_SPLIT)) return EXAT_ERR_STATE;   // only k_mode12_v3<..., TAB> reads the block table
     int rt = choose_rt(pl, generated);
     if (pipelined) {
         // rt = 128-row units of the workgroup tile: 2 = 4 waves x 2 row tiles, 3 = 4 waves x 3, 4 = 8 waves x 2
@@ -331,9 +331,12 @@ int run_chain(exat_plan_s *pl, Mode12Params mp, bool generated, float *Yout, int
         UFragParams uf;
         uf.Uf = pl->Ufrag; uf.nig = pl->Ipad / (bf ? 16 : 8); uf.Vf = pl->Vfrag; uf.Vz = pl->Vfragz;
         if (!generated) {
-            if (bf) rc = rt == 4 ? launch_v3_mat<__bf16, 8, 2>(mp, gs, uf, nk, st) : launch_v3_mat<__bf16, 4, 2>(mp, gs, uf, nk, st);
-            else if (mp.xtab)   // a slab of blocks: exat_compress_blocks has checked that this kernel applies
-                rc = rt == 4 ? launch_v3_mat_zt_tab<8, 2>(mp, gs, uf, nk, st) : launch_v3_mat_zt_tab<4, 2>(mp, gs, uf, nk, st);
+            if (mp.xtab) {   // a slab of blocks (exat_compress_blocks has checked that these kernels apply)
+                if (bf) rc = rt == 4 ? launch_v3_mat<__bf16, 8, 2, true>(mp, gs, uf, nk, st) : launch_v3_mat<__bf16, 4, 2, true>(mp, gs, uf, nk, st);
+                else if (pl->d.L % 32 == 0 && env_int("EXAT_ZT", 1))
+                    rc = rt == 4 ? launch_v3_mat_zt_tab<8, 2>(mp, gs, uf, nk, st) : launch_v3_mat_zt_tab<4, 2>(mp, gs, uf, nk, st);
+                else rc = rt == 4 ? launch_v3_mat<float, 8, 2, true>(mp, gs, uf, nk, st) : launch_v3_mat<float, 4, 2, true>(mp, gs, uf, nk, st);
+            } else if (bf) rc = rt == 4 ? launch_v3_mat<__bf16, 8, 2>(mp, gs, uf, nk, st) : launch_v3_mat<__bf16, 4, 2>(mp, gs, uf, nk, st);
             else if (pl->d.L % 32 == 0 && env_int("EXAT_ZT", 1))
                 rc = rt == 4 ? launch_v3_mat_zt<8, 2>(mp, gs, uf, nk, st) : launch_v3_mat_zt<4, 2>(mp, gs, uf, nk, st);
             else rc = rt == 4 ? launch_v3_mat<float, 8, 2>(mp, gs, uf, nk, st) : launch_v3_mat<float, 4, 2>(mp, gs, uf, nk, st);
@@ -625,11 +628,12 @@ int exat_compress_blocks(exat_plan_t pl, const void *const *Xblk, int32_t bj0, i
         for (int64_t bj = bj0; bj < bj1; bj++)
             for (int64_t bi = 0; bi < nbi; bi++)
                 if (pl->submitted[(size_t)(bi + nbi * (bj + nbj * bk))]) return EXAT_ERR_STATE;
-    // One launch over the slab needs the kernel that reads X through a table of block pointers: fp32 plans with
-    // L a multiple of 32, whole 16-value stages of i and whole 128-fibre chunks inside every block, 16-byte aligned
+    // One launch over the slab needs the kernels that read X through a table of block pointers: fp32 or bf16 plans,
+    // whole stages of i (16 fp32 / 32 bf16 values) and whole 128-fibre chunks inside every block, 16-byte aligned
     // blocks.  Any other slab is compressed block by block.
-    bool one_launch = d.in_dtype == EXAT_F32 && d.L % 32 == 0 && d.I % d.dI == 0 && d.dI % 16 == 0 && d.dJ % 128 == 0 &&
-                      env_int("EXAT_PIPELINED", 1) != 0 && env_int("EXAT_ZT", 1) != 0 && env_int("EXAT_SLAB", 1) != 0;
+    const int ei = d.in_dtype == EXAT_BF16 ? 32 : 16;
+    bool one_launch = (d.in_dtype == EXAT_F32 || d.in_dtype == EXAT_BF16) && d.I % d.dI == 0 && d.dI % ei == 0 && d.dJ % 128 == 0 &&
+                      env_int("EXAT_PIPELINED", 1) != 0 && env_int("EXAT_SLAB", 1) != 0;
     for (int64_t q = 0; q < n && one_launch; q++)
         if ((uintptr_t)Xblk[q] & 15) one_launch = false;
     if (!one_launch) {

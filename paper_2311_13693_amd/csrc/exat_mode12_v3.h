@@ -225,6 +225,8 @@ __global__ __launch_bounds__(64 * NW, WPS) void k_mode12_v3(const Mode12Params p
         };
         // TAB: start of stage s inside its block (block bi of the chunk's column).  The pointer is read from the table a
         // whole stage before the loads that use it are issued, behind the loads of the stage before.
+        // a pointer that came out of the table is a pointer to device memory: say so, or every load through it is a flat load
+        auto gptr = [](const T *q) { return (const __attribute__((address_space(1))) u32x4 *)(uintptr_t)q; };
         const T *tab_next = nullptr;
         auto tab_fetch = [&](int s) {
             if constexpr (TAB) {
@@ -233,7 +235,6 @@ __global__ __launch_bounds__(64 * NW, WPS) void k_mode12_v3(const Mode12Params p
             }
         };
         if constexpr (TAB) {
-            static_assert(!TAB || DX == 1, "TAB: one register set of X");
             tab_fetch(have_next ? 1 : 0);   // the first load of the prologue: stage 0, or stage 1 when tile 0 was prefetched
         }
         auto load_x = [&](int s, u32x4 *slot) {
@@ -244,7 +245,7 @@ __global__ __launch_bounds__(64 * NW, WPS) void k_mode12_v3(const Mode12Params p
 #pragma unroll
                 for (int u = 0; u < XPT; u++) {
                     u32x4 v = {0u, 0u, 0u, 0u};
-                    if (x_ok[u]) v = *(const u32x4 *)(xb + x_off[u]);
+                    if (x_ok[u]) v = *gptr(xb + x_off[u]);
                     slot[u] = v;
                 }
                 if constexpr (TAB) tab_fetch(s + 1);   // the calls come in the order of the stages
@@ -527,7 +528,7 @@ __global__ __launch_bounds__(64 * NW, WPS) void k_mode12_v3(const Mode12Params p
                     for (int u = 0; u < XPT; u++) {
                         const int64_t j = jn + pr0 + PSTEP * u;
                         u32x4 v = {0u, 0u, 0u, 0u};
-                        if (j >= p.j0 && j < p.j1) v = *(const u32x4 *)(xb + pf * E16 + (j - jb0) * p.x_dI + (k - bk * p.x_dK) * p.x_dI * djb);
+                        if (j >= p.j0 && j < p.j1) v = *gptr(xb + pf * E16 + (j - jb0) * p.x_dI + (k - bk * p.x_dK) * p.x_dI * djb);
                         xnext[u] = v;
                     }
                 } else {

@@ -45,18 +45,22 @@ def _nb(n, d):
 
 
 def _block(X, cfg, bi, bj, bk):
-    return gu.to_dev_x(np.asfortranarray(X[bi * cfg.dI:(bi + 1) * cfg.dI, bj * cfg.dJ:(bj + 1) * cfg.dJ, bk * cfg.dK:(bk + 1) * cfg.dK]))
+    return gu.to_dev_x(np.asfortranarray(X[bi * cfg.dI:(bi + 1) * cfg.dI, bj * cfg.dJ:(bj + 1) * cfg.dJ, bk * cfg.dK:(bk + 1) * cfg.dK]),
+                       bf16=cfg.dtype == "bf16")
 
 
 def _slab(X, cfg, bj0, bj1, bk0, bk1):
     return [_block(X, cfg, bi, bj, bk) for bk in range(bk0, bk1) for bj in range(bj0, bj1) for bi in range(_nb(cfg.I, cfg.dI))]
 
 
-# shapes the one-launch kernel takes (L % 32 == 0, dI % 16 == 0 dividing I, dJ % 128 == 0); ragged last blocks along j and k
+# shapes the one-launch kernels take (dI a multiple of the stage, 16 fp32 / 32 bf16 values, that divides I; dJ % 128 == 0);
+# ragged last blocks along j and k; mode 2 from the accumulators (L % 32 == 0) and through LDS; fp32 and bf16 plans
 CASES = {
     "two_by_two_by_two": dict(I=64, J=256, K=6, R=4, P=3, L=32, M=8, N=5, dI=32, dJ=128, dK=3),
     "ragged_j_and_k": dict(I=96, J=300, K=7, R=3, P=2, L=32, M=33, N=4, dI=32, dJ=128, dK=3),
     "two_row_groups_l64": dict(I=48, J=128, K=5, R=5, P=10, L=64, M=20, N=3, dI=16, dJ=128, dK=2),
+    "l50_mode2_through_lds": dict(I=64, J=200, K=5, R=4, P=7, L=50, M=50, N=6, dI=16, dJ=128, dK=3),
+    "bf16": dict(I=128, J=300, K=5, R=4, P=7, L=50, M=50, N=6, dI=64, dJ=128, dK=2, dtype="bf16"),
 }
 
 
@@ -67,12 +71,16 @@ def test_slabs_match_oracle_one_shot_and_any_order(name, rt):
         os.environ["EXAT_RT"] = rt
     cfg = wl.small(name=name, index=700 + list(CASES).index(name), **CASES[name])
     A, B, C, U, V, W = _inputs(cfg)
-    X = oracle.gen_box(A, B, C, cfg.seed, cfg.sigma)
-    Yo = oracle.comp_multi(X, U, V, W, cfg.P)
+    bf = cfg.dtype == "bf16"
+    # bf16 plans: a tensor that is exactly representable in bf16, against the oracle on bf16-rounded matrices (what
+    # isolates the kernel from the quantisation of its inputs)
+    X = oracle.gen_box(A, B, C, cfg.seed, cfg.sigma, to_bf16=bf)
+    rb = oracle.round_bf16 if bf else (lambda a: a)
+    Yo = oracle.comp_multi(X, rb(U), rb(V), rb(W), cfg.P)
     plan = gu.plan_with_factors(cfg, U, V, W)
     nbj, nbk = _nb(cfg.J, cfg.dJ), _nb(cfg.K, cfg.dK)
     # one slab that holds every block: the same launches as the one-shot call, so the same bits
-    y_one = plan.compress(gu.to_dev_x(X)).clone()
+    y_one = plan.compress(gu.to_dev_x(X, bf16=bf)).clone()
     plan.compress_blocks(_slab(X, cfg, 0, nbj, 0, nbk), 0, nbj, 0, nbk)
     y_all = plan.finalize().clone()
     assert torch.equal(y_one, y_all)
