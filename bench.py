@@ -58,6 +58,9 @@ def parse():
     ap.add_argument("--slab", type=int, default=0,
                     help="with --blocks: compress the blocks in slabs of this many block layers along k per call "
                          "(exat_compress_blocks; all blocks of a slab resident at once) instead of one call per block")
+    ap.add_argument("--mfma-ceiling", action="store_true",
+                    help="measure what the matrix cores of this GPU sustain when a kernel issues nothing but MFMAs "
+                         "(exat_probe_mfma: bf16 32x32x16 and fp32 32x32x2, constant and random operands) and print it")
     ap.add_argument("--split", action="store_true",
                     help="fp32 materialised configurations only: run the contractions on the fp16 matrix cores with "
                          "two-piece operands (EXAT_F32_SPLIT) instead of fp32 MFMA; reported against the fp16 MFMA peak")
@@ -74,6 +77,22 @@ def parse():
                          "configuration's own stacked compression matrices (needs P*L >= 1.5 I: cfg3); value then counts "
                          "matrix elements streamed per second (two passes over the stacked matrix per iteration)")
     return ap.parse_args()
+
+
+def mfma_ceiling(args):
+    """The MFMA-only rate of this machine: the ceiling of any kernel here, next to the published peak."""
+    import torch
+    from paper_2311_13693_amd import exat
+    torch.cuda.set_device(0)
+    torch.zeros(1, device="cuda")            # the device is initialised through torch, as everywhere in this file
+    out = {"metric": "MFMA-only rate of this GPU (measurement aid: no compression work)", "unit": "TFLOP/s", "n_gpus": 1,
+           "workgroups": 256, "waves_per_workgroup": 8, "rates": {}}
+    # about 100 ms per launch: 64 MFMAs per iteration and wave, two waves per SIMD
+    for name, kind, iters, peak in (("bf16_32x32x16", 0, 40000, PEAK_TFLOPS["bf16"]), ("f32_32x32x2", 1, 20000, PEAK_TFLOPS["f32"])):
+        for operands in ("constant", "random"):
+            tf, ghz = exat.probe_mfma(kind, operands == "random", iters, 256)
+            out["rates"]["%s, %s operands" % (name, operands)] = {"tflops": tf, "core_ghz": ghz, "published_peak": peak, "frac": tf / peak}
+    print(json.dumps(out))
 
 
 def cpals(args):
@@ -385,6 +404,8 @@ def main():
               "run with --gpus 1. Throughput at N GPUs is not measured.", file=sys.stderr)
         sys.exit(2)
     sys.path.insert(0, os.path.join(ROOT, "tests"))
+    if args.mfma_ceiling:
+        return mfma_ceiling(args)
     if args.two_stage:
         return two_stage(args)
     if args.cpals:
@@ -508,6 +529,11 @@ def main():
                      "frac": achieved / peak,
                      "traffic": recorded_traffic(cfg.name) if (frac == 1.0 and not split and not blocks) else None},
     }
+    # what this machine sustains when a kernel issues nothing but MFMAs of the same kind on changing operands (after the
+    # timed region; context for `frac`, which stays against the published peak)
+    tf_only, ghz_only = exat.probe_mfma(0 if (cfg.dtype == "bf16" or split) else 1, True, 40000 if (cfg.dtype == "bf16" or split) else 20000, 256)
+    out["mfma_only_on_this_box"] = {"tflops": tf_only, "core_ghz": ghz_only, "operands": "random",
+                                    "instruction": "32x32x16 bf16" if (cfg.dtype == "bf16" or split) else "32x32x2 f32"}
     if cfg.materialised:
         out["hbm_algorithmic_gbps"] = cfg.elements * (2 if cfg.dtype == "bf16" else 4) / (ms12 * 1e-3) / 1e9
     if frac != 1.0:

@@ -198,6 +198,17 @@ int exat_plan_set_timing(exat_plan_t plan, int enable);
 int exat_plan_last_timing(exat_plan_t plan, float *ms_mode12, float *ms_mode3);
 int exat_plan_timing_of(exat_plan_t plan, int32_t age, float *ms_mode12, float *ms_mode3);
 
+/* Measurement aid (not part of the paper's method): what the matrix cores of this GPU sustain when a kernel issues
+ * nothing but MFMAs -- the ceiling a compression kernel could reach at best on the box it runs on, next to the
+ * published peak its roofline fraction is quoted against.  Launches `workgroups` workgroups of eight waves (two per
+ * SIMD) that each issue iters * 64 independent MFMAs, kind 0: 32x32x16 bf16, kind 1: 32x32x2 fp32, on operands that
+ * are all 0.5 (random_operands == 0) or pseudo-random in [-1, 1) and different for consecutive MFMAs; runs the launch
+ * twice on the default stream and times the second.  tflops: the measured rate; core_ghz: the core clock during the
+ * launch (core-clock ticks over 100 MHz wall-clock ticks of one workgroup).  Blocks until done; allocates and frees
+ * two small buffers.  Errors: NULL, SHAPE, ALLOC, HIP. */
+int exat_probe_mfma(int32_t kind, int32_t random_operands, int32_t iters, int32_t workgroups, double *tflops,
+                    double *core_ghz);
+
 /* ---- Two-stage compression (Sec. 4.4) --------------------------------------------------------------
  * The paper builds the compression matrices as U_p = U'_p U, V_p = V'_p V, W_p = W'_p W with sparse
  * U (A1 x I), V (B1 x J), W (C1 x K) shared by all replicas (A1 = alpha L etc., alpha > 1), which turns

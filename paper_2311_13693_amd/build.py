@@ -15,6 +15,7 @@ UNITS = {
     "exat_stage1.hip": [],
     "exat_cpals.hip": [],
     "exat_ls.hip": [],
+    "exat_probe.hip": [],
 }
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-w",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -19,7 +19,7 @@ EXPORTS = ["exat_plan_create", "exat_plan_destroy", "exat_set_factors", "exat_co
            "exat_stage1_create", "exat_stage1_destroy", "exat_stage1_dims", "exat_stage1_apply", "exat_stage1_apply_host",
            "exat_stage1_set_timing", "exat_stage1_last_timing", "exat_cpals_workspace_floats", "exat_cpals",
            "exat_cpals_checked", "exat_cpals_noalloc",
-           "exat_ls_workspace_floats", "exat_ls", "exat_strerror"]
+           "exat_ls_workspace_floats", "exat_ls", "exat_probe_mfma", "exat_strerror"]
 
 
 class Desc(ctypes.Structure):
@@ -94,6 +94,7 @@ def lib():
         L.exat_cpals_noalloc.argtypes = [vp, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp]
         L.exat_ls_workspace_floats.argtypes = [i32, i32, i32, i32]
         L.exat_ls.argtypes = [vp, i64, i32, i32, i32, vp, i32, i32, ctypes.c_float, vp, vp, vp, vp]
+        L.exat_probe_mfma.argtypes = [i32, i32, i32, i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
         L.exat_strerror.argtypes = [ctypes.c_int]
         L.exat_strerror.restype = ctypes.c_char_p
         for name in EXPORTS[:-1]:
@@ -102,6 +103,13 @@ def lib():
         L.exat_ls_workspace_floats.restype = ctypes.c_int64
         _lib = L
     return _lib
+
+
+def probe_mfma(kind, random_operands, iters, workgroups=256):
+    """MFMA-only rate (TFLOP/s) and core clock (GHz) of this GPU; kind 0 = bf16 32x32x16, 1 = fp32 32x32x2."""
+    tf, ghz = ctypes.c_double(0.0), ctypes.c_double(0.0)
+    _check(lib().exat_probe_mfma(kind, 1 if random_operands else 0, iters, workgroups, ctypes.byref(tf), ctypes.byref(ghz)))
+    return tf.value, ghz.value
 
 
 def strerror(status):

@@ -39,3 +39,20 @@ def test_timing_ring():
     with pytest.raises(exat.ExatError):
         plan.last_timing()
     plan.close()
+
+
+def test_mfma_probe_reports_a_rate_below_the_published_peak():
+    """exat_probe_mfma (measurement aid): a short launch of each kind gives a positive rate that does not exceed the
+    published MFMA peak, and a plausible core clock; bad arguments are refused."""
+    import ctypes
+    for kind, peak in ((0, 2500.0), (1, 157.3)):
+        for rnd in (False, True):
+            tf, ghz = exat.probe_mfma(kind, rnd, 2000, 256)
+            print("  kind %d random %d: %.1f TFLOP/s at %.2f GHz" % (kind, rnd, tf, ghz), flush=True)
+            assert 0.05 * peak < tf <= 1.02 * peak
+            assert 0.5 < ghz < 3.0
+    L = exat.lib()
+    tf, ghz = ctypes.c_double(), ctypes.c_double()
+    assert L.exat_probe_mfma(2, 0, 10, 256, ctypes.byref(tf), ctypes.byref(ghz)) == exat.ERR_SHAPE
+    assert L.exat_probe_mfma(0, 0, 0, 256, ctypes.byref(tf), ctypes.byref(ghz)) == exat.ERR_SHAPE
+    assert L.exat_probe_mfma(0, 0, 10, 256, None, ctypes.byref(ghz)) == exat.ERR_NULL
