@@ -83,3 +83,27 @@ def test_compress_in_a_graph():
     eager = [Y.clone()]
     _replays_match(_capture(run), [Y], eager)
     plan.close()
+
+
+def test_block_streamed_pass_in_a_graph():
+    """A whole block-streamed pass -- a slab through exat_compress_blocks (its table entries travel in the arguments of
+    a small launch, nothing is copied from the host), single blocks through exat_compress_block, the merge of
+    exat_finalize -- recorded once the first eager pass has made the plan's allocations."""
+    I, J, K, L, M, N, P, dI, dJ, dK = 64, 256, 4, 32, 8, 6, 3, 32, 128, 2
+    gen = torch.Generator(device="cpu").manual_seed(4)
+    plan = exat.Plan(exat.make_desc(I, J, K, L, M, N, P, dI, dJ, dK, exat.EXAT_F32))
+    plan.set_factors(*(torch.randn(P * d, n, generator=gen).cuda() for d, n in ((L, I), (M, J), (N, K))))
+    blocks = {(bi, bj, bk): torch.randn(dI * dJ * dK, generator=gen).cuda() for bk in range(2) for bj in range(2) for bi in range(2)}
+    Y = plan.new_y()
+
+    def run():
+        plan.compress_blocks([blocks[(bi, bj, 0)] for bj in range(2) for bi in range(2)], 0, 2, 0, 1)   # layer 0 as a slab
+        for bj in range(2):
+            for bi in range(2):
+                plan.compress_block(blocks[(bi, bj, 1)], bi, bj, 1)                                      # layer 1 block by block
+        plan.finalize(Y)
+    run()                         # the allocating pass
+    torch.cuda.synchronize()
+    eager = [Y.clone()]
+    _replays_match(_capture(run), [Y], eager)
+    plan.close()
