@@ -19,7 +19,8 @@
  *   - Y is fp32, column-major per replica, replicas outermost:
  *     Y[l + L*(m + M*(n + N*p))].
  *   - `stream` is a borrowed hipStream_t (NULL = default stream).  All work is
- *     enqueued asynchronously on it; no call synchronises the device.
+ *     enqueued asynchronously on it; no call synchronises the device (the
+ *     measurement aids that wait for their own events say so).
  *   - The caller owns every buffer it passes.  A plan owns only its workspace
  *     (packed operand copies, the mode-2 intermediate, block partials).
  *   - Every function returns EXAT_OK (0) or a negative exat_status_t; nothing is
