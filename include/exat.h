@@ -148,9 +148,9 @@ int exat_compress_block(exat_plan_t plan, const void *Xblk, int32_t bi, int32_t 
  * over the slab's j range before mode 3, so every mode is applied once per element (a lone block repeats modes 2
  * and 3) and one launch fills the chip.  The slab leaves one partial result, which exat_finalize merges with those
  * of the other slabs and single blocks of the pass in a fixed order: Y does not depend on the order of the calls,
- * only on how the blocks were grouped into slabs (rounding).  Requirements of the one-launch form: EXAT_F32 or
- * EXAT_BF16, dI a multiple of 16 (bf16: 32) that divides I, dJ a multiple of 128, 16-byte aligned blocks; any
- * other slab is compressed block by block, as by exat_compress_block.  Allocates on its first use with a plan (the block
+ * only on how the blocks were grouped into slabs (rounding).  Requirements of the one-launch form: dI a
+ * multiple of 16 (EXAT_BF16 and EXAT_F32_SPLIT: 32) that divides I, dJ a multiple of 128, 16-byte aligned
+ * blocks; any other slab is compressed block by block, as by exat_compress_block.  Allocates on its first use with a plan (the block
  * partials and a table of one pointer per block).
  * Errors: NULL, STATE (factors not set, a block of the slab submitted twice), SHAPE, ALLOC, HIP. */
 int exat_compress_blocks(exat_plan_t plan, const void *const *Xblk, int32_t bj0, int32_t bj1, int32_t bk0,

@@ -246,11 +246,11 @@ int launch_v4_gen_bf16(const Mode12Params &mp, const GenSplitParams &gs, const U
 }
 
 // fp32 data on the fp16 matrix cores (two-piece split), materialised source, 4 waves x RT row tiles
-template <int RT>
+template <int RT, bool TAB = false>
 int launch_split(const Mode12Params &mp, const SplitParams &sp, int nk, hipStream_t st)
 {
     typedef Mode12SplitCfg<4, RT> cfg;
-    auto kern = k_mode12_split<4, RT, 2, 4>;
+    auto kern = k_mode12_split<4, RT, 2, 4, TAB>;
     static bool attr_done = false;
     if (!attr_done) {
         if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, cfg::LDS_BYTES) != hipSuccess) return EXAT_ERR_HIP;
@@ -273,7 +273,8 @@ int run_chain(exat_plan_s *pl, Mode12Params mp, bool generated, float *Yout, int
     bool pipelined = env_int("EXAT_PIPELINED", 1) != 0;
     if (generated) pipelined = pipelined && mp.R <= 64;
     else pipelined = pipelined && mp.x_vec && (mp.i0 % ei == 0) && ((mp.i1 - mp.i0) % ei == 0);
-    if (mp.xtab && (!pipelined || generated || pl->d.in_dtype == EXAT_F32_SPLIT)) return EXAT_ERR_STATE;   // only k_mode12_v3<..., TAB> reads the block table
+    // only k_mode12_v3<..., TAB> and k_mode12_split<..., TAB> read the block table
+    if (mp.xtab && (generated || (pl->d.in_dtype == EXAT_F32_SPLIT ? (mp.i0 % 32 != 0 || (mp.i1 - mp.i0) % 32 != 0) : !pipelined))) return EXAT_ERR_STATE;
     int rt = choose_rt(pl, generated);
     if (pipelined) {
         // rt = 128-row units of the workgroup tile: 2 = 4 waves x 2 row tiles, 3 = 4 waves x 3, 4 = 8 waves x 2
@@ -320,10 +321,10 @@ int run_chain(exat_plan_s *pl, Mode12Params mp, bool generated, float *Yout, int
         // remainder of at most 128 rows gets a launch of its own with one row tile per wave
         const int full = pl->PL / 256, rem = pl->PL - 256 * full;
         rc = EXAT_OK;
-        if (full > 0 || rem > 128) { mp.G = rem > 128 ? full + 1 : full; rc = launch_split<2>(mp, sp, nk, st); }
+        if (full > 0 || rem > 128) { mp.G = rem > 128 ? full + 1 : full; rc = mp.xtab ? launch_split<2, true>(mp, sp, nk, st) : launch_split<2>(mp, sp, nk, st); }
         if (rc == EXAT_OK && rem > 0 && rem <= 128) {
             mp.row_base = 256 * full; mp.G = 1;
-            rc = launch_split<1>(mp, sp, nk, st);
+            rc = mp.xtab ? launch_split<1, true>(mp, sp, nk, st) : launch_split<1>(mp, sp, nk, st);
         }
     } else if (pipelined) {
         const bool boxed = generated && (mp.i0 != 0 || mp.i1 != pl->d.I);
@@ -628,12 +629,12 @@ int exat_compress_blocks(exat_plan_t pl, const void *const *Xblk, int32_t bj0, i
         for (int64_t bj = bj0; bj < bj1; bj++)
             for (int64_t bi = 0; bi < nbi; bi++)
                 if (pl->submitted[(size_t)(bi + nbi * (bj + nbj * bk))]) return EXAT_ERR_STATE;
-    // One launch over the slab needs the kernels that read X through a table of block pointers: fp32 or bf16 plans,
-    // whole stages of i (16 fp32 / 32 bf16 values) and whole 128-fibre chunks inside every block, 16-byte aligned
-    // blocks.  Any other slab is compressed block by block.
-    const int ei = d.in_dtype == EXAT_BF16 ? 32 : 16;
-    bool one_launch = (d.in_dtype == EXAT_F32 || d.in_dtype == EXAT_BF16) && d.I % d.dI == 0 && d.dI % ei == 0 && d.dJ % 128 == 0 &&
-                      env_int("EXAT_PIPELINED", 1) != 0 && env_int("EXAT_SLAB", 1) != 0;
+    // One launch over the slab needs the kernels that read X through a table of block pointers: whole stages of i
+    // (16 values for fp32 plans, 32 for bf16 and split-fp16 plans) and whole 128-fibre chunks inside every block,
+    // 16-byte aligned blocks.  Any other slab is compressed block by block.
+    const int ei = d.in_dtype == EXAT_F32 ? 16 : 32;
+    bool one_launch = d.I % d.dI == 0 && d.dI % ei == 0 && d.dJ % 128 == 0 &&
+                      (d.in_dtype == EXAT_F32_SPLIT || env_int("EXAT_PIPELINED", 1) != 0) && env_int("EXAT_SLAB", 1) != 0;
     for (int64_t q = 0; q < n && one_launch; q++)
         if ((uintptr_t)Xblk[q] & 15) one_launch = false;
     if (!one_launch) {

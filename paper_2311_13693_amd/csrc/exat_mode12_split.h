@@ -35,7 +35,8 @@ struct Mode12SplitCfg {
 };
 
 // DU: register sets of U fragments, DX: register sets of the X tile (as in k_mode12_v3)
-template <int NW, int RT, int DU, int DX>
+// TAB: X is a slab of separate blocks addressed through Mode12Params::xtab, as in k_mode12_v3.
+template <int NW, int RT, int DU, int DX, bool TAB = false>
 __global__ __launch_bounds__(64 * NW) void k_mode12_split(const Mode12Params p, const SplitParams sp)
 {
     typedef Mode12SplitCfg<NW, RT> cfg;
@@ -82,11 +83,25 @@ __global__ __launch_bounds__(64 * NW) void k_mode12_split(const Mode12Params p, 
                 for (int e = 0; e < 16; e++) acc[rt][ct][e] = 0.0f;
         int64_t x_off[XPT];
         bool x_ok[XPT];
+        const void *const *tabrow = nullptr;   // TAB: the block pointers of this chunk's column, indexed by bi
+        if constexpr (TAB) {
+            // the chunk lies inside block column (bj, bk): offsets are relative to the start of a block of that column
+            const int64_t bj = jc / p.x_dJ, bk = k / p.x_dK;
+            const int64_t jb0 = bj * p.x_dJ, djb = (p.j1 - jb0 < p.x_dJ) ? p.j1 - jb0 : p.x_dJ;
+            tabrow = p.xtab + (bk * p.tab_nbj + bj) * p.tab_nbi;
 #pragma unroll
-        for (int u = 0; u < XPT; u++) {
-            const int64_t j = jc + pr0 + PCOLS * u;
-            x_ok[u] = (j >= p.j0) && (j < p.j1);
-            x_off[u] = (pf * 8 - p.xo_i) + (j - p.xo_j) * p.x_sj + (k - p.xo_k) * p.x_sk;
+            for (int u = 0; u < XPT; u++) {
+                const int64_t j = jc + pr0 + PCOLS * u;
+                x_ok[u] = (j >= p.j0) && (j < p.j1);
+                x_off[u] = pf * 8 + (j - jb0) * p.x_dI + (k - bk * p.x_dK) * p.x_dI * djb;
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < XPT; u++) {
+                const int64_t j = jc + pr0 + PCOLS * u;
+                x_ok[u] = (j >= p.j0) && (j < p.j1);
+                x_off[u] = (pf * 8 - p.xo_i) + (j - p.xo_j) * p.x_sj + (k - p.xo_k) * p.x_sk;
+            }
         }
 
         auto stage_i = [&](int s) -> int64_t { return ia0 + (int64_t)(s < nstage ? s : nstage - 1) * EI; };
@@ -95,18 +110,32 @@ __global__ __launch_bounds__(64 * NW) void k_mode12_split(const Mode12Params p, 
             uh[d][rt][g2] = *(const f16x8 *)(ufh + o);
             ul[d][rt][g2] = *(const f16x8 *)(ufl + o);
         };
+        // TAB: start of stage s inside its block; the pointer is read from the table a whole stage before the loads
+        // that use it are issued (the calls of load_x come in the order of the stages, from stage 0)
+        auto gptr = [](const float *q) { return (const __attribute__((address_space(1))) f32x4 *)(uintptr_t)q; };
+        const float *tab_next = nullptr;
+        auto tab_fetch = [&](int s) {
+            if constexpr (TAB) {
+                const int ii = (int)stage_i(s), bi = ii / (int)p.x_dI;
+                tab_next = (const float *)tabrow[bi] + (ii - bi * (int)p.x_dI);
+            }
+        };
+        tab_fetch(0);
         auto load_x = [&](int s, f32x4 *slot) {
-            const float *xb = (const float *)p.X + stage_i(s);
+            const float *xb;
+            if constexpr (TAB) xb = tab_next;
+            else xb = (const float *)p.X + stage_i(s);
 #pragma unroll
             for (int u = 0; u < XPT; u++) {
                 f32x4 v0 = {0.0f, 0.0f, 0.0f, 0.0f}, v1 = v0;
                 if (x_ok[u]) {
-                    v0 = *(const f32x4 *)(xb + x_off[u]);
-                    v1 = *(const f32x4 *)(xb + x_off[u] + 4);
+                    v0 = *gptr(xb + x_off[u]);
+                    v1 = *gptr(xb + x_off[u] + 4);
                 }
                 slot[2 * u] = v0;
                 slot[2 * u + 1] = v1;
             }
+            tab_fetch(s + 1);
         };
         // splits the tile pieces held in `slot` and writes the two fp16 tiles of a stage into LDS at `base`
         auto commit = [&](const f32x4 *slot, unsigned char *base) {

@@ -61,6 +61,7 @@ CASES = {
     "two_row_groups_l64": dict(I=48, J=128, K=5, R=5, P=10, L=64, M=20, N=3, dI=16, dJ=128, dK=2),
     "l50_mode2_through_lds": dict(I=64, J=200, K=5, R=4, P=7, L=50, M=50, N=6, dI=16, dJ=128, dK=3),
     "forty_eight_blocks": dict(I=64, J=384, K=4, R=3, P=2, L=32, M=6, N=4, dI=16, dJ=128, dK=1),   # two launches fill the pointer table
+    "split_fp16": dict(I=128, J=300, K=5, R=4, P=9, L=32, M=20, N=6, dI=32, dJ=128, dK=2, dtype="f32s"),   # 288 rows: a remainder launch too
     "bf16": dict(I=128, J=300, K=5, R=4, P=7, L=50, M=50, N=6, dI=64, dJ=128, dK=2, dtype="bf16"),
 }
 
