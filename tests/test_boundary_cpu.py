@@ -126,3 +126,13 @@ def test_timing_argument_errors():
     f = ctypes.c_float()
     assert L.exat_plan_timing_of(None, 0, ctypes.byref(f), ctypes.byref(f)) == exat.ERR_NULL
     assert L.exat_plan_last_timing(None, ctypes.byref(f), ctypes.byref(f)) == exat.ERR_NULL
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU only: any other --gpus value exits with status 2 and says why, before touching a device."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    res = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert res.returncode == 2
+    assert "ONE GPU" in res.stderr and res.stdout.strip() == ""
